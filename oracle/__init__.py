@@ -1,0 +1,206 @@
+"""ctypes front end of the fp64 CPU oracle (``paro_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY.  Importers allowed: ``tests/``, the smoke check and
+the CPU-baseline leg of the benchmark.  The GPU package never imports this.
+
+Arrays are numpy, host memory.  fp16 tensors travel as their uint16 bit
+patterns (``arr.view(np.uint16)``), so no float conversion happens outside the
+C file's own hand-written converters.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "paro_oracle.c")
+_LIB = os.path.join(_HERE, "libparo_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP over tokens / output rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.oracle_fp16_to_f64.restype = ctypes.c_double
+        L.oracle_fp16_to_f64.argtypes = [ctypes.c_uint16]
+        L.oracle_f64_to_fp16.restype = ctypes.c_uint16
+        L.oracle_f64_to_fp16.argtypes = [ctypes.c_double]
+        L.oracle_rotate_scale.restype = ctypes.c_int
+        L.oracle_rotate_inplace.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == dtype, (a.dtype, dtype)
+    return a
+
+
+def _bits(a):
+    """fp16 array -> contiguous uint16 view (bit patterns)."""
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        return a.view(np.uint16)
+    assert a.dtype == np.uint16
+    return a
+
+
+def threads() -> int:
+    """Threads the OpenMP loops will use (all cores this process may run on)."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    n = len(os.sched_getaffinity(0))
+    return min(n, int(env)) if env and env.isdigit() else n
+
+
+def fp16_to_f64(bits: np.ndarray) -> np.ndarray:
+    b = _bits(bits)
+    out = np.empty(b.shape, dtype=np.float64)
+    lib().oracle_widen_fp16(_p(b, ctypes.c_uint16), ctypes.c_int64(b.size), _p(out, ctypes.c_double))
+    return out
+
+
+def round_fp16(v: np.ndarray) -> np.ndarray:
+    """fp64 -> fp16 round-to-nearest-even (the oracle's own converter); returns float16."""
+    v = _c(v, np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    lib().oracle_round_fp16(_p(v, ctypes.c_double), ctypes.c_int64(v.size), _p(out, ctypes.c_uint16))
+    return out.view(np.float16)
+
+
+def rotate_scale(x16, pairs, theta, ch_scale16=None, group=128, scale_order=0, n_layers=None) -> np.ndarray:
+    """u = R_K ... R_1 . S . x per token and group, fp64 [T][C]  (Eq. 4, 5, 8).
+
+    ``n_layers`` < K applies only the first layers (used by the per-layer pins).
+    """
+    xb = _bits(x16)
+    T, C = xb.shape
+    pairs = _c(pairs, np.int16)
+    theta = _c(theta, np.float32)
+    G, K, P, two = pairs.shape
+    assert two == 2 and G * group == C and theta.shape == (G, K, P)
+    if n_layers is not None and n_layers != K:
+        pairs = np.ascontiguousarray(pairs[:, :n_layers])
+        theta = np.ascontiguousarray(theta[:, :n_layers])
+        K = n_layers
+    sb = _bits(ch_scale16)
+    u = np.empty((T, C), dtype=np.float64)
+    rc = lib().oracle_rotate_scale(_p(xb, ctypes.c_uint16), ctypes.c_int64(C), ctypes.c_int32(T), ctypes.c_int32(C),
+                                   ctypes.c_int32(group), ctypes.c_int32(K), ctypes.c_int32(P),
+                                   _p(pairs, ctypes.c_int16), _p(theta, ctypes.c_float),
+                                   _p(sb, ctypes.c_uint16), ctypes.c_int32(scale_order),
+                                   _p(u, ctypes.c_double), ctypes.c_int64(C))
+    if rc != 0:
+        raise ValueError("pair index out of range")
+    return u
+
+
+def rotate_inplace(u, pairs, theta, group=128) -> np.ndarray:
+    """Apply the rotation layers alone to fp64 rows (returns a new array)."""
+    u = np.array(u, dtype=np.float64, order="C", copy=True)
+    T, C = u.shape
+    pairs = _c(pairs, np.int16)
+    theta = _c(theta, np.float32)
+    G, K, P, two = pairs.shape
+    assert two == 2 and G * group == C and theta.shape == (G, K, P)
+    rc = lib().oracle_rotate_inplace(_p(u, ctypes.c_double), ctypes.c_int64(C), ctypes.c_int32(T), ctypes.c_int32(C),
+                                     ctypes.c_int32(group), ctypes.c_int32(K), ctypes.c_int32(P),
+                                     _p(pairs, ctypes.c_int16), _p(theta, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("pair index out of range")
+    return u
+
+
+def unpack_codes(qweight: np.ndarray) -> np.ndarray:
+    q = _c(qweight, np.uint32)
+    N, C8 = q.shape
+    out = np.empty((N, C8 * 8), dtype=np.uint8)
+    lib().oracle_unpack_codes(_p(q, ctypes.c_uint32), ctypes.c_int32(N), ctypes.c_int32(C8 * 8), _p(out, ctypes.c_uint8))
+    return out
+
+
+def unpack_zeros(qzeros: np.ndarray) -> np.ndarray:
+    q = _c(qzeros, np.uint32)
+    G, N8 = q.shape
+    out = np.empty((G, N8 * 8), dtype=np.uint8)
+    lib().oracle_unpack_zeros(_p(q, ctypes.c_uint32), ctypes.c_int32(G), ctypes.c_int32(N8 * 8), _p(out, ctypes.c_uint8))
+    return out
+
+
+def _wargs(qweight, scales16, qzeros, group):
+    q = _c(qweight, np.uint32)
+    s = _bits(scales16)
+    z = _c(qzeros, np.uint32)
+    N, C8 = q.shape
+    C = C8 * 8
+    assert s.shape == (C // group, N) and z.shape == (C // group, N // 8)
+    return q, s, z, N, C
+
+
+def dequant(qweight, scales16, qzeros, group=128) -> np.ndarray:
+    """W^[n][c] = (q - z) * s in fp64 (Eq. 1 inverted, per-group s and z)."""
+    q, s, z, N, C = _wargs(qweight, scales16, qzeros, group)
+    W = np.empty((N, C), dtype=np.float64)
+    lib().oracle_dequant(_p(q, ctypes.c_uint32), _p(s, ctypes.c_uint16), _p(z, ctypes.c_uint32),
+                         ctypes.c_int32(N), ctypes.c_int32(C), ctypes.c_int32(group), _p(W, ctypes.c_double))
+    return W
+
+
+def row_sqnorms(qweight, scales16, qzeros, group=128) -> np.ndarray:
+    q, s, z, N, C = _wargs(qweight, scales16, qzeros, group)
+    out = np.empty(N, dtype=np.float64)
+    lib().oracle_row_sqnorms(_p(q, ctypes.c_uint32), _p(s, ctypes.c_uint16), _p(z, ctypes.c_uint32),
+                             ctypes.c_int32(N), ctypes.c_int32(C), ctypes.c_int32(group), _p(out, ctypes.c_double))
+    return out
+
+
+def linear(u, qweight, scales16, qzeros, bias16=None, group=128) -> np.ndarray:
+    """y[t][n] = sum_c W^[n][c] u[t][c] (+ b[n]) in fp64 (Eq. 2)."""
+    u = _c(u, np.float64)
+    q, s, z, N, C = _wargs(qweight, scales16, qzeros, group)
+    T = u.shape[0]
+    assert u.shape == (T, C)
+    b = _bits(bias16)
+    y = np.empty((T, N), dtype=np.float64)
+    lib().oracle_linear(_p(u, ctypes.c_double), ctypes.c_int64(C), ctypes.c_int32(T),
+                        _p(q, ctypes.c_uint32), _p(s, ctypes.c_uint16), _p(z, ctypes.c_uint32), _p(b, ctypes.c_uint16),
+                        ctypes.c_int32(N), ctypes.c_int32(C), ctypes.c_int32(group),
+                        _p(y, ctypes.c_double), ctypes.c_int64(N))
+    return y
+
+
+def linear_samples(u, qweight, scales16, qzeros, t_idx, n_idx, bias16=None, group=128):
+    """(y[s], ||w_row(n_s)||^2) for sampled (t_s, n_s), each computed on its own."""
+    u = _c(u, np.float64)
+    q, s, z, N, C = _wargs(qweight, scales16, qzeros, group)
+    t_idx = _c(np.asarray(t_idx, dtype=np.int32), np.int32)
+    n_idx = _c(np.asarray(n_idx, dtype=np.int32), np.int32)
+    assert t_idx.shape == n_idx.shape and u.shape[1] == C
+    b = _bits(bias16)
+    y = np.empty(t_idx.shape, dtype=np.float64)
+    ww = np.empty(t_idx.shape, dtype=np.float64)
+    lib().oracle_linear_samples(_p(u, ctypes.c_double), ctypes.c_int64(C),
+                                _p(q, ctypes.c_uint32), _p(s, ctypes.c_uint16), _p(z, ctypes.c_uint32),
+                                _p(b, ctypes.c_uint16), ctypes.c_int32(N), ctypes.c_int32(C), ctypes.c_int32(group),
+                                _p(t_idx, ctypes.c_int32), _p(n_idx, ctypes.c_int32), ctypes.c_int64(t_idx.size),
+                                _p(y, ctypes.c_double), _p(ww, ctypes.c_double))
+    return y, ww
