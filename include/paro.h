@@ -1,0 +1,156 @@
+/*
+ * paro.h - C ABI of libparo: the runtime hot path of Pairwise Rotation
+ * Quantization (arXiv 2511.10645) on AMD MI355X (gfx950).
+ *
+ * What the calls compute (column-vector form of Eq. 2 with the transform of Eq. 8):
+ *
+ *      y = W^ . ( R_K ... R_1 . S . x ) + b
+ *
+ *   S      = diag(ch_scale): per-channel scaling seen by the activations
+ *            (Section 4.1.4; the reciprocal of the alpha that multiplies the weights)
+ *   R_t    = one "independent rotation" (Def. 2): disjoint channel pairs inside each
+ *            group of `group` channels, pair (i, j, theta) updates
+ *                 u_i <- cos(theta) u_i - sin(theta) u_j
+ *                 u_j <- sin(theta) u_i + cos(theta) u_j            (Eq. 4, Eq. 5)
+ *            layers are applied in array order, layer 0 first
+ *   W^     = INT4 group-quantised weight, W^[n,c] = (q[n,c] - z[c/group,n]) * s[c/group,n]
+ *            (Eq. 1 read backwards; one s and z per `group` consecutive input channels
+ *            of an output column, Section 2.1)
+ *
+ * Conventions
+ *   - Every pointer inside the structs and every X / Y / workspace / blob argument is a
+ *     DEVICE pointer unless its name ends in _host.  The caller owns all memory; the
+ *     library never allocates, frees or keeps device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; they never synchronise.
+ *   - fp16 data is IEEE binary16, declared here as uint16_t bit patterns (paro_half_t).
+ *   - Argument errors are detected on the host before anything is launched, so a call
+ *     that returns an error has had no effect on the device.
+ *   - group must be 128, n_layers <= 8, pairs_per_layer <= 64 (Section 5, "Implementation").
+ */
+#ifndef PARO_H
+#define PARO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t paro_half_t;
+
+typedef enum {
+    PARO_OK = 0,
+    PARO_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    PARO_ERR_SHAPE = 2,       /* sizes inconsistent (c_in % group, ld < width, T <= 0, ...)   */
+    PARO_ERR_ALIGN = 3,       /* a pointer or row stride is not aligned as documented         */
+    PARO_ERR_PAIRS = 4,       /* pairs of one layer are not disjoint / index out of range     */
+    PARO_ERR_UNSUPPORTED = 5, /* group != 128, n_layers > 8, pairs_per_layer > 64, ...        */
+    PARO_ERR_WORKSPACE = 6,   /* workspace missing or smaller than paro_workspace_bytes()     */
+    PARO_ERR_HIP = 7          /* the HIP runtime reported an error at launch                  */
+} paro_status;
+
+/* The online transform of one linear layer's input (Section 4.1; Eq. 5, Eq. 8). */
+typedef struct {
+    int32_t c_in;             /* channels of X, multiple of group                             */
+    int32_t group;            /* channel-group size g (= quantisation group), 128             */
+    int32_t n_layers;         /* K, 0..8                                                       */
+    int32_t pairs_per_layer;  /* slots per layer and group, 1..64                              */
+    const int16_t *pairs;     /* [c_in/group][n_layers][pairs_per_layer][2]; 0-based indices
+                                 LOCAL to the group; i == j marks an empty slot; within one
+                                 layer and group no channel may appear twice (Def. 1)          */
+    const float *theta;       /* [c_in/group][n_layers][pairs_per_layer], radians              */
+    const paro_half_t *ch_scale; /* [c_in] multiplier applied to x; NULL = all ones            */
+    int32_t scale_order;      /* 0: scale, then rotate (Eq. 8 inverted; default)
+                                 1: rotate, then scale                                         */
+    const void *plan;         /* blob written by paro_rotation_plan_build(); NULL selects the
+                                 slower kernel that reads pairs/theta directly                 */
+} paro_rotation;
+
+/* An INT4 group-quantised weight (Eq. 1, Section 2.1), interchange layout. */
+typedef struct {
+    int32_t c_in;             /* multiple of group                                             */
+    int32_t c_out;            /* multiple of 16                                                */
+    int32_t group;            /* 128                                                           */
+    const uint32_t *qweight;  /* [c_out][c_in/8]; bits 4k..4k+3 of word w of row n hold the
+                                 code q[n, 8w+k]                                               */
+    const paro_half_t *scales;/* [c_in/group][c_out]                                           */
+    const uint32_t *qzeros;   /* [c_in/group][c_out/8]; bits 4k..4k+3 of word w hold z[g, 8w+k]*/
+    const paro_half_t *bias;  /* optional [c_out], added in fp32 before the fp16 store         */
+    const void *packed;       /* blob written by paro_w4_repack(); NULL selects the slower
+                                 kernels that read the interchange layout                      */
+} paro_w4_weight;
+
+int paro_version(void);
+const char *paro_status_string(paro_status s);
+
+/* Def. 1 on a HOST copy of the pair table: every index in [0, group) and no channel twice
+ * within a (group, layer).  Device kernels assume a table that passed this check.
+ * Returns PARO_OK, PARO_ERR_PAIRS, PARO_ERR_NULL, PARO_ERR_SHAPE. */
+paro_status paro_validate_pairs_host(const int16_t *pairs_host, int32_t n_groups, int32_t n_layers,
+                                     int32_t pairs_per_layer, int32_t group);
+
+/* One-time preparation (model-load side) ------------------------------------------------ */
+
+/* Size in bytes of the rotation plan for `rot` (0 on invalid arguments). */
+size_t paro_rotation_plan_bytes(const paro_rotation *rot);
+/* Builds the plan on the device: per group and layer, the lane routing, fp32 cos/sin
+ * (rounded from an fp64 evaluation) and the folded channel scales used by the fast
+ * rotation kernels.  plan_out: device buffer of paro_rotation_plan_bytes(), 256-byte
+ * aligned.  rot->plan is ignored. */
+paro_status paro_rotation_plan_build(const paro_rotation *rot, void *plan_out, void *stream);
+
+/* Size in bytes of the kernel-private weight blob for `w` (0 on invalid arguments). */
+size_t paro_w4_repack_bytes(const paro_w4_weight *w);
+/* Rewrites qweight / scales / qzeros into the tiled layout the fast kernels stream
+ * (a pure permutation of the same bits: paro_w4_unpack_codes() on the repacked weight
+ * returns the same codes).  packed_out: device buffer, 256-byte aligned. */
+paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stream);
+
+/* Hot path ------------------------------------------------------------------------------- */
+
+/* Bytes of workspace the two linear calls need for T tokens (rot may be NULL for the bare
+ * linear).  The workspace must be zero-filled ONCE after allocation; every call leaves it
+ * zero-filled again.  Two calls that share a workspace must not overlap in time. */
+size_t paro_workspace_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T);
+
+/* Xr[t, :] = R_K ... R_1 . S . X[t, :] for t < T, fp32 arithmetic, one fp16 rounding at the
+ * store (Eq. 5, Eq. 8).  X, Xr: fp16 [T][ld*], ld >= c_in, rows 4-byte aligned (ld even).
+ * Xr == X (in place, same ld) is allowed; other overlaps are not. */
+paro_status paro_rotate_scale(const paro_rotation *rot, const paro_half_t *X, int64_t ldx,
+                              paro_half_t *Xr, int64_t ldxr, int32_t T, void *stream);
+
+/* Y[t, n] = sum_c W^[n, c] X[t, c] (+ bias[n]), fp32 accumulation, fp16 store (Eq. 2 with
+ * T = identity).  X: fp16 [T][ldx], Y: fp16 [T][ldy]; ldx >= c_in, ldy >= c_out, both
+ * multiples of 8 (16-byte rows).  ws/ws_bytes: see paro_workspace_bytes(). */
+paro_status paro_w4a16_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ldx,
+                              paro_half_t *Y, int64_t ldy, int32_t T,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Y = W^ . (R_K ... R_1 . S . X) (+ bias): the transform fused in front of the linear
+ * (Eq. 2).  rot->c_in must equal w->c_in.  Same layouts as the two calls above. */
+paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *w,
+                                const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                                int32_t T, void *ws, size_t ws_bytes, void *stream);
+
+/* Test hooks for the bit-exact gate --------------------------------------------------- */
+
+/* codes[n][c] = q[n, c] as bytes 0..15 (from w->packed if set, else from w->qweight). */
+paro_status paro_w4_unpack_codes(const paro_w4_weight *w, uint8_t *codes, void *stream);
+/* zeros[g][n] = z[g, n] as bytes 0..15. */
+paro_status paro_w4_unpack_zeros(const paro_w4_weight *w, uint8_t *zeros, void *stream);
+/* W[n][c] = fp16( (q - z) * s ), exact product rounded once to nearest-even. */
+paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *stream);
+
+/* Diagnostics ---------------------------------------------------------------------------- */
+
+/* Tuning knob for experiments: target number of workgroups of a decode launch (<= 0 restores
+ * the default).  Process-wide and not thread-safe; results do not depend on it beyond fp32
+ * summation order. */
+void paro_tune_decode_blocks(int blocks);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARO_H */

@@ -1,0 +1,27 @@
+"""MI355X-native runtime hot path of Pairwise Rotation Quantization (arXiv 2511.10645).
+
+Thin Python binding over the C ABI of ``libparo.so`` (``include/paro.h``): argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; PyTorch is used
+for device memory and streams.  There is no CPU fallback: a missing library is an error.
+"""
+from .binding import (  # noqa: F401
+    ParoError,
+    Rotation,
+    W4Weight,
+    lib,
+    lib_path,
+    paro_rotate_scale,
+    paro_rotated_linear,
+    paro_rotation_plan_build,
+    paro_status_string,
+    paro_tune_decode_blocks,
+    paro_validate_pairs_host,
+    paro_version,
+    paro_w4_dequant,
+    paro_w4_repack,
+    paro_w4_unpack_codes,
+    paro_w4_unpack_zeros,
+    paro_w4a16_linear,
+    paro_workspace_bytes,
+    Workspace,
+)

@@ -1,0 +1,247 @@
+"""ctypes binding of libparo.so.  Names follow include/paro.h one to one."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libparo.so")
+_lib = None
+
+PARO_OK = 0
+
+
+class ParoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({paro_status_string(status)})")
+
+
+class _CRotation(ctypes.Structure):
+    _fields_ = [
+        ("c_in", ctypes.c_int32), ("group", ctypes.c_int32), ("n_layers", ctypes.c_int32),
+        ("pairs_per_layer", ctypes.c_int32),
+        ("pairs", ctypes.c_void_p), ("theta", ctypes.c_void_p), ("ch_scale", ctypes.c_void_p),
+        ("scale_order", ctypes.c_int32), ("plan", ctypes.c_void_p),
+    ]
+
+
+class _CW4Weight(ctypes.Structure):
+    _fields_ = [
+        ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32), ("group", ctypes.c_int32),
+        ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("qzeros", ctypes.c_void_p),
+        ("bias", ctypes.c_void_p), ("packed", ctypes.c_void_p),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Load libparo.so, building it first only if nothing has been built yet."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        rp, wp = ctypes.POINTER(_CRotation), ctypes.POINTER(_CW4Weight)
+        L.paro_version.restype = ctypes.c_int
+        L.paro_status_string.restype = ctypes.c_char_p
+        L.paro_status_string.argtypes = [ctypes.c_int]
+        L.paro_validate_pairs_host.argtypes = [vp, i32, i32, i32, i32]
+        L.paro_rotation_plan_bytes.restype = sz
+        L.paro_rotation_plan_bytes.argtypes = [rp]
+        L.paro_rotation_plan_build.argtypes = [rp, vp, vp]
+        L.paro_w4_repack_bytes.restype = sz
+        L.paro_w4_repack_bytes.argtypes = [wp]
+        L.paro_w4_repack.argtypes = [wp, vp, vp]
+        L.paro_workspace_bytes.restype = sz
+        L.paro_workspace_bytes.argtypes = [rp, wp, i32]
+        L.paro_rotate_scale.argtypes = [rp, vp, i64, vp, i64, i32, vp]
+        L.paro_w4a16_linear.argtypes = [wp, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.paro_rotated_linear.argtypes = [rp, wp, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.paro_w4_unpack_codes.argtypes = [wp, vp, vp]
+        L.paro_w4_unpack_zeros.argtypes = [wp, vp, vp]
+        L.paro_w4_dequant.argtypes = [wp, vp, vp]
+        L.paro_tune_decode_blocks.argtypes = [ctypes.c_int]
+        L.paro_tune_decode_blocks.restype = None
+        for name in ("paro_validate_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
+                     "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
+                     "paro_w4_dequant"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(st: int, where: str):
+    if st != PARO_OK:
+        raise ParoError(st, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def paro_version() -> int:
+    return lib().paro_version()
+
+
+def paro_status_string(status: int) -> str:
+    return lib().paro_status_string(int(status)).decode()
+
+
+def paro_validate_pairs_host(pairs: np.ndarray, group: int = 128) -> int:
+    """Def. 1 on a host (numpy int16) pair table [G][K][P][2]; returns the status code."""
+    p = np.ascontiguousarray(pairs, dtype=np.int16)
+    G, K, P, two = p.shape
+    assert two == 2
+    return lib().paro_validate_pairs_host(p.ctypes.data, G, K, P, group)
+
+
+def paro_tune_decode_blocks(blocks: int) -> None:
+    lib().paro_tune_decode_blocks(int(blocks))
+
+
+class Rotation:
+    """Device-side description of one linear's input transform (struct paro_rotation)."""
+
+    def __init__(self, pairs, theta, ch_scale=None, scale_order: int = 0, group: int = 128, device="cuda"):
+        self.pairs = torch.as_tensor(np.ascontiguousarray(pairs, dtype=np.int16)).to(device)
+        self.theta = torch.as_tensor(np.ascontiguousarray(theta, dtype=np.float32)).to(device)
+        G, K, P, _ = self.pairs.shape
+        self.c_in = G * group
+        self.ch_scale = None
+        if ch_scale is not None:
+            cs = np.ascontiguousarray(ch_scale)
+            assert cs.dtype == np.float16 and cs.shape == (self.c_in,)
+            self.ch_scale = torch.as_tensor(cs).to(device)
+        self.plan = None
+        self.c = _CRotation(self.c_in, group, K, P, _ptr(self.pairs), _ptr(self.theta), _ptr(self.ch_scale),
+                            scale_order, None)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+class W4Weight:
+    """Device-side INT4 group-quantised weight (struct paro_w4_weight)."""
+
+    def __init__(self, qweight, scales, qzeros, bias=None, group: int = 128, device="cuda"):
+        qw = np.ascontiguousarray(qweight, dtype=np.uint32)
+        self.c_out, c8 = qw.shape
+        self.c_in = c8 * 8
+        sc = np.ascontiguousarray(scales)
+        qz = np.ascontiguousarray(qzeros, dtype=np.uint32)
+        assert sc.dtype == np.float16 and sc.shape == (self.c_in // group, self.c_out)
+        assert qz.shape == (self.c_in // group, self.c_out // 8)
+        self.qweight = torch.as_tensor(qw.view(np.int32)).to(device)
+        self.scales = torch.as_tensor(sc).to(device)
+        self.qzeros = torch.as_tensor(qz.view(np.int32)).to(device)
+        self.bias = None if bias is None else torch.as_tensor(np.ascontiguousarray(bias, dtype=np.float16)).to(device)
+        self.packed = None
+        self.c = _CW4Weight(self.c_in, self.c_out, group, _ptr(self.qweight), _ptr(self.scales), _ptr(self.qzeros),
+                            _ptr(self.bias), None)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+    def drop_interchange(self):
+        """Keep only the repacked blob (frees the interchange copies)."""
+        assert self.packed is not None
+        self.qweight = self.scales = self.qzeros = None
+        self.c.qweight = self.c.scales = self.c.qzeros = None
+
+
+class Workspace:
+    """Zero-filled device scratch for the linear calls (see paro_workspace_bytes)."""
+
+    def __init__(self, nbytes: int, device="cuda"):
+        self.nbytes = int(nbytes)
+        self.buf = torch.zeros(max(self.nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def paro_rotation_plan_build(rot: Rotation) -> None:
+    n = lib().paro_rotation_plan_bytes(rot.ref())
+    if n == 0:
+        raise ParoError(5, "paro_rotation_plan_bytes")
+    plan = torch.empty(n, dtype=torch.uint8, device=rot.pairs.device)
+    _check(lib().paro_rotation_plan_build(rot.ref(), plan.data_ptr(), _stream()), "paro_rotation_plan_build")
+    rot.plan = plan
+    rot.c.plan = plan.data_ptr()
+
+
+def paro_w4_repack(w: W4Weight) -> None:
+    n = lib().paro_w4_repack_bytes(w.ref())
+    if n == 0:
+        raise ParoError(5, "paro_w4_repack_bytes")
+    blob = torch.empty(n, dtype=torch.uint8, device=w.qweight.device)
+    _check(lib().paro_w4_repack(w.ref(), blob.data_ptr(), _stream()), "paro_w4_repack")
+    w.packed = blob
+    w.c.packed = blob.data_ptr()
+
+
+def paro_workspace_bytes(rot: Rotation | None, w: W4Weight, T: int) -> int:
+    return lib().paro_workspace_bytes(rot.ref() if rot is not None else None, w.ref(), T)
+
+
+def _rows(x: torch.Tensor):
+    assert x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
+    return x.shape[0], x.stride(0)
+
+
+def paro_rotate_scale(rot: Rotation, X: torch.Tensor, Xr: torch.Tensor | None = None) -> torch.Tensor:
+    T, ldx = _rows(X)
+    if Xr is None:
+        Xr = torch.empty((T, rot.c_in), dtype=torch.float16, device=X.device)
+    _, ldxr = _rows(Xr)
+    _check(lib().paro_rotate_scale(rot.ref(), X.data_ptr(), ldx, Xr.data_ptr(), ldxr, T, _stream()), "paro_rotate_scale")
+    return Xr
+
+
+def paro_w4a16_linear(w: W4Weight, X: torch.Tensor, ws: Workspace | None = None, Y: torch.Tensor | None = None):
+    T, ldx = _rows(X)
+    if Y is None:
+        Y = torch.empty((T, w.c_out), dtype=torch.float16, device=X.device)
+    _, ldy = _rows(Y)
+    _check(lib().paro_w4a16_linear(w.ref(), X.data_ptr(), ldx, Y.data_ptr(), ldy, T,
+                                   ws.buf.data_ptr() if ws else None, ws.nbytes if ws else 0, _stream()),
+           "paro_w4a16_linear")
+    return Y
+
+
+def paro_rotated_linear(rot: Rotation, w: W4Weight, X: torch.Tensor, ws: Workspace, Y: torch.Tensor | None = None):
+    T, ldx = _rows(X)
+    if Y is None:
+        Y = torch.empty((T, w.c_out), dtype=torch.float16, device=X.device)
+    _, ldy = _rows(Y)
+    _check(lib().paro_rotated_linear(rot.ref(), w.ref(), X.data_ptr(), ldx, Y.data_ptr(), ldy, T,
+                                     ws.buf.data_ptr(), ws.nbytes, _stream()), "paro_rotated_linear")
+    return Y
+
+
+def paro_w4_unpack_codes(w: W4Weight) -> torch.Tensor:
+    out = torch.empty((w.c_out, w.c_in), dtype=torch.uint8, device=(w.packed if w.qweight is None else w.qweight).device)
+    _check(lib().paro_w4_unpack_codes(w.ref(), out.data_ptr(), _stream()), "paro_w4_unpack_codes")
+    return out
+
+
+def paro_w4_unpack_zeros(w: W4Weight) -> torch.Tensor:
+    out = torch.empty((w.c_in // 128, w.c_out), dtype=torch.uint8, device=(w.packed if w.qweight is None else w.qweight).device)
+    _check(lib().paro_w4_unpack_zeros(w.ref(), out.data_ptr(), _stream()), "paro_w4_unpack_zeros")
+    return out
+
+
+def paro_w4_dequant(w: W4Weight) -> torch.Tensor:
+    out = torch.empty((w.c_out, w.c_in), dtype=torch.float16, device=(w.packed if w.qweight is None else w.qweight).device)
+    _check(lib().paro_w4_dequant(w.ref(), out.data_ptr(), _stream()), "paro_w4_dequant")
+    return out

@@ -1,0 +1,339 @@
+// Decode-side W4A16 linear (1..16 tokens per pass), bare or with the scaled pairwise rotation
+// fused in front (Eq. 2 with T of Eq. 8).  HBM-bound: the packed INT4 weights are streamed
+// exactly once, as 1 KB tiles, and everything else is arranged around that stream.
+//
+// Work split.  The input channels are cut into K-slices of 4 groups (512 channels).  A block
+// owns ONE K-slice and a range of 16-row output tiles; its waves share the slice and take
+// different tiles.  A wave therefore needs the activations of 512 channels only, and keeps
+// them as MFMA A-fragments in registers for the whole stream (tokens padded to 16).  With the
+// rotation fused, each of the block's 4 waves rotates one of the slice's 4 groups (one
+// wavefront per (token, group), see rotate.hip) - the prologue costs one group-rotation per
+// wave however wide the layer is, and runs while the first weight tiles are in flight.
+//
+// Inner loop per 16x128 tile and lane: one 16-byte load (32 codes), and-or with the fp16
+// magic numbers 1024 / 64 (code lands in the mantissa), one packed fp16 add of -(1024+z) /
+// -(64+z) (exact: small integers), four v_mfma_f32_16x16x32_f16, then the group's scale is
+// applied once to the fp32 tile sum:  y += s * sum_k (q - z) x'.
+//
+// Split-K reduction: each block stores fp32 partial tiles to the workspace; the last block to
+// finish an output range (atomic counter) adds the KS partials in a fixed order, adds the
+// bias, rounds to fp16 and resets the counter.  The result is deterministic.
+#include "paro_internal.h"
+
+namespace paro {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDecWaves = 4;
+constexpr int kDecThreads = kDecWaves * 64;
+constexpr int kSliceCh = kSliceGroups * kGroup;      // 512
+constexpr int kXPad = 8;                             // halfs of padding per LDS row
+constexpr size_t kCounterBytes = 4096;               // up to 1024 N-blocks
+
+static int g_decode_target_blocks = 512;
+
+struct DecodeArgs {
+    PackedView pv;
+    const _Float16 *X; int64_t ldx;
+    _Float16 *Y; int64_t ldy;
+    const _Float16 *bias;
+    const uint32_t *plan;
+    float *partial;
+    uint32_t *counters;
+    int T, C, N, G, NT, KS, tiles_per_block;
+};
+
+struct Stage {
+    u32x4 w[kSliceGroups];
+    uint2 sc;
+    uint32_t zq;
+};
+
+__device__ inline void load_stage(const DecodeArgs &a, int nt, int ks, int lane, Stage &st)
+{
+    const u32x4 *base = (const u32x4 *)a.pv.tiles + ((size_t)nt * a.G + (size_t)ks * kSliceGroups) * 64 + lane;
+#pragma unroll
+    for (int gi = 0; gi < kSliceGroups; ++gi) st.w[gi] = __builtin_nontemporal_load(base + gi * 64);
+    size_t sidx = ((size_t)nt * a.KS + ks) * kTileN + (lane & 15);
+    st.sc = a.pv.scales[sidx];
+    st.zq = a.pv.zeros[sidx];
+}
+
+__device__ inline half2v as_h2(uint32_t u) { union { uint32_t u; half2v h; } c; c.u = u; return c.h; }
+__device__ inline uint32_t as_u32(half2v h) { union { uint32_t u; half2v h; } c; c.h = h; return c.u; }
+
+// sum over the slice's 4 groups of s_g * sum_k (q - z_g) x'  for one 16-row tile
+__device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGroups][4])
+{
+    float4v tot = {0.f, 0.f, 0.f, 0.f};
+    union { uint2 v; _Float16 h[4]; } sc; sc.v = st.sc;
+#pragma unroll
+    for (int gi = 0; gi < kSliceGroups; ++gi) {
+        uint32_t z = (st.zq >> (4 * gi)) & 15u;
+        half2v nlo = as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
+        half2v nhi = as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t u = st.w[gi][j];
+            union { uint32_t d[4]; half8 h; } b;
+            b.d[0] = as_u32(as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo);
+            b.d[1] = as_u32(as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi);
+            u >>= 8;
+            b.d[2] = as_u32(as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo);
+            b.d[3] = as_u32(as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[gi][j], b.h, acc, 0, 0, 0);
+        }
+        float s = (float)sc.h[gi];
+        tot += s * acc;
+    }
+    return tot;
+}
+
+// K >= 0: rotation with K layers fused; K < 0: bare linear on X.
+template <int K>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
+{
+    __shared__ _Float16 s_x[16][kSliceCh + kXPad];
+    __shared__ int s_last;
+    const int ks = blockIdx.x, nb = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tile_lo = nb * a.tiles_per_block;
+    const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
+
+    // start the weight stream before anything else
+    Stage st0, st1;
+    int nt = tile_lo + wave;
+    if (nt < tile_hi) load_stage(a, nt, ks, lane, st0);
+
+    // ---- activations of this K-slice -> MFMA A fragments ---------------------------------
+    half8 xf[kSliceGroups][4];
+    const int ft = lane & 15, fkb = lane >> 4;
+    const size_t c0 = (size_t)ks * kSliceCh;
+    if constexpr (K >= 0) {
+        // wave w rotates group w of the slice for all T tokens
+        const int gi = wave;
+        const uint32_t *gplan = a.plan + ((size_t)ks * kSliceGroups + gi) * plan_group_dwords(K);
+        // natural-order load first (independent of the plan), staged through LDS
+        for (int t = 0; t < a.T; ++t)
+            *(uint32_t *)&s_x[t][gi * kGroup + 2 * lane] =
+                *(const uint32_t *)(a.X + (size_t)t * a.ldx + c0 + gi * kGroup + 2 * lane);
+        uint32_t io = gplan[lane];
+        float sia = __uint_as_float(gplan[64 + lane]), sib = __uint_as_float(gplan[128 + lane]);
+        float soa = __uint_as_float(gplan[192 + lane]), sob = __uint_as_float(gplan[256 + lane]);
+        float pc[K > 0 ? K : 1], ps[K > 0 ? K : 1];
+        uint32_t pm[K > 0 ? K : 1];
+#pragma unroll
+        for (int l = 0; l < K; ++l) {
+            const uint32_t *row = gplan + (size_t)(kPlanHeadRows + kPlanRowsPerLayer * l) * 64;
+            pc[l] = __uint_as_float(row[lane]); ps[l] = __uint_as_float(row[64 + lane]); pm[l] = row[128 + lane];
+        }
+        const int in_a = io & 0xff, in_b = (io >> 8) & 0xff, out_a = (io >> 16) & 0xff, out_b = io >> 24;
+        for (int t = 0; t < a.T; ++t) {
+            float va = (float)s_x[t][gi * kGroup + in_a] * sia;
+            float vb = (float)s_x[t][gi * kGroup + in_b] * sib;
+#pragma unroll
+            for (int l = 0; l < K; ++l) {
+                float m00, m01, m10, m11;
+                bool ai = pm[l] & kMetaAIsI, ki = pm[l] & kMetaKeepI;
+                float c = pc[l], s = ps[l];
+                float ni_a = ai ? c : -s, ni_b = ai ? -s : c, nj_a = ai ? s : c, nj_b = ai ? c : s;
+                m00 = ki ? ni_a : nj_a; m01 = ki ? ni_b : nj_b; m10 = ki ? nj_a : ni_a; m11 = ki ? nj_b : ni_b;
+                float na = m00 * va + m01 * vb, nb2 = m10 * va + m11 * vb;
+                va = na;
+                vb = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute((int)(pm[l] & 0xff), __float_as_int(nb2)))
+                                 : nb2;
+            }
+            // all lanes have read their inputs of token t (the bpermutes above are wave-wide),
+            // so the staging row can be overwritten with the result
+            s_x[t][gi * kGroup + out_a] = (_Float16)(va * soa);
+            s_x[t][gi * kGroup + out_b] = (_Float16)(vb * sob);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (ft < a.T) v = *(const half8 *)&s_x[ft][g2 * kGroup + fkb * 32 + j * 8];
+                xf[g2][j] = v;
+            }
+    } else {
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (ft < a.T) v = *(const half8 *)(a.X + (size_t)ft * a.ldx + c0 + g2 * kGroup + fkb * 32 + j * 8);
+                xf[g2][j] = v;
+            }
+    }
+
+    // ---- stream the tiles: two register stages, the next tile is in flight while this one is used
+    const int n_in_tile = lane & 15, tq = lane >> 4;
+    auto emit = [&](const Stage &stg, int tile) {
+        float4v tot = tile_dot(stg, xf);
+        const size_t n = (size_t)tile * kTileN + n_in_tile;
+        if (a.KS == 1) {
+            float bv = a.bias ? (float)a.bias[n] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int t = tq * 4 + r;
+                if (t < a.T) a.Y[(size_t)t * a.ldy + n] = (_Float16)(tot[r] + bv);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int t = tq * 4 + r;
+                if (t < a.T)
+                    __hip_atomic_store(a.partial + ((size_t)ks * a.T + t) * a.N + n, tot[r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    };
+    while (nt < tile_hi) {
+        int nxt = nt + kDecWaves;
+        if (nxt < tile_hi) load_stage(a, nxt, ks, lane, st1);
+        emit(st0, nt);
+        nt = nxt;
+        if (nt >= tile_hi) break;
+        nxt = nt + kDecWaves;
+        if (nxt < tile_hi) load_stage(a, nxt, ks, lane, st0);
+        emit(st1, nt);
+        nt = nxt;
+    }
+
+    // ---- split-K: the last block of this output range reduces --------------------------------
+    if (a.KS > 1) {
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t old = __hip_atomic_fetch_add(a.counters + nb, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (old == (uint32_t)(a.KS - 1));
+        }
+        __syncthreads();
+        if (s_last) {
+            __threadfence();
+            const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
+            for (int idx = threadIdx.x; idx < a.T * width; idx += kDecThreads) {
+                int t = idx / width, n = n_lo + idx % width;
+                float sum = 0.f;
+                for (int k2 = 0; k2 < a.KS; ++k2)
+                    sum += __hip_atomic_load(a.partial + ((size_t)k2 * a.T + t) * a.N + n, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+                if (a.bias) sum += (float)a.bias[n];
+                a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
+            }
+            if (threadIdx.x == 0)
+                __hip_atomic_store(a.counters + nb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+DecodeGeometry decode_geometry(int c_in, int c_out, int T)
+{
+    DecodeGeometry d;
+    int G = c_in / kGroup, NT = c_out / kTileN;
+    d.ks = G / kSliceGroups;
+    d.waves = kDecWaves;
+    int nb = g_decode_target_blocks / d.ks;
+    if (nb < 1) nb = 1;
+    int tpb = (NT + nb - 1) / nb;
+    tpb = (tpb + kDecWaves - 1) / kDecWaves * kDecWaves;     // whole rounds of the block's waves
+    d.tiles_per_block = tpb;
+    d.nb = (NT + tpb - 1) / tpb;
+    int t16 = T < 16 ? T : 16;
+    d.partial_bytes = d.ks > 1 ? (size_t)d.ks * t16 * c_out * sizeof(float) : 0;
+    d.counter_bytes = d.ks > 1 ? kCounterBytes : 0;
+    return d;
+}
+
+template <int K>
+static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, hipStream_t s)
+{
+    hipLaunchKernelGGL(decode_kernel<K>, dim3(d.ks, d.nb), dim3(kDecThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
+                         paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s)
+{
+    DecodeGeometry d = decode_geometry(w.c_in, w.c_out, T);
+    if ((size_t)d.nb * sizeof(uint32_t) > kCounterBytes) return hipErrorInvalidValue;
+    DecodeArgs a;
+    a.pv = packed_view(w.packed, w.c_in, w.c_out);
+    a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
+    a.bias = (const _Float16 *)w.bias;
+    a.plan = rot ? (const uint32_t *)rot->plan : nullptr;
+    a.counters = (uint32_t *)ws;
+    a.partial = (float *)((char *)ws + kCounterBytes);
+    a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN; a.KS = d.ks;
+    a.tiles_per_block = d.tiles_per_block;
+    if (!rot) return launch_decode_k<-1>(a, d, s);
+    switch (rot->n_layers) {
+    case 0: return launch_decode_k<0>(a, d, s);
+    case 1: return launch_decode_k<1>(a, d, s);
+    case 2: return launch_decode_k<2>(a, d, s);
+    case 3: return launch_decode_k<3>(a, d, s);
+    case 4: return launch_decode_k<4>(a, d, s);
+    case 5: return launch_decode_k<5>(a, d, s);
+    case 6: return launch_decode_k<6>(a, d, s);
+    case 7: return launch_decode_k<7>(a, d, s);
+    default: return launch_decode_k<8>(a, d, s);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic linear on the interchange layout: one wave per output row, plain fp32 FMAs.
+// Slow; used when no repacked blob was supplied.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void linear_generic_kernel(const uint32_t *__restrict__ qweight,
+                                                             const _Float16 *__restrict__ scales,
+                                                             const uint32_t *__restrict__ qzeros,
+                                                             const _Float16 *__restrict__ bias, int C, int N,
+                                                             const _Float16 *__restrict__ X, int64_t ldx,
+                                                             _Float16 *__restrict__ Y, int64_t ldy, int T)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t n = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= (size_t)N) return;
+    const int words = C / 8;
+    for (int t0 = 0; t0 < T; t0 += 4) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int wi = lane; wi < words; wi += 64) {
+            uint32_t w = qweight[n * words + wi];
+            int g = wi / 16;
+            float s = (float)scales[(size_t)g * N + n];
+            int z = (int)((qzeros[(size_t)g * (N / 8) + n / 8] >> (4 * (n % 8))) & 15u);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float wv = (float)((int)((w >> (4 * e)) & 15u) - z) * s;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (t0 + u < T) acc[u] += wv * (float)X[(size_t)(t0 + u) * ldx + (size_t)wi * 8 + e];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float v = acc[u];
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0 && t0 + u < T) Y[(size_t)(t0 + u) * ldy + n] = (_Float16)(v + (bias ? (float)bias[n] : 0.f));
+        }
+    }
+}
+
+hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y,
+                                 int64_t ldy, int T, hipStream_t s)
+{
+    hipLaunchKernelGGL(linear_generic_kernel, dim3((w.c_out + 3) / 4), dim3(256), 0, s, w.qweight,
+                       (const _Float16 *)w.scales, w.qzeros, (const _Float16 *)w.bias, w.c_in, w.c_out,
+                       (const _Float16 *)X, ldx, (_Float16 *)Y, ldy, T);
+    return hipGetLastError();
+}
+
+void set_decode_target_blocks(int blocks) { g_decode_target_blocks = blocks > 0 ? blocks : 512; }
+
+}  // namespace paro

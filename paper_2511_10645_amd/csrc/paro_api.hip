@@ -1,0 +1,259 @@
+// C ABI of libparo (include/paro.h): argument validation on the host, then dispatch to the
+// kernels.  No device memory is allocated or retained here.
+#include "paro_internal.h"
+
+using namespace paro;
+
+namespace paro {
+void set_decode_target_blocks(int blocks);
+}
+
+namespace {
+
+constexpr int kFuseMaxTokens = 4;   // rotation runs inside the decode kernel up to this many tokens
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+paro_status check_rotation(const paro_rotation *r)
+{
+    if (!r) return PARO_ERR_NULL;
+    if (r->group != kGroup) return PARO_ERR_UNSUPPORTED;
+    if (r->n_layers < 0 || r->n_layers > kMaxLayers) return PARO_ERR_UNSUPPORTED;
+    if (r->pairs_per_layer < 1 || r->pairs_per_layer > kGroup / 2) return PARO_ERR_UNSUPPORTED;
+    if (r->scale_order != 0 && r->scale_order != 1) return PARO_ERR_UNSUPPORTED;
+    if (r->c_in <= 0 || r->c_in % r->group) return PARO_ERR_SHAPE;
+    if (r->n_layers > 0 && (!r->pairs || !r->theta)) return PARO_ERR_NULL;
+    if (!aligned(r->pairs, 4) || !aligned(r->theta, 4) || !aligned(r->ch_scale, 2) || !aligned(r->plan, 256))
+        return PARO_ERR_ALIGN;
+    return PARO_OK;
+}
+
+paro_status check_weight(const paro_w4_weight *w, bool need_interchange)
+{
+    if (!w) return PARO_ERR_NULL;
+    if (w->group != kGroup) return PARO_ERR_UNSUPPORTED;
+    if (w->c_in <= 0 || w->c_out <= 0 || w->c_in % w->group || w->c_out % kTileN) return PARO_ERR_SHAPE;
+    bool have_ic = w->qweight && w->scales && w->qzeros;
+    if (need_interchange ? !have_ic : (!have_ic && !w->packed)) return PARO_ERR_NULL;
+    if (!aligned(w->qweight, 16) || !aligned(w->scales, 2) || !aligned(w->qzeros, 4) || !aligned(w->bias, 2) ||
+        !aligned(w->packed, 256))
+        return PARO_ERR_ALIGN;
+    return PARO_OK;
+}
+
+inline bool fast_weight(const paro_w4_weight *w) { return w->packed && (w->c_in / kGroup) % kSliceGroups == 0; }
+
+paro_status check_io(const void *X, int64_t ldx, int width_x, const void *Y, int64_t ldy, int width_y, int T,
+                     int64_t ld_mult)
+{
+    if (!X || !Y) return PARO_ERR_NULL;
+    if (T <= 0 || ldx < width_x || ldy < width_y) return PARO_ERR_SHAPE;
+    if (ldx % ld_mult || ldy % ld_mult || !aligned(X, 2 * ld_mult) || !aligned(Y, 2 * ld_mult)) return PARO_ERR_ALIGN;
+    return PARO_OK;
+}
+
+struct WsLayout {
+    size_t decode_bytes;   // counters + split-K partial sums
+    size_t xr_offset;      // rotated activations (fp16 [T][c_in]) when the rotation is a separate pass
+    size_t total;
+};
+
+WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
+{
+    WsLayout L{0, 0, 0};
+    if (fast_weight(w)) {
+        DecodeGeometry d = decode_geometry(w->c_in, w->c_out, T);
+        L.decode_bytes = round_up(d.counter_bytes + d.partial_bytes, 256);
+    }
+    L.xr_offset = L.decode_bytes;
+    L.total = L.decode_bytes + (rot ? round_up((size_t)T * w->c_in * 2, 256) : 0);
+    return L;
+}
+
+paro_status from_hip(hipError_t e) { return e == hipSuccess ? PARO_OK : PARO_ERR_HIP; }
+
+// bare linear on (already transformed) activations, any T
+paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T,
+                       void *ws, hipStream_t s)
+{
+    if (!fast_weight(w)) {
+        if (!(w->qweight && w->scales && w->qzeros)) return PARO_ERR_UNSUPPORTED;
+        return from_hip(launch_linear_generic(*w, X, ldx, Y, ldy, T, s));
+    }
+    for (int t0 = 0; t0 < T; t0 += 16) {
+        int tc = T - t0 < 16 ? T - t0 : 16;
+        hipError_t e = launch_decode(nullptr, *w, X + (size_t)t0 * ldx, ldx, Y + (size_t)t0 * ldy, ldy, tc, ws, s);
+        if (e != hipSuccess) return PARO_ERR_HIP;
+    }
+    return PARO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int paro_version(void) { return 100; }
+
+const char *paro_status_string(paro_status s)
+{
+    switch (s) {
+    case PARO_OK: return "ok";
+    case PARO_ERR_NULL: return "a required pointer is NULL";
+    case PARO_ERR_SHAPE: return "inconsistent sizes";
+    case PARO_ERR_ALIGN: return "misaligned pointer or row stride";
+    case PARO_ERR_PAIRS: return "pairs of a layer are not independent (Def. 1) or an index is out of range";
+    case PARO_ERR_UNSUPPORTED: return "unsupported configuration";
+    case PARO_ERR_WORKSPACE: return "workspace missing or too small";
+    case PARO_ERR_HIP: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+paro_status paro_validate_pairs_host(const int16_t *pairs_host, int32_t n_groups, int32_t n_layers,
+                                     int32_t pairs_per_layer, int32_t group)
+{
+    if (!pairs_host) return PARO_ERR_NULL;
+    if (n_groups < 0 || n_layers < 0 || pairs_per_layer < 0 || group <= 0 || group > 32767) return PARO_ERR_SHAPE;
+    uint8_t used[32768 / 8];
+    for (int64_t gl = 0; gl < (int64_t)n_groups * n_layers; ++gl) {
+        for (int c = 0; c < (group + 7) / 8; ++c) used[c] = 0;
+        const int16_t *p = pairs_host + gl * pairs_per_layer * 2;
+        for (int k = 0; k < pairs_per_layer; ++k) {
+            int i = p[2 * k], j = p[2 * k + 1];
+            if (i < 0 || j < 0 || i >= group || j >= group) return PARO_ERR_PAIRS;
+            if (i == j) continue;   // empty slot: names no channel
+            if ((used[i >> 3] >> (i & 7)) & 1 || (used[j >> 3] >> (j & 7)) & 1) return PARO_ERR_PAIRS;
+            used[i >> 3] |= (uint8_t)(1u << (i & 7));
+            used[j >> 3] |= (uint8_t)(1u << (j & 7));
+        }
+    }
+    return PARO_OK;
+}
+
+size_t paro_rotation_plan_bytes(const paro_rotation *rot)
+{
+    if (check_rotation(rot) != PARO_OK) return 0;
+    return round_up((size_t)(rot->c_in / kGroup) * plan_group_dwords(rot->n_layers) * 4, 256);
+}
+
+paro_status paro_rotation_plan_build(const paro_rotation *rot, void *plan_out, void *stream)
+{
+    paro_status st = check_rotation(rot);
+    if (st != PARO_OK) return st;
+    if (!plan_out) return PARO_ERR_NULL;
+    if (!aligned(plan_out, 256)) return PARO_ERR_ALIGN;
+    return from_hip(launch_plan_build(*rot, plan_out, (hipStream_t)stream));
+}
+
+size_t paro_w4_repack_bytes(const paro_w4_weight *w)
+{
+    if (check_weight(w, false) != PARO_OK) return 0;
+    if ((w->c_in / kGroup) % kSliceGroups) return 0;   // the tiled layout needs whole 512-channel slices
+    return round_up(packed_tiles_bytes(w->c_in, w->c_out) + packed_scales_bytes(w->c_in, w->c_out) +
+                        packed_zeros_bytes(w->c_in, w->c_out),
+                    256);
+}
+
+paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stream)
+{
+    paro_status st = check_weight(w, true);
+    if (st != PARO_OK) return st;
+    if (!packed_out) return PARO_ERR_NULL;
+    if (!aligned(packed_out, 256)) return PARO_ERR_ALIGN;
+    if ((w->c_in / kGroup) % kSliceGroups) return PARO_ERR_UNSUPPORTED;
+    return from_hip(launch_repack(*w, packed_out, (hipStream_t)stream));
+}
+
+size_t paro_workspace_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T)
+{
+    if (check_weight(w, false) != PARO_OK || T <= 0) return 0;
+    if (rot && (check_rotation(rot) != PARO_OK || rot->c_in != w->c_in)) return 0;
+    return ws_layout(rot, w, T).total;
+}
+
+paro_status paro_rotate_scale(const paro_rotation *rot, const paro_half_t *X, int64_t ldx, paro_half_t *Xr,
+                              int64_t ldxr, int32_t T, void *stream)
+{
+    paro_status st = check_rotation(rot);
+    if (st != PARO_OK) return st;
+    st = check_io(X, ldx, rot->c_in, Xr, ldxr, rot->c_in, T, 2);
+    if (st != PARO_OK) return st;
+    if (X == Xr && ldx != ldxr) return PARO_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    if (rot->plan) return from_hip(launch_rotate_planned(*rot, X, ldx, Xr, ldxr, T, s));
+    return from_hip(launch_rotate_generic(*rot, X, ldx, Xr, ldxr, T, s));
+}
+
+paro_status paro_w4a16_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                              int32_t T, void *ws, size_t ws_bytes, void *stream)
+{
+    paro_status st = check_weight(w, false);
+    if (st != PARO_OK) return st;
+    st = check_io(X, ldx, w->c_in, Y, ldy, w->c_out, T, 8);
+    if (st != PARO_OK) return st;
+    WsLayout L = ws_layout(nullptr, w, T);
+    if (L.total && (!ws || ws_bytes < L.total)) return PARO_ERR_WORKSPACE;
+    if (L.total && !aligned(ws, 256)) return PARO_ERR_ALIGN;
+    return run_linear(w, X, ldx, Y, ldy, T, ws, (hipStream_t)stream);
+}
+
+paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X, int64_t ldx,
+                                paro_half_t *Y, int64_t ldy, int32_t T, void *ws, size_t ws_bytes, void *stream)
+{
+    paro_status st = check_rotation(rot);
+    if (st != PARO_OK) return st;
+    st = check_weight(w, false);
+    if (st != PARO_OK) return st;
+    if (rot->c_in != w->c_in) return PARO_ERR_SHAPE;
+    st = check_io(X, ldx, w->c_in, Y, ldy, w->c_out, T, 8);
+    if (st != PARO_OK) return st;
+    WsLayout L = ws_layout(rot, w, T);
+    if (!ws || ws_bytes < L.total) return PARO_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return PARO_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (fast_weight(w) && rot->plan && T <= kFuseMaxTokens)
+        return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
+
+    // two passes: transform into the workspace, then the bare linear
+    paro_half_t *xr = (paro_half_t *)((char *)ws + L.xr_offset);
+    hipError_t e = rot->plan ? launch_rotate_planned(*rot, X, ldx, xr, w->c_in, T, s)
+                             : launch_rotate_generic(*rot, X, ldx, xr, w->c_in, T, s);
+    if (e != hipSuccess) return PARO_ERR_HIP;
+    return run_linear(w, xr, w->c_in, Y, ldy, T, ws, s);
+}
+
+paro_status paro_w4_unpack_codes(const paro_w4_weight *w, uint8_t *codes, void *stream)
+{
+    paro_status st = check_weight(w, false);
+    if (st != PARO_OK) return st;
+    if (!codes) return PARO_ERR_NULL;
+    if (!aligned(codes, 8)) return PARO_ERR_ALIGN;
+    if (w->packed && (w->c_in / kGroup) % kSliceGroups) return PARO_ERR_UNSUPPORTED;
+    return from_hip(launch_unpack_codes(*w, codes, (hipStream_t)stream));
+}
+
+paro_status paro_w4_unpack_zeros(const paro_w4_weight *w, uint8_t *zeros, void *stream)
+{
+    paro_status st = check_weight(w, false);
+    if (st != PARO_OK) return st;
+    if (!zeros) return PARO_ERR_NULL;
+    if (w->packed && (w->c_in / kGroup) % kSliceGroups) return PARO_ERR_UNSUPPORTED;
+    return from_hip(launch_unpack_zeros(*w, zeros, (hipStream_t)stream));
+}
+
+paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *stream)
+{
+    paro_status st = check_weight(w, false);
+    if (st != PARO_OK) return st;
+    if (!W) return PARO_ERR_NULL;
+    if (!aligned(W, 16)) return PARO_ERR_ALIGN;
+    if (w->packed && (w->c_in / kGroup) % kSliceGroups) return PARO_ERR_UNSUPPORTED;
+    return from_hip(launch_dequant(*w, W, (hipStream_t)stream));
+}
+
+// Tuning knob (process-wide, not thread-safe): target number of decode blocks per launch.
+void paro_tune_decode_blocks(int blocks) { paro::set_decode_target_blocks(blocks); }
+
+}  // extern "C"

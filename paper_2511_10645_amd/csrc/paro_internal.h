@@ -1,0 +1,106 @@
+// Internal declarations shared by the HIP translation units of libparo.
+// Nothing here is part of the C ABI (see include/paro.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "paro.h"
+
+namespace paro {
+
+constexpr int kGroup = 128;        // channel-group size g (Section 5, "Implementation")
+constexpr int kMaxLayers = 8;      // K
+constexpr int kLanes = 64;         // one wavefront owns one (token, group): lane p <-> pair slot p
+constexpr int kTileN = 16;         // output rows per weight tile (MFMA 16x16x32 B operand)
+constexpr int kSliceGroups = 4;    // groups per K-slice: unit of the scales/zeros tiling
+
+// ---------------------------------------------------------------------------------------
+// Rotation plan (blob of paro_rotation_plan_build).  One block per channel group, made of
+// rows of 64 dwords (one per lane), so every row is one coalesced 256-byte load:
+//   row 0            io word: in_a | in_b<<8 | out_a<<16 | out_b<<24   (local channel ids)
+//   row 1, 2         fp32 multipliers applied to the two loaded values (ch_scale or 1)
+//   row 3, 4         fp32 multipliers applied to the two stored values (1 or ch_scale)
+//   row 5+3l .. 7+3l layer l: cos(theta), sin(theta), meta
+// meta bits: [7:0] byte address (lane*4) this lane pulls its next "b" value from,
+//            bit 8  A_IS_I  : slot a holds channel i of the pair (else channel j)
+//            bit 9  KEEP_I  : the updated channel i stays in this lane (else channel j stays)
+// A lane holds two values (a, b).  After a layer it keeps one result in `a` and hands the
+// other to exactly one other lane, receiving one in return: one ds_bpermute per layer.
+// ---------------------------------------------------------------------------------------
+constexpr int kPlanHeadRows = 5;
+constexpr int kPlanRowsPerLayer = 3;
+constexpr uint32_t kMetaAIsI = 1u << 8;
+constexpr uint32_t kMetaKeepI = 1u << 9;
+
+__host__ __device__ inline int plan_rows(int n_layers) { return kPlanHeadRows + kPlanRowsPerLayer * n_layers; }
+__host__ __device__ inline size_t plan_group_dwords(int n_layers) { return (size_t)plan_rows(n_layers) * kLanes; }
+
+// ---------------------------------------------------------------------------------------
+// Repacked weight blob (paro_w4_repack).  NT = c_out/16 row tiles, G = c_in/128 groups,
+// S = G/4 K-slices.
+//   tiles  [NT][G][64 lanes][4 dwords]   lane = kb*16 + n; dword j holds the 8 codes of row
+//          16*nt+n, channels 128*g + 32*kb + 8*j + (0..7); code e sits in nibble
+//          (e>>1) + 4*(e&1), so that (w & 0x000F000F), ((w>>4) & 0x000F000F), ... give
+//          channel pairs (0,1), (2,3), (4,5), (6,7) as packed 16-bit lanes
+//   scales [NT][S][16 n][4 groups] fp16
+//   zeros  [NT][S][16 n] uint16: nibble gi = zero point of group 4*s+gi, row 16*nt+n
+// ---------------------------------------------------------------------------------------
+struct PackedView {
+    const uint4 *tiles;
+    const uint2 *scales;     // 4 fp16 per (nt, s, n)
+    const uint16_t *zeros;   // 4 nibbles per (nt, s, n)
+};
+
+__host__ __device__ inline size_t packed_tiles_bytes(int c_in, int c_out) {
+    return (size_t)(c_out / kTileN) * (size_t)(c_in / kGroup) * 1024u;
+}
+__host__ __device__ inline size_t packed_scales_bytes(int c_in, int c_out) {
+    return (size_t)(c_out / kTileN) * (size_t)(c_in / kGroup / kSliceGroups) * (kTileN * kSliceGroups * 2u);
+}
+__host__ __device__ inline size_t packed_zeros_bytes(int c_in, int c_out) {
+    return (size_t)(c_out / kTileN) * (size_t)(c_in / kGroup / kSliceGroups) * (kTileN * 2u);
+}
+__host__ __device__ inline PackedView packed_view(const void *blob, int c_in, int c_out) {
+    const char *p = (const char *)blob;
+    PackedView v;
+    v.tiles = (const uint4 *)p;
+    v.scales = (const uint2 *)(p + packed_tiles_bytes(c_in, c_out));
+    v.zeros = (const uint16_t *)(p + packed_tiles_bytes(c_in, c_out) + packed_scales_bytes(c_in, c_out));
+    return v;
+}
+
+// nibble position of logical element e (0..7) inside a repacked dword
+__host__ __device__ inline int packed_nibble_pos(int e) { return (e >> 1) + 4 * (e & 1); }
+
+// ---------------------------------------------------------------------------------------
+// Launchers (defined next to their kernels).  All return the hipError_t of the launch.
+// ---------------------------------------------------------------------------------------
+hipError_t launch_plan_build(const paro_rotation &rot, void *plan_out, hipStream_t s);
+hipError_t launch_rotate_planned(const paro_rotation &rot, const paro_half_t *X, int64_t ldx,
+                                 paro_half_t *Xr, int64_t ldxr, int T, hipStream_t s);
+hipError_t launch_rotate_generic(const paro_rotation &rot, const paro_half_t *X, int64_t ldx,
+                                 paro_half_t *Xr, int64_t ldxr, int T, hipStream_t s);
+
+hipError_t launch_repack(const paro_w4_weight &w, void *packed_out, hipStream_t s);
+hipError_t launch_unpack_codes(const paro_w4_weight &w, uint8_t *codes, hipStream_t s);
+hipError_t launch_unpack_zeros(const paro_w4_weight &w, uint8_t *zeros, hipStream_t s);
+hipError_t launch_dequant(const paro_w4_weight &w, paro_half_t *W, hipStream_t s);
+
+// Decode-side linear (T <= 16 per pass).  rot == nullptr: bare linear on X.
+struct DecodeGeometry {
+    int ks;           // K-slices (grid.x)
+    int nb;           // N-blocks per slice (grid.y)
+    int waves;        // waves per block
+    int tiles_per_block;
+    size_t partial_bytes;   // fp32 partial sums [ks][T][c_out] (0 when ks == 1)
+    size_t counter_bytes;   // one uint32 per N-block (0 when ks == 1)
+};
+DecodeGeometry decode_geometry(int c_in, int c_out, int T);
+hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
+                         paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s);
+hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
+                                 paro_half_t *Y, int64_t ldy, int T, hipStream_t s);
+
+}  // namespace paro

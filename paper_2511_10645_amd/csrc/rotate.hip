@@ -1,0 +1,352 @@
+// Scaled pairwise rotation of activations (Section 4.1, Eq. 4/5/8; kernel idea of Section 4.3
+// re-designed for CDNA4 wave64):
+//
+//   one wavefront owns one (token, channel group); lane p owns the pair it is currently
+//   rotating, as two fp32 registers (a, b).  Because the pairs of a layer are disjoint
+//   (Def. 1) the 64 lanes never need to synchronise inside a layer.  Between layer l and
+//   l+1 the union of the two perfect matchings is a set of alternating cycles, so the pair
+//   of layer l+1 can be placed in a lane that already holds one of its two channels: every
+//   lane keeps one value and receives exactly one from another lane - a single
+//   ds_bpermute_b32 per layer, no LDS allocation, no barrier.  The routing, cos/sin (fp64
+//   evaluation rounded to fp32) and the folded channel scales are precomputed once per
+//   weight into a "plan" (paro_rotation_plan_build).
+#include "paro_internal.h"
+
+namespace paro {
+
+// ------------------------------------------------------------------------------------------
+// Plan build: one 64-thread block per channel group.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restrict__ pairs,
+                                                        const float *__restrict__ theta,
+                                                        const paro_half_t *__restrict__ ch_scale, int n_layers,
+                                                        int ppl, int scale_order, uint32_t *__restrict__ plan)
+{
+    __shared__ uint8_t s_pi[kMaxLayers][64], s_pj[kMaxLayers][64];   // completed matching per layer
+    __shared__ int16_t s_slot[kMaxLayers][64];                        // source slot of pair, -1 = filler
+    __shared__ float s_c[kMaxLayers][64], s_s[kMaxLayers][64];
+    __shared__ uint8_t s_cha[kMaxLayers][64], s_chb[kMaxLayers][64];  // channels in slots a, b before layer l
+    __shared__ uint8_t s_pair[kMaxLayers][64];                        // which completed pair lane p processes
+    __shared__ uint8_t s_src[kMaxLayers][64];                         // lane to pull from after layer l
+    __shared__ uint8_t s_keep[kMaxLayers][64], s_send[kMaxLayers][64];
+    __shared__ uint8_t s_tmp[3][128];
+
+    const int g = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int16_t *gp = pairs + (size_t)g * n_layers * ppl * 2;
+    const float *gt = theta + (size_t)g * n_layers * ppl;
+
+    // Phase A: complete every layer to a perfect matching of the 128 channels.  Channels that
+    // no pair of the layer names are paired among themselves with the identity rotation.
+    if (lane == 0) {
+        uint8_t *used = s_tmp[0];
+        for (int l = 0; l < n_layers; ++l) {
+            for (int c = 0; c < kGroup; ++c) used[c] = 0;
+            int cnt = 0;
+            for (int p = 0; p < ppl && cnt < 64; ++p) {
+                int i = gp[((size_t)l * ppl + p) * 2], j = gp[((size_t)l * ppl + p) * 2 + 1];
+                if (i == j || i < 0 || j < 0 || i >= kGroup || j >= kGroup) continue;
+                if (used[i] || used[j]) continue;   // table violates Def. 1: ignore the slot
+                used[i] = used[j] = 1;
+                s_pi[l][cnt] = (uint8_t)i; s_pj[l][cnt] = (uint8_t)j; s_slot[l][cnt] = (int16_t)p;
+                ++cnt;
+            }
+            int first = -1;
+            for (int c = 0; c < kGroup && cnt < 64; ++c) {
+                if (used[c]) continue;
+                if (first < 0) { first = c; continue; }
+                s_pi[l][cnt] = (uint8_t)first; s_pj[l][cnt] = (uint8_t)c; s_slot[l][cnt] = -1;
+                ++cnt; first = -1;
+            }
+        }
+    }
+    __syncthreads();
+    for (int l = 0; l < n_layers; ++l) {
+        int slot = s_slot[l][lane];
+        float c = 1.0f, s = 0.0f;
+        if (slot >= 0) {
+            double sd, cd;
+            sincos((double)gt[(size_t)l * ppl + slot], &sd, &cd);
+            c = (float)cd; s = (float)sd;
+        }
+        s_c[l][lane] = c; s_s[l][lane] = s;
+    }
+    __syncthreads();
+
+    // Phase B: lane assignment.  Layer 0: lane p takes completed pair p with a = i, b = j.
+    // For each following layer walk the alternating cycles of (layer l) U (layer l+1).
+    if (lane == 0) {
+        for (int p = 0; p < 64; ++p) {
+            if (n_layers > 0) { s_cha[0][p] = s_pi[0][p]; s_chb[0][p] = s_pj[0][p]; s_pair[0][p] = (uint8_t)p; }
+        }
+        uint8_t *lane_of = s_tmp[0], *partner = s_tmp[1], *pair_of = s_tmp[2];
+        for (int l = 0; l + 1 < n_layers; ++l) {
+            for (int p = 0; p < 64; ++p) {
+                lane_of[s_cha[l][p]] = (uint8_t)p; lane_of[s_chb[l][p]] = (uint8_t)p;
+                partner[s_pi[l + 1][p]] = s_pj[l + 1][p]; partner[s_pj[l + 1][p]] = s_pi[l + 1][p];
+                pair_of[s_pi[l + 1][p]] = (uint8_t)p; pair_of[s_pj[l + 1][p]] = (uint8_t)p;
+            }
+            uint64_t visited = 0;
+            for (int p0 = 0; p0 < 64; ++p0) {
+                if ((visited >> p0) & 1) continue;
+                int p = p0;
+                int x = s_cha[l][p0];                     // channel this lane hands on
+                for (int guard = 0; guard < 64; ++guard) {
+                    visited |= 1ull << p;
+                    int y = (s_cha[l][p] == x) ? s_chb[l][p] : s_cha[l][p];   // channel that stays
+                    s_send[l][p] = (uint8_t)x; s_keep[l][p] = (uint8_t)y;
+                    int xn = partner[y];
+                    int pn = lane_of[xn];
+                    s_src[l][p] = (uint8_t)pn;
+                    s_cha[l + 1][p] = (uint8_t)y; s_chb[l + 1][p] = (uint8_t)xn; s_pair[l + 1][p] = pair_of[y];
+                    p = pn; x = xn;
+                    if (p == p0) break;
+                }
+            }
+        }
+        if (n_layers > 0) {
+            int l = n_layers - 1;
+            for (int p = 0; p < 64; ++p) {
+                s_keep[l][p] = s_pi[l][s_pair[l][p]]; s_send[l][p] = s_pj[l][s_pair[l][p]]; s_src[l][p] = (uint8_t)p;
+            }
+        }
+    }
+    __syncthreads();
+
+    // Phase C: write the rows.
+    uint32_t *out = plan + (size_t)g * plan_group_dwords(n_layers);
+    int in_a, in_b, out_a, out_b;
+    if (n_layers > 0) {
+        in_a = s_cha[0][lane]; in_b = s_chb[0][lane];
+        out_a = s_keep[n_layers - 1][lane]; out_b = s_send[n_layers - 1][lane];
+    } else {
+        in_a = out_a = 2 * lane; in_b = out_b = 2 * lane + 1;
+    }
+    out[0 * 64 + lane] = (uint32_t)in_a | ((uint32_t)in_b << 8) | ((uint32_t)out_a << 16) | ((uint32_t)out_b << 24);
+    const _Float16 *cs = (const _Float16 *)ch_scale;
+    float one = 1.0f;
+    float sia = one, sib = one, soa = one, sob = one;
+    if (cs) {
+        if (scale_order == 0) { sia = (float)cs[(size_t)g * kGroup + in_a]; sib = (float)cs[(size_t)g * kGroup + in_b]; }
+        else                  { soa = (float)cs[(size_t)g * kGroup + out_a]; sob = (float)cs[(size_t)g * kGroup + out_b]; }
+    }
+    out[1 * 64 + lane] = __float_as_uint(sia); out[2 * 64 + lane] = __float_as_uint(sib);
+    out[3 * 64 + lane] = __float_as_uint(soa); out[4 * 64 + lane] = __float_as_uint(sob);
+    for (int l = 0; l < n_layers; ++l) {
+        int pr = s_pair[l][lane];
+        uint32_t meta = (uint32_t)s_src[l][lane] << 2;
+        if (s_cha[l][lane] == s_pi[l][pr]) meta |= kMetaAIsI;
+        if (s_keep[l][lane] == s_pi[l][pr]) meta |= kMetaKeepI;
+        uint32_t *row = out + (size_t)(kPlanHeadRows + kPlanRowsPerLayer * l) * 64;
+        row[0 * 64 + lane] = __float_as_uint(s_c[l][pr]);
+        row[1 * 64 + lane] = __float_as_uint(s_s[l][pr]);
+        row[2 * 64 + lane] = meta;
+    }
+}
+
+hipError_t launch_plan_build(const paro_rotation &rot, void *plan_out, hipStream_t s)
+{
+    int G = rot.c_in / rot.group;
+    hipLaunchKernelGGL(plan_build_kernel, dim3(G), dim3(64), 0, s, rot.pairs, rot.theta, rot.ch_scale, rot.n_layers,
+                       rot.pairs_per_layer, rot.scale_order, (uint32_t *)plan_out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Planned rotation kernel.
+// ------------------------------------------------------------------------------------------
+template <int K>
+struct LanePlan {
+    float m00[K > 0 ? K : 1], m01[K > 0 ? K : 1], m10[K > 0 ? K : 1], m11[K > 0 ? K : 1];
+    int src[K > 0 ? K : 1];
+    int in_a, in_b, out_a, out_b;
+    float sia, sib, soa, sob;
+};
+
+// Expand (cos, sin, meta) into the 2x2 block that maps the lane's (a, b) to (keep, send).
+__device__ inline void expand_coeffs(float c, float s, uint32_t meta, float &m00, float &m01, float &m10, float &m11)
+{
+    bool ai = meta & kMetaAIsI, ki = meta & kMetaKeepI;
+    // updated channel i and j as combinations of (a, b)   (Eq. 4)
+    float ni_a = ai ? c : -s, ni_b = ai ? -s : c;
+    float nj_a = ai ? s : c,  nj_b = ai ? c : s;
+    m00 = ki ? ni_a : nj_a; m01 = ki ? ni_b : nj_b;
+    m10 = ki ? nj_a : ni_a; m11 = ki ? nj_b : ni_b;
+}
+
+template <int K>
+__device__ inline void load_lane_plan(const uint32_t *__restrict__ gplan, int lane, LanePlan<K> &P)
+{
+    uint32_t io = gplan[lane];
+    P.in_a = io & 0xff; P.in_b = (io >> 8) & 0xff; P.out_a = (io >> 16) & 0xff; P.out_b = io >> 24;
+    P.sia = __uint_as_float(gplan[1 * 64 + lane]); P.sib = __uint_as_float(gplan[2 * 64 + lane]);
+    P.soa = __uint_as_float(gplan[3 * 64 + lane]); P.sob = __uint_as_float(gplan[4 * 64 + lane]);
+#pragma unroll
+    for (int l = 0; l < K; ++l) {
+        const uint32_t *row = gplan + (size_t)(kPlanHeadRows + kPlanRowsPerLayer * l) * 64;
+        float c = __uint_as_float(row[lane]), s = __uint_as_float(row[64 + lane]);
+        uint32_t meta = row[128 + lane];
+        expand_coeffs(c, s, meta, P.m00[l], P.m01[l], P.m10[l], P.m11[l]);
+        P.src[l] = (int)(meta & 0xff);
+    }
+}
+
+// Run the K layers on TU independent tokens held as (a[u], b[u]); results: a = kept, b = sent slot.
+template <int K, int TU>
+__device__ inline void rotate_layers(const LanePlan<K> &P, float (&a)[TU], float (&b)[TU])
+{
+#pragma unroll
+    for (int l = 0; l < K; ++l) {
+#pragma unroll
+        for (int u = 0; u < TU; ++u) {
+            float na = P.m00[l] * a[u] + P.m01[l] * b[u];
+            float nb = P.m10[l] * a[u] + P.m11[l] * b[u];
+            a[u] = na;
+            b[u] = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute(P.src[l], __float_as_int(nb))) : nb;
+        }
+    }
+}
+
+constexpr int kRotWaves = 4;   // waves per block
+constexpr int kRotTU = 4;      // tokens in flight per wave
+
+template <int K>
+__global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const uint32_t *__restrict__ plan,
+                                                                         const _Float16 *X, int64_t ldx,
+                                                                         _Float16 *Xr, int64_t ldxr, int T,
+                                                                         int tokens_per_wave)
+{
+    const int g = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int t0 = (blockIdx.y * kRotWaves + wave) * tokens_per_wave;
+    if (t0 >= T) return;
+    const int t1 = min(T, t0 + tokens_per_wave);
+
+    LanePlan<K> P;
+    load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
+
+    const _Float16 *xg = X + (size_t)g * kGroup;
+    _Float16 *yg = Xr + (size_t)g * kGroup;
+    for (int t = t0; t < t1; t += kRotTU) {
+        float a[kRotTU], b[kRotTU];
+#pragma unroll
+        for (int u = 0; u < kRotTU; ++u) {
+            int tt = min(t + u, t1 - 1);
+            a[u] = (float)xg[(size_t)tt * ldx + P.in_a] * P.sia;
+            b[u] = (float)xg[(size_t)tt * ldx + P.in_b] * P.sib;
+        }
+        rotate_layers<K, kRotTU>(P, a, b);
+#pragma unroll
+        for (int u = 0; u < kRotTU; ++u) {
+            if (t + u < t1) {
+                yg[(size_t)(t + u) * ldxr + P.out_a] = (_Float16)(a[u] * P.soa);
+                yg[(size_t)(t + u) * ldxr + P.out_b] = (_Float16)(b[u] * P.sob);
+            }
+        }
+    }
+}
+
+template <int K>
+static hipError_t launch_rotate_k(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, paro_half_t *Xr,
+                                  int64_t ldxr, int T, hipStream_t s)
+{
+    int G = rot.c_in / kGroup;
+    // enough waves to fill 256 CUs several times over, but at least kRotTU tokens per wave
+    int tpw = 8;
+    while (tpw > 1 && (int64_t)G * ((T + tpw - 1) / tpw) < 4096) tpw >>= 1;
+    int waves_t = (T + tpw - 1) / tpw;
+    dim3 grid(G, (waves_t + kRotWaves - 1) / kRotWaves);
+    hipLaunchKernelGGL(rotate_planned_kernel<K>, grid, dim3(kRotWaves * 64), 0, s, (const uint32_t *)rot.plan,
+                       (const _Float16 *)X, ldx, (_Float16 *)Xr, ldxr, T, tpw);
+    return hipGetLastError();
+}
+
+hipError_t launch_rotate_planned(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, paro_half_t *Xr,
+                                 int64_t ldxr, int T, hipStream_t s)
+{
+    switch (rot.n_layers) {
+    case 0: return launch_rotate_k<0>(rot, X, ldx, Xr, ldxr, T, s);
+    case 1: return launch_rotate_k<1>(rot, X, ldx, Xr, ldxr, T, s);
+    case 2: return launch_rotate_k<2>(rot, X, ldx, Xr, ldxr, T, s);
+    case 3: return launch_rotate_k<3>(rot, X, ldx, Xr, ldxr, T, s);
+    case 4: return launch_rotate_k<4>(rot, X, ldx, Xr, ldxr, T, s);
+    case 5: return launch_rotate_k<5>(rot, X, ldx, Xr, ldxr, T, s);
+    case 6: return launch_rotate_k<6>(rot, X, ldx, Xr, ldxr, T, s);
+    case 7: return launch_rotate_k<7>(rot, X, ldx, Xr, ldxr, T, s);
+    default: return launch_rotate_k<8>(rot, X, ldx, Xr, ldxr, T, s);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic rotation kernel: reads pairs/theta directly (no plan).  One wave per block; the
+// group's 128 channels of one token live in LDS as fp32, each lane updates the pair of its
+// slot (Eq. 4), layers in array order (Eq. 5).  Slower; used when no plan was built.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void rotate_generic_kernel(const int16_t *__restrict__ pairs,
+                                                            const float *__restrict__ theta,
+                                                            const _Float16 *__restrict__ ch_scale, int n_layers,
+                                                            int ppl, int scale_order, const _Float16 *X, int64_t ldx,
+                                                            _Float16 *Xr, int64_t ldxr, int T, int tokens_per_block)
+{
+    __shared__ float s_c[kMaxLayers][64], s_s[kMaxLayers][64];
+    __shared__ int16_t s_i[kMaxLayers][64], s_j[kMaxLayers][64];
+    __shared__ float s_u[kGroup];
+    const int g = blockIdx.x, lane = threadIdx.x;
+    for (int l = 0; l < n_layers; ++l) {
+        int i = 0, j = 0;
+        float c = 1.0f, s = 0.0f;
+        if (lane < ppl) {
+            size_t k = ((size_t)g * n_layers + l) * ppl + lane;
+            i = pairs[2 * k]; j = pairs[2 * k + 1];
+            if (i < 0 || j < 0 || i >= kGroup || j >= kGroup) { i = 0; j = 0; }
+            if (i != j) {
+                double sd, cd;
+                sincos((double)theta[k], &sd, &cd);
+                c = (float)cd; s = (float)sd;
+            }
+        }
+        s_i[l][lane] = (int16_t)i; s_j[l][lane] = (int16_t)j; s_c[l][lane] = c; s_s[l][lane] = s;
+    }
+    float sc0 = 1.0f, sc1 = 1.0f;
+    if (ch_scale) { sc0 = (float)ch_scale[(size_t)g * kGroup + lane]; sc1 = (float)ch_scale[(size_t)g * kGroup + 64 + lane]; }
+    __syncthreads();
+    const int t0 = blockIdx.y * tokens_per_block, t1 = min(T, t0 + tokens_per_block);
+    for (int t = t0; t < t1; ++t) {
+        float v0 = (float)X[(size_t)t * ldx + (size_t)g * kGroup + lane];
+        float v1 = (float)X[(size_t)t * ldx + (size_t)g * kGroup + 64 + lane];
+        if (scale_order == 0) { v0 *= sc0; v1 *= sc1; }
+        s_u[lane] = v0; s_u[64 + lane] = v1;
+        __syncthreads();
+        for (int l = 0; l < n_layers; ++l) {
+            int i = s_i[l][lane], j = s_j[l][lane];
+            float ui = s_u[i], uj = s_u[j];
+            __syncthreads();
+            if (i != j) {
+                float c = s_c[l][lane], s = s_s[l][lane];
+                s_u[i] = c * ui - s * uj;
+                s_u[j] = s * ui + c * uj;
+            }
+            __syncthreads();
+        }
+        v0 = s_u[lane]; v1 = s_u[64 + lane];
+        if (scale_order == 1) { v0 *= sc0; v1 *= sc1; }
+        Xr[(size_t)t * ldxr + (size_t)g * kGroup + lane] = (_Float16)v0;
+        Xr[(size_t)t * ldxr + (size_t)g * kGroup + 64 + lane] = (_Float16)v1;
+        __syncthreads();
+    }
+}
+
+hipError_t launch_rotate_generic(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, paro_half_t *Xr,
+                                 int64_t ldxr, int T, hipStream_t s)
+{
+    int G = rot.c_in / kGroup;
+    int tpb = 16;
+    dim3 grid(G, (T + tpb - 1) / tpb);
+    hipLaunchKernelGGL(rotate_generic_kernel, grid, dim3(64), 0, s, rot.pairs, rot.theta,
+                       (const _Float16 *)rot.ch_scale, rot.n_layers, rot.pairs_per_layer, rot.scale_order,
+                       (const _Float16 *)X, ldx, (_Float16 *)Xr, ldxr, T, tpb);
+    return hipGetLastError();
+}
+
+}  // namespace paro

@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_10645_amd as paro
+from paper_2511_10645_amd import binding as B
+import paro_inputs as pin
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # non-NULL, 256-byte aligned; never dereferenced because validation fails first
+
+(OK, E_NULL, E_SHAPE, E_ALIGN, E_PAIRS, E_UNSUP, E_WS, E_HIP) = range(8)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "paro.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(paro_[a-z0-9_]+)\s*\(", hdr)))
+    assert len(names) >= 14
+    L = ctypes.CDLL(paro.lib_path())
+    for n in names:
+        assert hasattr(L, n), n
+    assert paro.paro_version() >= 100
+    assert "Def. 1" in paro.paro_status_string(E_PAIRS)
+
+
+def test_validate_pairs_host():
+    li = pin.make_linear(0, 0)
+    assert paro.paro_validate_pairs_host(li.pairs) == OK
+    dup = li.pairs.copy(); dup[1, 3, 5, 1] = dup[1, 3, 9, 0]
+    assert paro.paro_validate_pairs_host(dup) == E_PAIRS
+    oob = li.pairs.copy(); oob[0, 0, 0, 0] = 128
+    assert paro.paro_validate_pairs_host(oob) == E_PAIRS
+    neg = li.pairs.copy(); neg[0, 0, 0, 1] = -1
+    assert paro.paro_validate_pairs_host(neg) == E_PAIRS
+    # empty slots (i, i) name no channel, even when repeated
+    sent = li.pairs.copy(); sent[:, :, -2:, 1] = sent[:, :, -2:, 0]; sent[:, :, -1, :] = sent[:, :, -2, :]
+    assert paro.paro_validate_pairs_host(sent) == OK
+    assert paro.lib().paro_validate_pairs_host(None, 1, 1, 1, 128) == E_NULL
+
+
+def _rot(**kw):
+    d = dict(c_in=512, group=128, n_layers=8, pairs_per_layer=64, pairs=FAKE, theta=FAKE, ch_scale=FAKE,
+             scale_order=0, plan=None)
+    d.update(kw)
+    return B._CRotation(**d)
+
+
+def _w(**kw):
+    d = dict(c_in=512, c_out=512, group=128, qweight=FAKE, scales=FAKE, qzeros=FAKE, bias=None, packed=None)
+    d.update(kw)
+    return B._CW4Weight(**d)
+
+
+def test_rotate_scale_argument_errors():
+    L = paro.lib()
+    call = lambda r, X=FAKE, ldx=512, Xr=FAKE, ldxr=512, T=1: L.paro_rotate_scale(ctypes.byref(r), X, ldx, Xr, ldxr, T, None)
+    assert L.paro_rotate_scale(None, FAKE, 512, FAKE, 512, 1, None) == E_NULL
+    assert call(_rot(group=64)) == E_UNSUP
+    assert call(_rot(n_layers=9)) == E_UNSUP
+    assert call(_rot(pairs_per_layer=65)) == E_UNSUP
+    assert call(_rot(scale_order=2)) == E_UNSUP
+    assert call(_rot(c_in=500)) == E_SHAPE
+    assert call(_rot(pairs=None)) == E_NULL
+    assert call(_rot(), X=None) == E_NULL
+    assert call(_rot(), T=0) == E_SHAPE
+    assert call(_rot(), ldx=256) == E_SHAPE
+    assert call(_rot(), ldx=513) == E_ALIGN
+    assert call(_rot(), X=FAKE + 2) == E_ALIGN
+    assert call(_rot(plan=FAKE + 16)) == E_ALIGN
+    assert call(_rot(), Xr=FAKE, X=FAKE, ldx=512, ldxr=520) == E_SHAPE     # in place needs equal strides
+
+
+def test_linear_argument_errors_and_workspace():
+    L = paro.lib()
+    lin = lambda w, X=FAKE, ldx=512, Y=FAKE, ldy=512, T=1, ws=None, n=0: L.paro_w4a16_linear(
+        ctypes.byref(w), X, ldx, Y, ldy, T, ws, n, None)
+    assert lin(_w(group=32)) == E_UNSUP
+    assert lin(_w(c_out=520)) == E_SHAPE
+    assert lin(_w(c_in=640 + 64)) == E_SHAPE
+    assert lin(_w(qweight=None)) == E_NULL
+    assert lin(_w(), Y=None) == E_NULL
+    assert lin(_w(), ldy=256) == E_SHAPE
+    assert lin(_w(), ldx=516) == E_ALIGN
+    assert lin(_w(qweight=FAKE + 4)) == E_ALIGN
+    # a repacked 1024-channel weight needs the split-K workspace
+    w2 = _w(c_in=1024, packed=FAKE)
+    need = L.paro_workspace_bytes(None, ctypes.byref(w2), 1)
+    assert need >= 4096 + 2 * 1 * 512 * 4
+    assert lin(w2, ldx=1024) == E_WS
+    assert lin(w2, ldx=1024, ws=FAKE, n=need - 1) == E_WS
+    rl = lambda r, w, ws=FAKE, n=1 << 30: L.paro_rotated_linear(ctypes.byref(r), ctypes.byref(w), FAKE, 1024, FAKE, 512, 1, ws, n, None)
+    assert rl(_rot(c_in=512), w2) == E_SHAPE                       # rot.c_in != w.c_in
+    assert rl(_rot(c_in=1024), w2, ws=None, n=0) == E_WS
+    need_r = L.paro_workspace_bytes(ctypes.byref(_rot(c_in=1024)), ctypes.byref(w2), 3)
+    assert need_r >= L.paro_workspace_bytes(None, ctypes.byref(w2), 3) + 3 * 1024 * 2
+    assert L.paro_workspace_bytes(ctypes.byref(_rot(c_in=512)), ctypes.byref(w2), 1) == 0
+
+
+def test_prepare_calls_argument_errors():
+    L = paro.lib()
+    assert L.paro_rotation_plan_bytes(ctypes.byref(_rot())) == 4 * (5 + 3 * 8) * 64 * 4
+    assert L.paro_rotation_plan_bytes(ctypes.byref(_rot(group=100))) == 0
+    assert L.paro_rotation_plan_build(ctypes.byref(_rot()), None, None) == E_NULL
+    assert L.paro_rotation_plan_build(ctypes.byref(_rot()), FAKE + 8, None) == E_ALIGN
+    assert L.paro_w4_repack_bytes(ctypes.byref(_w())) == 32 * 4 * 1024 + 32 * 1 * 128 + 32 * 1 * 32
+    assert L.paro_w4_repack_bytes(ctypes.byref(_w(c_in=640))) == 0      # 5 groups: not whole 512-channel slices
+    assert L.paro_w4_repack(ctypes.byref(_w(c_in=640)), FAKE, None) == E_UNSUP
+    assert L.paro_w4_repack(ctypes.byref(_w(qweight=None, packed=FAKE)), FAKE, None) == E_NULL
+    assert L.paro_w4_unpack_codes(ctypes.byref(_w()), None, None) == E_NULL
+    assert L.paro_w4_dequant(ctypes.byref(_w()), FAKE + 2, None) == E_ALIGN

@@ -1,0 +1,312 @@
+"""GPU parity: the HIP path (through the C ABI binding) against the fp64 CPU oracle,
+element by element, on seeded inputs.
+
+  unpack / zero points / dequant : bit-exact
+  rotated activations            : within 2 fp16 ulp (tests/paro_tol.py states the floor)
+  linear outputs                 : |err| <= 5e-3 * ||w_row|| * ||u_t|| / sqrt(c_in)
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import paro_inputs as pin
+from paro_tol import linear_allowed, rotation_check
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    import paper_2511_10645_amd as paro
+    assert torch.cuda.is_available()
+    paro.lib()
+    return paro
+
+
+def dev(a):
+    import torch
+    return torch.as_tensor(np.ascontiguousarray(a)).cuda()
+
+
+def make_rot(P, li, plan=True, scale=True, scale_order=0):
+    r = P.Rotation(li.pairs, li.theta, li.ch_scale if scale else None, scale_order=scale_order)
+    if plan:
+        P.paro_rotation_plan_build(r)
+    return r
+
+
+def make_w(P, li, packed=True, bias=None):
+    w = P.W4Weight(li.qweight, li.scales, li.qzeros, bias=bias)
+    if packed:
+        P.paro_w4_repack(w)
+    return w
+
+
+# ----------------------------------------------------------------------------- bit-exact hooks
+
+@pytest.mark.parametrize("shape", [(512, 512), (1024, 16 * 37), (1536, 48)])
+def test_unpack_and_dequant_bit_exact(P, shape):
+    c_in, c_out = shape
+    say(f"hooks c_in={c_in} c_out={c_out}")
+    li = pin.make_custom(100 + c_in, 1, c_in, c_out)
+    want_codes = oracle.unpack_codes(li.qweight)
+    want_zeros = oracle.unpack_zeros(li.qzeros)
+    want_deq = oracle.round_fp16(oracle.dequant(li.qweight, li.scales, li.qzeros)).view(np.uint16)
+    assert np.array_equal(want_codes, li.codes) and np.array_equal(want_zeros, li.zeros)
+    for packed in (False, True):
+        w = make_w(P, li, packed=packed)
+        if packed:
+            w.drop_interchange()        # the hooks must read the repacked blob, not the original
+        assert np.array_equal(P.paro_w4_unpack_codes(w).cpu().numpy(), want_codes), f"codes packed={packed}"
+        assert np.array_equal(P.paro_w4_unpack_zeros(w).cpu().numpy(), want_zeros), f"zeros packed={packed}"
+        got = P.paro_w4_dequant(w).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, want_deq), f"dequant packed={packed}"
+
+
+def test_dequant_bit_exact_over_scale_range(P):
+    """Scales across the whole fp16 range (subnormal products, large products)."""
+    say("dequant scale sweep")
+    rng = np.random.default_rng(77)
+    li = pin.make_custom(78, 1, 512, 1024)
+    bits = rng.integers(0, 0x7800, size=li.scales.shape).astype(np.uint16)       # finite, up to 2^15
+    li.scales = bits.view(np.float16)
+    want = oracle.round_fp16(oracle.dequant(li.qweight, li.scales, li.qzeros)).view(np.uint16)
+    for packed in (False, True):
+        w = make_w(P, li, packed=packed)
+        assert np.array_equal(P.paro_w4_dequant(w).cpu().numpy().view(np.uint16), want)
+
+
+# ----------------------------------------------------------------------------- rotation
+
+def _check_rot(P, li, rot, ref, note, X=None):
+    import torch
+    x = dev(li.x) if X is None else X
+    got = P.paro_rotate_scale(rot, x).cpu().numpy()
+    ok, stats = rotation_check(got[:, :li.c_in], ref)
+    say(f"{note}: {stats}")
+    assert ok, (note, stats)
+    return stats
+
+
+@pytest.mark.parametrize("plan", [True, False])
+def test_rotate_config0(P, plan):
+    li = pin.make_linear(0, 0)
+    ref = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    stats = _check_rot(P, li, make_rot(P, li, plan=plan), ref, f"rotate config0 plan={plan}")
+    assert stats["frac_within_2ulp_strict"] > 0.98
+
+
+@pytest.mark.parametrize("plan", [True, False])
+@pytest.mark.parametrize("case", [
+    dict(T=37, c_in=384, K=8, P=64, scale=True, order=0),
+    dict(T=5, c_in=256, K=3, P=64, scale=True, order=1),
+    dict(T=19, c_in=256, K=8, P=40, scale=False, order=0),
+    dict(T=2, c_in=128, K=1, P=1, scale=True, order=0),
+    dict(T=130, c_in=640, K=5, P=17, scale=True, order=1),
+])
+def test_rotate_edge_shapes(P, plan, case):
+    li = pin.make_custom(500 + case["T"], case["T"], case["c_in"], 16, n_layers=case["K"],
+                         pairs_per_layer=case["P"], n_outlier=2)
+    cs = li.ch_scale if case["scale"] else None
+    ref = oracle.rotate_scale(li.x, li.pairs, li.theta, cs, scale_order=case["order"])
+    rot = make_rot(P, li, plan=plan, scale=case["scale"], scale_order=case["order"])
+    _check_rot(P, li, rot, ref, f"rotate {case} plan={plan}")
+
+
+def test_rotate_zero_layers_and_identity(P):
+    li = pin.make_custom(9, 4, 256, 16)
+    say("rotate K=0 / theta=0")
+    import torch
+    rot0 = P.Rotation(li.pairs[:, :0], li.theta[:, :0], li.ch_scale)
+    P.paro_rotation_plan_build(rot0)
+    ref = li.x.astype(np.float64) * li.ch_scale.astype(np.float64)
+    got = P.paro_rotate_scale(rot0, dev(li.x)).cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), oracle.round_fp16(ref).view(np.uint16))
+    rot1 = P.Rotation(li.pairs, np.zeros_like(li.theta), None)
+    P.paro_rotation_plan_build(rot1)
+    got = P.paro_rotate_scale(rot1, dev(li.x)).cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), li.x.view(np.uint16))       # identity transform is exact
+
+
+def test_rotate_in_place_and_strided(P):
+    import torch
+    li = pin.make_custom(10, 33, 384, 16, n_outlier=3)
+    ref = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    rot = make_rot(P, li)
+    say("rotate in place, ld > c_in")
+    buf = torch.zeros((33, 400), dtype=torch.float16, device="cuda")
+    buf[:, :384] = dev(li.x)
+    buf[:, 384:] = 7.0
+    view = buf[:, :384]
+    P.paro_rotate_scale(rot, view, view)
+    got = buf.cpu().numpy()
+    ok, stats = rotation_check(got[:, :384], ref)
+    assert ok, stats
+    assert (got[:, 384:] == 7.0).all()                                   # padding untouched
+
+
+# ----------------------------------------------------------------------------- linear
+
+def _linear_ref(li, u, bias=None):
+    y = oracle.linear(u, li.qweight, li.scales, li.qzeros, bias)
+    allowed = linear_allowed(oracle.row_sqnorms(li.qweight, li.scales, li.qzeros), u)
+    return y, allowed
+
+
+def _assert_linear(got16, y, allowed, note):
+    err = np.abs(got16.astype(np.float64) - y)
+    worst = float((err / allowed).max())
+    say(f"{note}: worst err/allowed = {worst:.3f}")
+    assert worst <= 1.0, (note, worst)
+    return worst
+
+
+@pytest.mark.parametrize("packed", [True, False])
+@pytest.mark.parametrize("case", [
+    dict(T=1, c_in=512, c_out=512),
+    dict(T=3, c_in=1024, c_out=16 * 37),
+    dict(T=16, c_in=1536, c_out=16 * 9),
+    dict(T=23, c_in=2048, c_out=16 * 21),
+])
+def test_bare_linear(P, packed, case):
+    li = pin.make_custom(700 + case["T"], case["T"], case["c_in"], case["c_out"], n_outlier=3)
+    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] == 3 else None
+    u = li.x.astype(np.float64)
+    y, allowed = _linear_ref(li, u, bias)
+    w = make_w(P, li, packed=packed, bias=bias)
+    ws = P.Workspace(P.paro_workspace_bytes(None, w, case["T"]))
+    got = P.paro_w4a16_linear(w, dev(li.x), ws).cpu().numpy()
+    _assert_linear(got, y, allowed, f"bare {case} packed={packed}")
+    assert int(ws.buf[:4096].sum().item()) == 0                          # counters back to zero
+
+
+@pytest.mark.parametrize("case", [
+    dict(T=1, c_in=512, c_out=512, plan=True, packed=True),
+    dict(T=1, c_in=2048, c_out=16 * 37, plan=True, packed=True),
+    dict(T=4, c_in=1024, c_out=16 * 13, plan=True, packed=True),
+    dict(T=7, c_in=1024, c_out=16 * 13, plan=True, packed=True),
+    dict(T=16, c_in=1536, c_out=256, plan=True, packed=True),
+    dict(T=40, c_in=512, c_out=16 * 5, plan=True, packed=True),
+    dict(T=2, c_in=1024, c_out=64, plan=False, packed=True),
+    dict(T=2, c_in=640, c_out=64, plan=True, packed=False),
+    dict(T=3, c_in=512, c_out=64, plan=False, packed=False),
+])
+def test_rotated_linear(P, case):
+    li = pin.make_custom(900 + case["T"] + case["c_in"], case["T"], case["c_in"], case["c_out"], n_outlier=3)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    y, allowed = _linear_ref(li, u)
+    rot = make_rot(P, li, plan=case["plan"])
+    w = make_w(P, li, packed=case["packed"])
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, case["T"]))
+    x = dev(li.x)
+    got = P.paro_rotated_linear(rot, w, x, ws)
+    _assert_linear(got.cpu().numpy(), y, allowed, f"rotated {case}")
+    # same call again on the same workspace: bit-identical (deterministic reduction, clean counters)
+    got2 = P.paro_rotated_linear(rot, w, x, ws)
+    assert (got == got2).all()
+
+
+def test_identity_transform_equals_bare_linear(P):
+    """theta = 0 and scale = 1: the fused call must give the bare linear's bits."""
+    li = pin.make_custom(31, 2, 1024, 256)
+    say("identity transform")
+    rot = P.Rotation(li.pairs, np.zeros_like(li.theta), None)
+    P.paro_rotation_plan_build(rot)
+    w = make_w(P, li)
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, 2))
+    a = P.paro_rotated_linear(rot, w, dev(li.x), ws)
+    b = P.paro_w4a16_linear(w, dev(li.x), ws)
+    assert (a == b).all()
+
+
+def test_tuning_knob_changes_only_summation_order(P):
+    li = pin.make_custom(32, 1, 2048, 16 * 50)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    y, allowed = _linear_ref(li, u)
+    rot, w = make_rot(P, li), make_w(P, li)
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, 1))
+    try:
+        for blocks in (8, 64, 4096):
+            P.paro_tune_decode_blocks(blocks)
+            got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
+            _assert_linear(got, y, allowed, f"decode blocks={blocks}")
+    finally:
+        P.paro_tune_decode_blocks(0)
+
+
+# ----------------------------------------------------------------------------- full configs
+
+def _full_config_case(P, config, linear, T, n_samples=4096):
+    """Full-size check in the launch configuration the benchmark times: rotation against the
+    oracle on every element, linear outputs on sampled (t, n) computed one by one."""
+    li = pin.make_linear(config, linear, tokens=T, keep_codes=False)
+    say(f"config {config} {li.shape.name} T={T} C={li.c_in} N={li.c_out}")
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    rot, w = make_rot(P, li), make_w(P, li)
+    x = dev(li.x)
+    xr = P.paro_rotate_scale(rot, x).cpu().numpy()
+    ok, stats = rotation_check(xr, u)
+    say(f"  rotation {stats}")
+    assert ok, stats
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, T))
+    w.drop_interchange()
+    got = P.paro_rotated_linear(rot, w, x, ws).cpu().numpy()
+    rng = np.random.default_rng(config * 10 + linear)
+    ns = min(n_samples, T * li.c_out)
+    t_idx = rng.integers(0, T, ns)
+    n_idx = rng.integers(0, li.c_out, ns)
+    n_idx[:16] = np.arange(li.c_out - 16, li.c_out)                  # always include the last tile
+    ys, ww = oracle.linear_samples(u, li.qweight, li.scales, li.qzeros, t_idx, n_idx)
+    allowed = 5e-3 * np.sqrt(ww) * np.linalg.norm(u, axis=1)[t_idx] / np.sqrt(li.c_in)
+    err = np.abs(got[t_idx, n_idx].astype(np.float64) - ys)
+    worst = float((err / allowed).max())
+    say(f"  linear worst err/allowed = {worst:.3f} over {ns} samples")
+    assert worst <= 1.0
+    assert np.isfinite(got.astype(np.float32)).all()
+    # the bare linear on the rotated fp16 activations, same samples (oracle fed with those bits)
+    yb = P.paro_w4a16_linear(w, dev(xr), ws).cpu().numpy()
+    ub = xr.astype(np.float64)
+    ys_b, _ = oracle.linear_samples(ub, li.qweight, li.scales, li.qzeros, t_idx, n_idx)
+    allowed_b = 5e-3 * np.sqrt(ww) * np.linalg.norm(ub, axis=1)[t_idx] / np.sqrt(li.c_in)
+    worst_b = float((np.abs(yb[t_idx, n_idx].astype(np.float64) - ys_b) / allowed_b).max())
+    say(f"  bare linear worst err/allowed = {worst_b:.3f}")
+    assert worst_b <= 1.0
+
+
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+def test_config1_decode_b1(P, linear):
+    _full_config_case(P, 1, linear, 1)
+
+
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+def test_config2_decode_b16(P, linear):
+    _full_config_case(P, 2, linear, 16)
+
+
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+def test_config3_prefill_2048(P, linear):
+    _full_config_case(P, 3, linear, 2048)
+
+
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+@pytest.mark.parametrize("T", [1, 4096])
+def test_config4_32b(P, linear, T):
+    _full_config_case(P, 4, linear, T)
+
+
+def test_config0_tiny_full(P):
+    li = pin.make_linear(0, 0)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    y, allowed = _linear_ref(li, u)
+    rot, w = make_rot(P, li), make_w(P, li)
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, 1))
+    got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
+    _assert_linear(got, y, allowed, "config0 fused")
