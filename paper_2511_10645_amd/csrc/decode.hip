@@ -15,12 +15,11 @@
 // -(64+z) (exact: small integers), four v_mfma_f32_16x16x32_f16, then the group's scale is
 // applied once to the fp32 tile sum:  y += s * sum_k (q - z) x'.
 //
-// Split-K reduction: each block stores fp32 partial tiles to the workspace; the last block to
-// finish an output range (atomic counter) adds the KS partials in a fixed order, adds the
-// bias, rounds to fp16 and resets counter and partials.  The result is deterministic.
-// Agent-scope release/acquire fences would cost an L2 write-back and invalidate per wave on
-// this multi-XCD part (measured: +40..85 us per launch), so none are used: each partial word
-// is its own full/empty flag.
+// Split-K reduction: each block stores fp32 partial tiles to the workspace, then sums its
+// share of the output range over the KS partials in a fixed order (deterministic), adds the
+// bias and rounds to fp16.  Agent-scope release/acquire fences would cost an L2 write-back and
+// invalidate per wave on this multi-XCD part (measured: +40..85 us per launch), so none are
+// used: each partial word is its own full/empty flag.
 #include "paro_internal.h"
 
 namespace paro {
@@ -34,22 +33,33 @@ constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * 64;
 constexpr int kSliceCh = kSliceGroups * kGroup;      // 512
 constexpr int kXPad = 8;                             // halfs of padding per LDS row
-constexpr size_t kCounterBytes = 4096;               // up to 1024 N-blocks
-constexpr int kReduceUnroll = 8;                     // partial words in flight per thread in the reduction
+constexpr int kReduceWords = 2048;                   // partial words gathered per reduction round (LDS floats)
 constexpr int kSpinLimit = 1 << 22;                  // bounded wait for a partial word to fill
 
 static int g_decode_target_blocks = 512;
 
 struct DecodeArgs {
-    PackedView pv;
+    const void *blob;            // repacked weight: tiles | scales | zeros
+    uint32_t blob_bytes, scales_off, zeros_off;
     const _Float16 *X; int64_t ldx;
     _Float16 *Y; int64_t ldy;
     const _Float16 *bias;
     const uint32_t *plan;
     float *partial;
-    uint32_t *counters;
     int T, C, N, G, NT, KS, tiles_per_block;
 };
+
+// Raw buffer resources (stride 0): an access whose byte offset lies beyond num_records returns 0
+// (loads) or is dropped (stores).  Predication by offset keeps every memory instruction of the
+// stream loop unconditional, so the outstanding-load count is static and the compiler can wait
+// for exactly the stage it needs while later stages stay in flight.
+constexpr uint32_t kOob = 0x80000000u;
+constexpr int kRsrcFlags = 0x00020000;        // 32-bit data format field of a gfx9-family raw buffer
+constexpr int kAuxSc1 = 16;                   // agent-scope (write-through / cache-bypassing) access
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, kRsrcFlags);
+}
 
 struct Stage {
     u32x4 w[kSliceGroups];
@@ -57,18 +67,20 @@ struct Stage {
     uint32_t zq;
 };
 
-__device__ inline void load_stage(const DecodeArgs &a, int nt, int ks, int lane, Stage &st)
+// tile < 0 loads nothing (all zeros)
+__device__ inline void load_stage(__amdgpu_buffer_rsrc_t blob, const DecodeArgs &a, int tile, int ks, int lane,
+                                  Stage &st)
 {
-    const u32x4 *base = (const u32x4 *)a.pv.tiles + ((size_t)nt * a.G + (size_t)ks * kSliceGroups) * 64 + lane;
+    const bool ok = tile >= 0;
+    const uint32_t toff = ok ? (((uint32_t)tile * a.G + (uint32_t)ks * kSliceGroups) * 64u + lane) * 16u : kOob;
 #pragma unroll
-#ifdef PARO_EXP_NO_NT
-    for (int gi = 0; gi < kSliceGroups; ++gi) st.w[gi] = base[gi * 64];
-#else
-    for (int gi = 0; gi < kSliceGroups; ++gi) st.w[gi] = __builtin_nontemporal_load(base + gi * 64);
-#endif
-    size_t sidx = ((size_t)nt * a.KS + ks) * kTileN + (lane & 15);
-    st.sc = a.pv.scales[sidx];
-    st.zq = a.pv.zeros[sidx];
+    for (int gi = 0; gi < kSliceGroups; ++gi)
+        st.w[gi] = __builtin_amdgcn_raw_buffer_load_b128(blob, (int)(toff + gi * 1024u), 0, 0);
+    const uint32_t sidx = ((uint32_t)tile * a.KS + ks) * kTileN + (lane & 15);
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 sc = __builtin_amdgcn_raw_buffer_load_b64(blob, ok ? (int)(a.scales_off + sidx * 8u) : (int)kOob, 0, 0);
+    st.sc = make_uint2(sc[0], sc[1]);
+    st.zq = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(blob, ok ? (int)(a.zeros_off + sidx * 2u) : (int)kOob, 0, 0);
 }
 
 __device__ inline half2v as_h2(uint32_t u) { union { uint32_t u; half2v h; } c; c.u = u; return c.h; }
@@ -102,21 +114,24 @@ __device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGrou
     return tot;
 }
 
-// K >= 0: rotation with K layers fused; K < 0: bare linear on X.
-template <int K>
+// K >= 0: rotation with K layers fused; K < 0: bare linear on X.  SPLIT: more than one K-slice.
+template <int K, bool SPLIT>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
 {
     __shared__ _Float16 s_x[16][kSliceCh + kXPad];
-    __shared__ int s_last;
+    __shared__ float s_red[kReduceWords];
     const int ks = blockIdx.x, nb = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tile_lo = nb * a.tiles_per_block;
     const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
+    const int n_iter = (tile_hi - tile_lo + kDecWaves - 1) / kDecWaves;      // same for all waves of the block
+    auto tile_of = [&](int i) {                                              // -1: nothing to do
+        int t = tile_lo + wave + i * kDecWaves;
+        return (i < n_iter && t < tile_hi) ? t : -1;
+    };
+    const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
 
-    // start the weight stream before anything else
-    Stage st0, st1;
-    int nt = tile_lo + wave;
-    if (nt < tile_hi) load_stage(a, nt, ks, lane, st0);
+    Stage st0, st1, st2;
 
     // ---- activations of this K-slice -> MFMA A fragments ---------------------------------
     half8 xf[kSliceGroups][4];
@@ -140,6 +155,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
             const uint32_t *row = gplan + (size_t)(kPlanHeadRows + kPlanRowsPerLayer * l) * 64;
             pc[l] = __uint_as_float(row[lane]); ps[l] = __uint_as_float(row[64 + lane]); pm[l] = row[128 + lane];
         }
+        // The weight stream starts here, behind the (older, L2-resident) plan and X loads: vector
+        // memory returns in order, so waiting for the plan must not mean waiting for HBM tiles.
+        load_stage(blob, a, tile_of(0), ks, lane, st0);
+        load_stage(blob, a, tile_of(1), ks, lane, st1);
         const int in_a = io & 0xff, in_b = (io >> 8) & 0xff, out_a = (io >> 16) & 0xff, out_b = io >> 24;
         for (int t = 0; t < a.T; ++t) {
             float va = (float)s_x[t][gi * kGroup + in_a] * sia;
@@ -171,95 +190,99 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
                 xf[g2][j] = v;
             }
     } else {
+        // rows >= T lie beyond the resource: they read as zero
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
+        const uint32_t xoff = ft < a.T ? (uint32_t)(((size_t)ft * a.ldx + c0 + fkb * 32) * 2) : kOob;
 #pragma unroll
         for (int g2 = 0; g2 < kSliceGroups; ++g2)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (ft < a.T) v = *(const half8 *)(a.X + (size_t)ft * a.ldx + c0 + g2 * kGroup + fkb * 32 + j * 8);
-                xf[g2][j] = v;
+                union { u32x4 u; half8 h; } v;
+                v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
+                xf[g2][j] = v.h;
             }
+        load_stage(blob, a, tile_of(0), ks, lane, st0);
+        load_stage(blob, a, tile_of(1), ks, lane, st1);
     }
 
-    // ---- stream the tiles: two register stages, the next tile is in flight while this one is used
+    // ---- stream the tiles: three register stages, two tiles in flight while one is used -----
     const int n_in_tile = lane & 15, tq = lane >> 4;
+    const __amdgpu_buffer_rsrc_t yr = make_rsrc(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
+    const __amdgpu_buffer_rsrc_t pr = make_rsrc(a.partial, SPLIT ? (uint32_t)((size_t)a.KS * a.T * a.N * 4) : 0u);
+    const __amdgpu_buffer_rsrc_t br = make_rsrc(a.bias, a.bias ? (uint32_t)a.N * 2u : 0u);      // no bias: reads 0
     auto emit = [&](const Stage &stg, int tile) {
         float4v tot = tile_dot(stg, xf);
-        const size_t n = (size_t)tile * kTileN + n_in_tile;
-        if (a.KS == 1) {
-            float bv = a.bias ? (float)a.bias[n] : 0.f;
+        const uint32_t n = (uint32_t)tile * kTileN + n_in_tile;
+        if constexpr (!SPLIT) {
+            union { uint16_t u; _Float16 h; } bb;
+            bb.u = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(br, tile >= 0 ? (int)(n * 2u) : (int)kOob, 0, 0);
+            const float bv = (float)bb.h;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 int t = tq * 4 + r;
-                if (t < a.T) a.Y[(size_t)t * a.ldy + n] = (_Float16)(tot[r] + bv);
+                union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(tot[r] + bv);
+                uint32_t off = (tile >= 0 && t < a.T) ? (uint32_t)(((size_t)t * a.ldy + n) * 2) : kOob;
+                __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
             }
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 int t = tq * 4 + r;
-                if (t < a.T) {
-                    uint32_t bits = __float_as_uint(tot[r]);
-                    if ((bits << 1) == 0u) bits = 0x80000000u;      // +-0 is stored as -0: 0 means "empty"
-                    __hip_atomic_store((uint32_t *)(a.partial + ((size_t)ks * a.T + t) * a.N + n), bits,
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+                uint32_t bits = __float_as_uint(tot[r]);
+                if ((bits << 1) == 0u) bits = 0x80000000u;      // +-0 is stored as -0: 0 means "empty"
+                uint32_t off = (tile >= 0 && t < a.T) ? (uint32_t)((((size_t)ks * a.T + t) * a.N + n) * 4) : kOob;
+                __builtin_amdgcn_raw_buffer_store_b32(bits, pr, (int)off, 0, kAuxSc1);
             }
         }
     };
-    while (nt < tile_hi) {
-        int nxt = nt + kDecWaves;
-        if (nxt < tile_hi) load_stage(a, nxt, ks, lane, st1);
-        emit(st0, nt);
-        nt = nxt;
-        if (nt >= tile_hi) break;
-        nxt = nt + kDecWaves;
-        if (nxt < tile_hi) load_stage(a, nxt, ks, lane, st0);
-        emit(st1, nt);
-        nt = nxt;
+    for (int i = 0; i < n_iter; i += 3) {
+        load_stage(blob, a, tile_of(i + 2), ks, lane, st2);
+        emit(st0, tile_of(i));
+        if (i + 1 >= n_iter) break;
+        load_stage(blob, a, tile_of(i + 3), ks, lane, st0);
+        emit(st1, tile_of(i + 1));
+        if (i + 2 >= n_iter) break;
+        load_stage(blob, a, tile_of(i + 4), ks, lane, st1);
+        emit(st2, tile_of(i + 2));
     }
 
-    // ---- split-K: the last block of this output range reduces --------------------------------
-    // No fences: every partial word carries its own "full" state (0 = empty, values are never
-    // stored as +0), is written and read with agent-scope atomic accesses, and is reset to
-    // empty by the reader.  The arrival counter only elects the reader.
+    // ---- split-K reduction, spread over the KS blocks of this output range -------------------
+    // The T*width outputs of the range are cut into KS contiguous shares; block ks sums the KS
+    // partials of its share in a fixed order (deterministic), adds the bias and stores fp16.
+    // No fences and no counters: every partial word is its own full/empty flag (0 = empty; a
+    // value is never stored as +0), written and read with agent-scope accesses and reset to
+    // empty by its reader.  A reader polls a word until it fills; the writers are the blocks
+    // dispatched next to it, which never wait on anything before writing.
 #ifndef PARO_EXP_NO_FINALIZE
-    if (a.KS > 1) {
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t old = __hip_atomic_fetch_add(a.counters + nb, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (old == (uint32_t)(a.KS - 1));
-        }
-        __syncthreads();
-        if (s_last) {
-            const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
-            for (int idx = threadIdx.x; idx < a.T * width; idx += kDecThreads) {
-                int t = idx / width, n = n_lo + idx % width;
+    if constexpr (SPLIT) {
+        const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
+        const int outputs = a.T * width;
+        const int share = (outputs + a.KS - 1) / a.KS;
+        const int o_lo = ks * share, o_hi = min(outputs, o_lo + share);
+        const int round_outputs = kReduceWords / a.KS;
+        for (int base = o_lo; base < o_hi; base += round_outputs) {
+            const int n_out = min(round_outputs, o_hi - base);
+            __syncthreads();
+            for (int j = threadIdx.x; j < n_out * a.KS; j += kDecThreads) {
+                const int o = base + j / a.KS, k2 = j % a.KS;
+                const int t = o / width, n = n_lo + o % width;
+                uint32_t *p = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
+                uint32_t bits = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int spin = 0; bits == 0u && spin < kSpinLimit; ++spin)
+                    bits = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // a word that never filled is reported as NaN, not as a silent zero
+                s_red[j] = bits == 0u ? __builtin_nanf("") : __uint_as_float(bits);
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < n_out; i += kDecThreads) {
+                const int o = base + i;
+                const int t = o / width, n = n_lo + o % width;
                 float sum = 0.f;
-                for (int k0 = 0; k0 < a.KS; k0 += kReduceUnroll) {
-                    uint32_t bits[kReduceUnroll];
-#pragma unroll
-                    for (int j = 0; j < kReduceUnroll; ++j) {
-                        uint32_t *p = (uint32_t *)(a.partial + ((size_t)(k0 + j) * a.T + t) * a.N + n);
-                        bits[j] = (k0 + j < a.KS) ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                                  : 0x80000000u;
-                    }
-#pragma unroll
-                    for (int j = 0; j < kReduceUnroll; ++j) {
-                        if (k0 + j < a.KS) {
-                            uint32_t *p = (uint32_t *)(a.partial + ((size_t)(k0 + j) * a.T + t) * a.N + n);
-                            for (int spin = 0; bits[j] == 0u && spin < kSpinLimit; ++spin)
-                                bits[j] = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            // a word that never filled is reported as NaN, not as a silent zero
-                            sum += bits[j] == 0u ? __builtin_nanf("") : __uint_as_float(bits[j]);
-                        }
-                    }
-                }
+                for (int k2 = 0; k2 < a.KS; ++k2) sum += s_red[i * a.KS + k2];
                 if (a.bias) sum += (float)a.bias[n];
                 a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
             }
-            if (threadIdx.x == 0)
-                __hip_atomic_store(a.counters + nb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 #endif
@@ -279,14 +302,15 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T)
     d.nb = (NT + tpb - 1) / tpb;
     int t16 = T < 16 ? T : 16;
     d.partial_bytes = d.ks > 1 ? (size_t)d.ks * t16 * c_out * sizeof(float) : 0;
-    d.counter_bytes = d.ks > 1 ? kCounterBytes : 0;
+    d.counter_bytes = 0;
     return d;
 }
 
 template <int K>
 static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_kernel<K>, dim3(d.ks, d.nb), dim3(kDecThreads), 0, s, a);
+    if (d.ks > 1) hipLaunchKernelGGL((decode_kernel<K, true>), dim3(d.ks, d.nb), dim3(kDecThreads), 0, s, a);
+    else          hipLaunchKernelGGL((decode_kernel<K, false>), dim3(d.ks, d.nb), dim3(kDecThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -294,14 +318,18 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
                          paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s)
 {
     DecodeGeometry d = decode_geometry(w.c_in, w.c_out, T);
-    if ((size_t)d.nb * sizeof(uint32_t) > kCounterBytes) return hipErrorInvalidValue;
+    if (d.ks > kReduceWords) return hipErrorInvalidValue;
+    if (packed_tiles_bytes(w.c_in, w.c_out) + packed_scales_bytes(w.c_in, w.c_out) + packed_zeros_bytes(w.c_in, w.c_out) >= (1ull << 31))
+        return hipErrorInvalidValue;   // 32-bit buffer offsets
     DecodeArgs a;
-    a.pv = packed_view(w.packed, w.c_in, w.c_out);
+    a.blob = w.packed;
+    a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);
+    a.zeros_off = a.scales_off + (uint32_t)packed_scales_bytes(w.c_in, w.c_out);
+    a.blob_bytes = a.zeros_off + (uint32_t)packed_zeros_bytes(w.c_in, w.c_out);
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
     a.plan = rot ? (const uint32_t *)rot->plan : nullptr;
-    a.counters = (uint32_t *)ws;
-    a.partial = (float *)((char *)ws + kCounterBytes);
+    a.partial = (float *)ws;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN; a.KS = d.ks;
     a.tiles_per_block = d.tiles_per_block;
     if (!rot) return launch_decode_k<-1>(a, d, s);

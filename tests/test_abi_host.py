@@ -91,7 +91,7 @@ def test_linear_argument_errors_and_workspace():
     # a repacked 1024-channel weight needs the split-K workspace
     w2 = _w(c_in=1024, packed=FAKE)
     need = L.paro_workspace_bytes(None, ctypes.byref(w2), 1)
-    assert need >= 4096 + 2 * 1 * 512 * 4
+    assert need >= 2 * 1 * 512 * 4
     assert lin(w2, ldx=1024) == E_WS
     assert lin(w2, ldx=1024, ws=FAKE, n=need - 1) == E_WS
     rl = lambda r, w, ws=FAKE, n=1 << 30: L.paro_rotated_linear(ctypes.byref(r), ctypes.byref(w), FAKE, 1024, FAKE, 512, 1, ws, n, None)
