@@ -47,7 +47,7 @@ def main() -> int:
     ap.add_argument("--pool-mb", type=int, default=1200, help="minimum total size of the weight-copy pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
-    ap.add_argument("--decode-blocks", type=int, default=0, help="tuning knob (0 = library default)")
+    ap.add_argument("--decode-waves", type=int, default=0, help="tuning knob (0 = library default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it", file=sys.stderr)
@@ -62,8 +62,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     paro.lib()
-    if args.decode_blocks:
-        paro.paro_tune_decode_blocks(args.decode_blocks)
+    if args.decode_waves:
+        paro.paro_tune_decode_waves(args.decode_waves)
     cfg = pin.CONFIGS[args.config]
     T = cfg.tokens[0]
     dev = "cuda"

@@ -145,10 +145,9 @@ paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *strea
 
 /* Diagnostics ---------------------------------------------------------------------------- */
 
-/* Tuning knob for experiments: target number of workgroups of a decode launch (<= 0 restores
- * the default).  Process-wide and not thread-safe; results do not depend on it beyond fp32
- * summation order. */
-void paro_tune_decode_blocks(int blocks);
+/* Tuning knob for experiments: target number of wavefronts of a decode launch (<= 0 restores
+ * the default).  Process-wide and not thread-safe; results do not depend on it. */
+void paro_tune_decode_waves(int waves);
 
 #ifdef __cplusplus
 }

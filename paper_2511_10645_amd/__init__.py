@@ -14,7 +14,7 @@ from .binding import (  # noqa: F401
     paro_rotated_linear,
     paro_rotation_plan_build,
     paro_status_string,
-    paro_tune_decode_blocks,
+    paro_tune_decode_waves,
     paro_validate_pairs_host,
     paro_version,
     paro_w4_dequant,

@@ -69,8 +69,8 @@ def lib():
         L.paro_w4_unpack_codes.argtypes = [wp, vp, vp]
         L.paro_w4_unpack_zeros.argtypes = [wp, vp, vp]
         L.paro_w4_dequant.argtypes = [wp, vp, vp]
-        L.paro_tune_decode_blocks.argtypes = [ctypes.c_int]
-        L.paro_tune_decode_blocks.restype = None
+        L.paro_tune_decode_waves.argtypes = [ctypes.c_int]
+        L.paro_tune_decode_waves.restype = None
         for name in ("paro_validate_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant"):
@@ -108,8 +108,8 @@ def paro_validate_pairs_host(pairs: np.ndarray, group: int = 128) -> int:
     return lib().paro_validate_pairs_host(p.ctypes.data, G, K, P, group)
 
 
-def paro_tune_decode_blocks(blocks: int) -> None:
-    lib().paro_tune_decode_blocks(int(blocks))
+def paro_tune_decode_waves(blocks: int) -> None:
+    lib().paro_tune_decode_waves(int(blocks))
 
 
 class Rotation:

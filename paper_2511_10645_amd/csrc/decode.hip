@@ -10,10 +10,10 @@
 // wavefront per (token, group), see rotate.hip) - the prologue costs one group-rotation per
 // wave however wide the layer is, and runs while the first weight tiles are in flight.
 //
-// Inner loop per 16x128 tile and lane: one 16-byte load (32 codes), and-or with the fp16
-// magic numbers 1024 / 64 (code lands in the mantissa), one packed fp16 add of -(1024+z) /
-// -(64+z) (exact: small integers), four v_mfma_f32_16x16x32_f16, then the group's scale is
-// applied once to the fp32 tile sum:  y += s * sum_k (q - z) x'.
+// Inner loop per 16x128 tile and lane: one 16-byte load (32 codes), v_and_or_b32 with the fp16
+// magic numbers 1024 / 64 (the code lands in the mantissa: 5 VALU ops per 8 weights), four
+// v_mfma_f32_16x16x32_f16 whose accumulator starts at the bias / zero-point correction (see
+// tile_dot), then the group's scale is applied once to the fp32 sum:  y += s * sum_k (q - z) x'.
 //
 // Split-K reduction: each block stores fp32 partial tiles to the workspace, then sums its
 // share of the output range over the KS partials in a fixed order (deterministic), adds the
@@ -33,10 +33,11 @@ constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * 64;
 constexpr int kSliceCh = kSliceGroups * kGroup;      // 512
 constexpr int kXPad = 8;                             // halfs of padding per LDS row
-constexpr int kReduceWords = 2048;                   // partial words gathered per reduction round (LDS floats)
+constexpr int kReducePerThread = 4;                   // partial words requested per thread and round
+constexpr int kReduceWords = kReducePerThread * 256;  // partial words gathered per reduction round (LDS floats)
 constexpr int kSpinLimit = 1 << 22;                  // bounded wait for a partial word to fill
 
-static int g_decode_target_blocks = 512;
+static int g_decode_target_blocks = 0;      // 0: choose by size (see decode_geometry)
 
 struct DecodeArgs {
     const void *blob;            // repacked weight: tiles | scales | zeros
@@ -86,36 +87,63 @@ __device__ inline void load_stage(__amdgpu_buffer_rsrc_t blob, const DecodeArgs 
 __device__ inline half2v as_h2(uint32_t u) { union { uint32_t u; half2v h; } c; c.u = u; return c.h; }
 __device__ inline uint32_t as_u32(half2v h) { union { uint32_t u; half2v h; } c; c.h = h; return c.u; }
 
-// sum over the slice's 4 groups of s_g * sum_k (q - z_g) x'  for one 16-row tile
-__device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGroups][4])
+// (a & mask) | magic in one VALU op.  GFX9-family VOP3 encodings take no literals, so the
+// compiler splits the expression into two VOP2 ops with literals; operands held in registers
+// keep it at one.
+__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(mask), "v"(magic));
+    return r;
+}
+
+struct DequantConsts {
+    uint32_t m_lo, m_hi, k_lo, k_hi;     // 0x000F000F, 0x00F000F0, 0x64006400 (1024.0 x2), 0x54005400 (64.0 x2)
+};
+
+// Sum over the slice's 4 groups of s_g * sum_k (q - z_g) x' for one 16-row tile.
+//
+// The codes are turned into fp16 by or-ing them into the mantissa of 1024.0 (low nibble of a
+// byte) or 64.0 (high nibble): B holds b_k + q with b_k in {1024, 64}.  Instead of subtracting
+// b_k + z from every weight, the MFMA accumulator starts at
+//      -(sum_k b_k x'_k) - z * (sum_k x'_k)  =  nb1 + z * nb2
+// (two per-token, per-group sums computed once per block), so that after the four MFMAs it
+// holds sum_k (q - z) x'.  fp32 accumulation: the bias inflates partial sums by <= 1039x, which
+// costs ~2^-24 * 1039 relative to the group's |x'| mass - far inside the output tolerance.
+// T1: one token, only accumulator row 0 is live.
+template <bool T1>
+__device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGroups][4],
+                                   const float4v (&nb1)[kSliceGroups], const float4v (&nb2)[kSliceGroups],
+                                   const DequantConsts &k)
 {
     float4v tot = {0.f, 0.f, 0.f, 0.f};
     union { uint2 v; _Float16 h[4]; } sc; sc.v = st.sc;
 #pragma unroll
     for (int gi = 0; gi < kSliceGroups; ++gi) {
-        uint32_t z = (st.zq >> (4 * gi)) & 15u;
-        half2v nlo = as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
-        half2v nhi = as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
+        const float zf = (float)((st.zq >> (4 * gi)) & 15u);
+        float4v acc;
+        if constexpr (T1) { acc[0] = zf * nb2[gi][0] + nb1[gi][0]; acc[1] = acc[2] = acc[3] = 0.f; }
+        else acc = zf * nb2[gi] + nb1[gi];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint32_t u = st.w[gi][j];
+            const uint32_t u = st.w[gi][j], t = u >> 8;
             union { uint32_t d[4]; half8 h; } b;
-            b.d[0] = as_u32(as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo);
-            b.d[1] = as_u32(as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi);
-            u >>= 8;
-            b.d[2] = as_u32(as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo);
-            b.d[3] = as_u32(as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi);
+            b.d[0] = and_or(u, k.m_lo, k.k_lo);
+            b.d[1] = and_or(u, k.m_hi, k.k_hi);
+            b.d[2] = and_or(t, k.m_lo, k.k_lo);
+            b.d[3] = and_or(t, k.m_hi, k.k_hi);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[gi][j], b.h, acc, 0, 0, 0);
         }
-        float s = (float)sc.h[gi];
-        tot += s * acc;
+        const float s = (float)sc.h[gi];
+        if constexpr (T1) tot[0] += s * acc[0];
+        else tot += s * acc;
     }
     return tot;
 }
 
 // K >= 0: rotation with K layers fused; K < 0: bare linear on X.  SPLIT: more than one K-slice.
-template <int K, bool SPLIT>
+// T1: exactly one token.
+template <int K, bool SPLIT, bool T1>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
 {
     __shared__ _Float16 s_x[16][kSliceCh + kXPad];
@@ -205,20 +233,39 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
         load_stage(blob, a, tile_of(1), ks, lane, st1);
     }
 
+    // per token and group: nb1 = -sum_k b_k x'_k, nb2 = -sum_k x'_k, as MFMAs against constant
+    // operands whose 16 columns are equal - every lane gets the sums of its own 4 token rows
+    float4v nb1[kSliceGroups], nb2[kSliceGroups];
+    {
+        const half8 cb1 = {-1024, -1024, -64, -64, -1024, -1024, -64, -64};
+        const half8 cb2 = {-1, -1, -1, -1, -1, -1, -1, -1};
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+            float4v s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb1, s1, 0, 0, 0);
+                s2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb2, s2, 0, 0, 0);
+            }
+            nb1[g2] = s1; nb2[g2] = s2;
+        }
+    }
+    DequantConsts dq = {0x000F000Fu, 0x00F000F0u, 0x64006400u, 0x54005400u};
+
     // ---- stream the tiles: three register stages, two tiles in flight while one is used -----
     const int n_in_tile = lane & 15, tq = lane >> 4;
     const __amdgpu_buffer_rsrc_t yr = make_rsrc(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
     const __amdgpu_buffer_rsrc_t pr = make_rsrc(a.partial, SPLIT ? (uint32_t)((size_t)a.KS * a.T * a.N * 4) : 0u);
     const __amdgpu_buffer_rsrc_t br = make_rsrc(a.bias, a.bias ? (uint32_t)a.N * 2u : 0u);      // no bias: reads 0
     auto emit = [&](const Stage &stg, int tile) {
-        float4v tot = tile_dot(stg, xf);
+        float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
         const uint32_t n = (uint32_t)tile * kTileN + n_in_tile;
         if constexpr (!SPLIT) {
             union { uint16_t u; _Float16 h; } bb;
             bb.u = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(br, tile >= 0 ? (int)(n * 2u) : (int)kOob, 0, 0);
             const float bv = (float)bb.h;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < (T1 ? 1 : 4); ++r) {
                 int t = tq * 4 + r;
                 union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(tot[r] + bv);
                 uint32_t off = (tile >= 0 && t < a.T) ? (uint32_t)(((size_t)t * a.ldy + n) * 2) : kOob;
@@ -226,7 +273,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
             }
         } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < (T1 ? 1 : 4); ++r) {
                 int t = tq * 4 + r;
                 uint32_t bits = __float_as_uint(tot[r]);
                 if ((bits << 1) == 0u) bits = 0x80000000u;      // +-0 is stored as -0: 0 means "empty"
@@ -263,23 +310,40 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
         for (int base = o_lo; base < o_hi; base += round_outputs) {
             const int n_out = min(round_outputs, o_hi - base);
             __syncthreads();
-            for (int j = threadIdx.x; j < n_out * a.KS; j += kDecThreads) {
-                const int o = base + j / a.KS, k2 = j % a.KS;
+            // all of a thread's words are requested before any is examined: one round trip
+            uint32_t bits[kReducePerThread];
+            uint32_t *ptr[kReducePerThread];
+#pragma unroll
+            for (int u = 0; u < kReducePerThread; ++u) {
+                const int j = threadIdx.x + u * kDecThreads;
+                const bool on = j < n_out * a.KS;
+                // consecutive threads take consecutive outputs of one K-slice: coalesced requests
+                const int o = base + (on ? j % n_out : 0), k2 = on ? j / n_out : 0;
                 const int t = o / width, n = n_lo + o % width;
-                uint32_t *p = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
-                uint32_t bits = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                for (int spin = 0; bits == 0u && spin < kSpinLimit; ++spin)
-                    bits = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                // a word that never filled is reported as NaN, not as a silent zero
-                s_red[j] = bits == 0u ? __builtin_nanf("") : __uint_as_float(bits);
+                ptr[u] = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
+                bits[u] = on ? __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
+            }
+#pragma unroll
+            for (int u = 0; u < kReducePerThread; ++u) {
+                const int j = threadIdx.x + u * kDecThreads;
+                if (j < n_out * a.KS) {
+#ifndef PARO_EXP_NO_SPIN
+                    for (int spin = 0; bits[u] == 0u && spin < kSpinLimit; ++spin)
+                        bits[u] = __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
+#ifndef PARO_EXP_NO_RESET
+                    __hip_atomic_store(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
+                    // a word that never filled is reported as NaN, not as a silent zero
+                    s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
+                }
             }
             __syncthreads();
             for (int i = threadIdx.x; i < n_out; i += kDecThreads) {
                 const int o = base + i;
                 const int t = o / width, n = n_lo + o % width;
                 float sum = 0.f;
-                for (int k2 = 0; k2 < a.KS; ++k2) sum += s_red[i * a.KS + k2];
+                for (int k2 = 0; k2 < a.KS; ++k2) sum += s_red[k2 * n_out + i];
                 if (a.bias) sum += (float)a.bias[n];
                 a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
             }
@@ -294,7 +358,11 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T)
     int G = c_in / kGroup, NT = c_out / kTileN;
     d.ks = G / kSliceGroups;
     d.waves = kDecWaves;
-    int nb = g_decode_target_blocks / d.ks;
+    // measured on MI355X: one 4-wave block per CU for the small linears (the prologue is repeated
+    // less often), two per CU once the weight stream exceeds ~24 MB
+    int target = g_decode_target_blocks;
+    if (target <= 0) target = packed_tiles_bytes(c_in, c_out) >= (24u << 20) ? 512 : 256;
+    int nb = target / d.ks;
     if (nb < 1) nb = 1;
     int tpb = (NT + nb - 1) / nb;
     tpb = (tpb + kDecWaves - 1) / kDecWaves * kDecWaves;     // whole rounds of the block's waves
@@ -309,8 +377,14 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T)
 template <int K>
 static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, hipStream_t s)
 {
-    if (d.ks > 1) hipLaunchKernelGGL((decode_kernel<K, true>), dim3(d.ks, d.nb), dim3(kDecThreads), 0, s, a);
-    else          hipLaunchKernelGGL((decode_kernel<K, false>), dim3(d.ks, d.nb), dim3(kDecThreads), 0, s, a);
+    const dim3 grid(d.ks, d.nb), block(kDecThreads);
+    if (a.T == 1) {
+        if (d.ks > 1) hipLaunchKernelGGL((decode_kernel<K, true, true>), grid, block, 0, s, a);
+        else          hipLaunchKernelGGL((decode_kernel<K, false, true>), grid, block, 0, s, a);
+    } else {
+        if (d.ks > 1) hipLaunchKernelGGL((decode_kernel<K, true, false>), grid, block, 0, s, a);
+        else          hipLaunchKernelGGL((decode_kernel<K, false, false>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
@@ -394,6 +468,6 @@ hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, 
     return hipGetLastError();
 }
 
-void set_decode_target_blocks(int blocks) { g_decode_target_blocks = blocks > 0 ? blocks : 512; }
+void set_decode_target_waves(int waves) { g_decode_target_blocks = waves > 0 ? (waves + kDecWaves - 1) / kDecWaves : 0; }
 
 }  // namespace paro

@@ -5,7 +5,7 @@
 using namespace paro;
 
 namespace paro {
-void set_decode_target_blocks(int blocks);
+void set_decode_target_waves(int blocks);
 }
 
 namespace {
@@ -253,7 +253,7 @@ paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *strea
     return from_hip(launch_dequant(*w, W, (hipStream_t)stream));
 }
 
-// Tuning knob (process-wide, not thread-safe): target number of decode blocks per launch.
-void paro_tune_decode_blocks(int blocks) { paro::set_decode_target_blocks(blocks); }
+// Tuning knob (process-wide, not thread-safe): target number of wavefronts of a decode launch.
+void paro_tune_decode_waves(int waves) { paro::set_decode_target_waves(waves); }
 
 }  // extern "C"

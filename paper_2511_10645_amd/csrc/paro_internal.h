@@ -94,8 +94,9 @@ struct DecodeGeometry {
     int nb;           // N-blocks per slice (grid.y)
     int waves;        // waves per block
     int tiles_per_block;
+    int tpw;          // tiles per wave (template parameter of the kernel)
     size_t partial_bytes;   // fp32 partial sums [ks][T][c_out] (0 when ks == 1)
-    size_t counter_bytes;   // one uint32 per N-block (0 when ks == 1)
+    size_t counter_bytes;   // unused (0)
 };
 DecodeGeometry decode_geometry(int c_in, int c_out, int T);
 hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,

@@ -236,12 +236,12 @@ def test_tuning_knob_changes_only_summation_order(P):
     rot, w = make_rot(P, li), make_w(P, li)
     ws = P.Workspace(P.paro_workspace_bytes(rot, w, 1))
     try:
-        for blocks in (8, 64, 4096):
-            P.paro_tune_decode_blocks(blocks)
+        for blocks in (16, 256, 100000):
+            P.paro_tune_decode_waves(blocks)
             got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
             _assert_linear(got, y, allowed, f"decode blocks={blocks}")
     finally:
-        P.paro_tune_decode_blocks(0)
+        P.paro_tune_decode_waves(0)
 
 
 # ----------------------------------------------------------------------------- full configs
