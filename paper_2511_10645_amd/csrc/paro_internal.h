@@ -104,4 +104,9 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
 hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                                  paro_half_t *Y, int64_t ldy, int T, hipStream_t s);
 
+// Prefill-side linear (MFMA GEMM on the repacked weight), any T.
+bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T);
+hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                       int T, hipStream_t s);
+
 }  // namespace paro

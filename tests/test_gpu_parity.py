@@ -175,10 +175,12 @@ def _assert_linear(got16, y, allowed, note):
     dict(T=3, c_in=1024, c_out=16 * 37),
     dict(T=16, c_in=1536, c_out=16 * 9),
     dict(T=23, c_in=2048, c_out=16 * 21),
+    dict(T=300, c_in=1024, c_out=16 * 21),      # MFMA GEMM path, ragged token and output tiles
+    dict(T=257, c_in=512, c_out=16 * 33),
 ])
 def test_bare_linear(P, packed, case):
     li = pin.make_custom(700 + case["T"], case["T"], case["c_in"], case["c_out"], n_outlier=3)
-    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] == 3 else None
+    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] in (3, 300) else None
     u = li.x.astype(np.float64)
     y, allowed = _linear_ref(li, u, bias)
     w = make_w(P, li, packed=packed, bias=bias)
