@@ -24,6 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# `bench.py --pmc-probe`, scaled by the same counters on a 256 MiB copy (profiles/ has the runs)
+TRAFFIC_BYTES_PER_LAUNCH = {1: 66_100_000}
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
 
 
@@ -48,6 +51,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--decode-waves", type=int, default=0, help="tuning knob (0 = library default)")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (config 3) side measurement")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: 3 plain 256 MiB device copies, then 3 launches of the dominant "
+                         "fused kernel on distinct weight copies; prints nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it", file=sys.stderr)
@@ -83,10 +90,12 @@ def main() -> int:
                         y=torch.empty((T, shp.c_out), dtype=torch.float16, device=dev),
                         bytes=algorithmic_bytes(shp.c_in, shp.c_out, T),
                         bytes_bare=algorithmic_bytes(shp.c_in, shp.c_out, T, rotated=False)))
-    n_copies = max(2, -(-args.pool_mb * (1 << 20) // layer_packed_bytes))
+    # every linear cycles through its own pool of >= pool_mb, so that it misses the Infinity Cache
+    # both inside the layer step and when it is timed alone
     for L in lin:
         copies = [L["w"]]
-        for _ in range(n_copies - 1):
+        L["n_copies"] = max(2, -(-args.pool_mb * (1 << 20) // L["w"].packed.numel()))
+        for _ in range(L["n_copies"] - 1):
             c = paro.W4Weight.__new__(paro.W4Weight)
             c.c_in, c.c_out = L["w"].c_in, L["w"].c_out
             c.qweight = c.scales = c.qzeros = c.bias = None
@@ -101,7 +110,7 @@ def main() -> int:
         for k, L in enumerate(lin):
             if which is not None and k != which:
                 continue
-            w = L["copies"][i % n_copies]
+            w = L["copies"][i % L["n_copies"]]
             if bare:
                 paro.paro_w4a16_linear(w, L["x"], L["ws"], L["y"])
             else:
@@ -138,6 +147,18 @@ def main() -> int:
         torch.cuda.synchronize()
         return start.elapsed_time(stop) / n_steps
 
+    if args.pmc_probe:
+        dom = max(lin, key=lambda L: L["bytes"])
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        k = lin.index(dom)
+        for i in range(3):
+            step(i, which=k)
+        torch.cuda.synchronize()
+        return 0
+
     # ---- the timed region: exactly --steps steps of the whole layer ---------------------------
     ms_step = timed(args.steps, args.warmup)
     step_bytes = sum(L["bytes"] for L in lin)
@@ -160,9 +181,50 @@ def main() -> int:
     dom_us = per[dom["shape"].name]["us_fused"]
     achieved = dom["bytes"] / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": f"decode_kernel<8> on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.config),
+                "kernel": f"decode_kernel (fused, split-K, T={T}) on {dom['shape'].name} "
+                          f"{dom['shape'].c_in}->{dom['shape'].c_out}",
                 "algorithmic_bytes_per_launch": dom["bytes"], "avg_launch_us": dom_us}
+
+    # ---- prefill side (config 3: 2048 tokens): rotation pass + MFMA GEMM per linear ----------------
+    prefill = None
+    if not args.no_prefill and args.config == 1:
+        Tp = pin.CONFIGS[3].tokens[0]
+        prefill = {"tokens": Tp, "per_linear": {}}
+        tot_fl = tot_us = tot_us_bare = 0.0
+        for k, L in enumerate(lin):
+            shp = L["shape"]
+            xp = torch.as_tensor(pin.make_x(3, k, Tp, shp.c_in, pin.CONFIGS[3].n_outlier(shp.c_in))[0]).to(dev)
+            xr = torch.empty_like(xp)
+            yp = torch.empty((Tp, shp.c_out), dtype=torch.float16, device=dev)
+            wsp = paro.Workspace(paro.paro_workspace_bytes(L["rot"], L["w"], Tp))
+
+            def t_us(fn, n=10):
+                for _ in range(2):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(n):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / n * 1e3
+
+            us_rot = t_us(lambda: paro.paro_rotate_scale(L["rot"], xp, xr))
+            us_gemm = t_us(lambda: paro.paro_w4a16_linear(L["w"], xr, wsp, yp))
+            us_full = t_us(lambda: paro.paro_rotated_linear(L["rot"], L["w"], xp, wsp, yp))
+            fl = 2.0 * Tp * shp.c_in * shp.c_out
+            prefill["per_linear"][shp.name] = {
+                "us_rotate": round(us_rot, 1), "rotate_gbs": round(Tp * shp.c_in * 4 / us_rot / 1e3, 1),
+                "us_gemm": round(us_gemm, 1), "gemm_tflops": round(fl / us_gemm / 1e6, 1),
+                "us_rotated_linear": round(us_full, 1)}
+            tot_fl += fl; tot_us += us_full; tot_us_bare += us_gemm
+            del xp, xr, yp, wsp
+        prefill["layer_tflops"] = round(tot_fl / tot_us / 1e6, 1)
+        prefill["pct_of_mfma_f16_peak"] = round(100.0 * tot_fl / tot_us / 1e6 / MFMA_F16_PEAK_TFLOPS, 2)
+        prefill["overhead_pct_vs_bare_w4a16"] = round(100.0 * (tot_us - tot_us_bare) / tot_us_bare, 2)
+        prefill["tokens_per_s_layer"] = round(Tp / (tot_us * 1e-6), 1)
 
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
     cpu = None
@@ -190,16 +252,17 @@ def main() -> int:
         "metric": "fused rotated-W4A16 linear: decode HBM GB/s",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 activations x int4 weights, f32 accumulate", "data": "synthetic",
+        "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"config {args.config} ({cfg.name}): one decoder layer's 4 linears "
                                + ", ".join(f"{s.name} {s.c_in}->{s.c_out}" for s in cfg.linears)
-                               + f"; T={T}, group 128, K=8; pool of {n_copies} weight copies",
+                               + f"; T={T}, group 128, K=8; every linear cycles through >= {args.pool_mb} MB of weight copies",
                    "launch": "eager" if args.no_graph else "hip graph replay", "tokens": T},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "tokens_per_s_layer": round(T / (ms_step * 1e-3), 1),
         "overhead_pct_vs_bare_w4a16": round(overhead_pct, 2),
         "ms_per_step_bare": round(ms_bare_step, 6),
         "per_linear": per,
+        "prefill": prefill,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
