@@ -35,6 +35,7 @@ constexpr int kSliceCh = kSliceGroups * kGroup;      // 512
 constexpr int kXPad = 8;                             // halfs of padding per LDS row
 constexpr int kReducePerThread = 4;                   // partial words requested per thread and round
 constexpr int kReduceWords = kReducePerThread * 256;  // partial words gathered per reduction round (LDS floats)
+constexpr int kMaxIter = 9;                          // tiles per wave (unrolled stream), multiple of 3
 constexpr int kSpinLimit = 1 << 22;                  // bounded wait for a partial word to fill
 
 static int g_decode_target_blocks = 0;      // 0: choose by size (see decode_geometry)
@@ -48,6 +49,7 @@ struct DecodeArgs {
     const uint32_t *plan;
     float *partial;
     int T, C, N, G, NT, KS, tiles_per_block;
+    uint32_t m_lo, m_hi, k_lo, k_hi;     // dequant constants, see DequantConsts
 };
 
 // Raw buffer resources (stride 0): an access whose byte offset lies beyond num_records returns 0
@@ -87,15 +89,13 @@ __device__ inline void load_stage(__amdgpu_buffer_rsrc_t blob, const DecodeArgs 
 __device__ inline half2v as_h2(uint32_t u) { union { uint32_t u; half2v h; } c; c.u = u; return c.h; }
 __device__ inline uint32_t as_u32(half2v h) { union { uint32_t u; half2v h; } c; c.h = h; return c.u; }
 
-// (a & mask) | magic in one VALU op.  GFX9-family VOP3 encodings take no literals, so the
-// compiler splits the expression into two VOP2 ops with literals; operands held in registers
-// keep it at one.
-__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic)
-{
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(mask), "v"(magic));
-    return r;
-}
+// (a & mask) | magic is one VALU op (v_and_or_b32) when mask and magic sit in registers.  GFX9-family
+// VOP3 encodings take no literals, so with compile-time constants the compiler emits two VOP2
+// ops with literals instead; the four constants therefore travel as kernel arguments and are
+// moved into VGPRs once per wave.  (Inline
+// asm is not an option: instructions hidden from the compiler's hazard handling next to MFMAs
+// produced wrong results.)
+__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) { return (a & mask) | magic; }
 
 struct DequantConsts {
     uint32_t m_lo, m_hi, k_lo, k_hi;     // 0x000F000F, 0x00F000F0, 0x64006400 (1024.0 x2), 0x54005400 (64.0 x2)
@@ -250,7 +250,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
             nb1[g2] = s1; nb2[g2] = s2;
         }
     }
-    DequantConsts dq = {0x000F000Fu, 0x00F000F0u, 0x64006400u, 0x54005400u};
+    // the four constants must live in VGPRs for v_and_or_b32 to be selected: route them through a
+    // lane permute (identity), whose result the compiler treats as a per-lane value
+    auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
+    const DequantConsts dq = {to_vgpr(a.m_lo), to_vgpr(a.m_hi), to_vgpr(a.k_lo), to_vgpr(a.k_hi)};
 
     // ---- stream the tiles: three register stages, two tiles in flight while one is used -----
     const int n_in_tile = lane & 15, tq = lane >> 4;
@@ -258,6 +261,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
     const __amdgpu_buffer_rsrc_t pr = make_rsrc(a.partial, SPLIT ? (uint32_t)((size_t)a.KS * a.T * a.N * 4) : 0u);
     const __amdgpu_buffer_rsrc_t br = make_rsrc(a.bias, a.bias ? (uint32_t)a.N * 2u : 0u);      // no bias: reads 0
     auto emit = [&](const Stage &stg, int tile) {
+#ifdef PARO_EXP_WAIT0
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
         float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
         const uint32_t n = (uint32_t)tile * kTileN + n_in_tile;
         if constexpr (!SPLIT) {
@@ -282,7 +288,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
             }
         }
     };
-    for (int i = 0; i < n_iter; i += 3) {
+    // Fully unrolled (n_iter <= kMaxIter, guaranteed by the host): straight-line code with uniform
+    // early exits and no back edge, so the waits inserted by the compiler are exact - a stage is
+    // awaited while the two younger ones stay in flight.
+#pragma unroll
+    for (int i = 0; i < kMaxIter; i += 3) {
         load_stage(blob, a, tile_of(i + 2), ks, lane, st2);
         emit(st0, tile_of(i));
         if (i + 1 >= n_iter) break;
@@ -291,6 +301,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
         if (i + 2 >= n_iter) break;
         load_stage(blob, a, tile_of(i + 4), ks, lane, st1);
         emit(st2, tile_of(i + 2));
+        if (i + 3 >= n_iter) break;
     }
 
     // ---- split-K reduction, spread over the KS blocks of this output range -------------------
@@ -366,6 +377,7 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T)
     if (nb < 1) nb = 1;
     int tpb = (NT + nb - 1) / nb;
     tpb = (tpb + kDecWaves - 1) / kDecWaves * kDecWaves;     // whole rounds of the block's waves
+    if (tpb > kMaxIter * kDecWaves) tpb = kMaxIter * kDecWaves;
     d.tiles_per_block = tpb;
     d.nb = (NT + tpb - 1) / tpb;
     int t16 = T < 16 ? T : 16;
@@ -406,6 +418,7 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
     a.partial = (float *)ws;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN; a.KS = d.ks;
     a.tiles_per_block = d.tiles_per_block;
+    a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
     if (!rot) return launch_decode_k<-1>(a, d, s);
     switch (rot->n_layers) {
     case 0: return launch_decode_k<0>(a, d, s);
