@@ -145,6 +145,62 @@ __device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGrou
     return tot;
 }
 
+// Split-K reduction, spread over the `parts` blocks of one output range.  The T*width outputs of
+// the range are cut into `parts` contiguous shares; block `part` sums the partials of its share
+// in a fixed order (deterministic), adds the bias and stores fp16.  No fences and no counters:
+// every partial word is its own full/empty flag (0 = empty; a value is never stored as +0),
+// written and read with agent-scope accesses and reset to empty by its reader.  A reader polls
+// a word until it fills; the writers are the blocks dispatched next to it, which never wait on
+// anything before writing.  The poll is bounded; a word that never fills is reported as NaN.
+template <int THREADS>
+__device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, int tile_lo, int tile_hi, float *s_red)
+{
+#ifndef PARO_EXP_NO_FINALIZE
+    const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
+    const int outputs = a.T * width;
+    const int share = (outputs + parts - 1) / parts;
+    const int o_lo = part * share, o_hi = min(outputs, o_lo + share);
+    const int round_outputs = kReduceWords / parts;
+    for (int base = o_lo; base < o_hi; base += round_outputs) {
+        const int n_out = min(round_outputs, o_hi - base);
+        __syncthreads();
+        // all of a thread's words are requested before any is examined: one round trip
+        constexpr int PER = kReduceWords / THREADS;
+        uint32_t bits[PER];
+        uint32_t *ptr[PER];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int j = threadIdx.x + u * THREADS;
+            const bool on = j < n_out * parts;
+            // consecutive threads take consecutive outputs of one K-part: coalesced requests
+            const int o = base + (on ? j % n_out : 0), k2 = on ? j / n_out : 0;
+            const int t = o / width, n = n_lo + o % width;
+            ptr[u] = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
+            bits[u] = on ? __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
+        }
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int j = threadIdx.x + u * THREADS;
+            if (j < n_out * parts) {
+                for (int spin = 0; bits[u] == 0u && spin < kSpinLimit; ++spin)
+                    bits[u] = __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < n_out; i += THREADS) {
+            const int o = base + i;
+            const int t = o / width, n = n_lo + o % width;
+            float sum = 0.f;
+            for (int k2 = 0; k2 < parts; ++k2) sum += s_red[k2 * n_out + i];
+            if (a.bias) sum += (float)a.bias[n];
+            a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
+        }
+    }
+#endif
+}
+
 // K >= 0: rotation with K layers fused; K < 0: bare linear on X.  SPLIT: more than one K-slice.
 // T1: exactly one token.
 template <int K, bool SPLIT, bool T1>
@@ -308,63 +364,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
         if (i + 3 >= n_iter) break;
     }
 
-    // ---- split-K reduction, spread over the KS blocks of this output range -------------------
-    // The T*width outputs of the range are cut into KS contiguous shares; block ks sums the KS
-    // partials of its share in a fixed order (deterministic), adds the bias and stores fp16.
-    // No fences and no counters: every partial word is its own full/empty flag (0 = empty; a
-    // value is never stored as +0), written and read with agent-scope accesses and reset to
-    // empty by its reader.  A reader polls a word until it fills; the writers are the blocks
-    // dispatched next to it, which never wait on anything before writing.
-#ifndef PARO_EXP_NO_FINALIZE
-    if constexpr (SPLIT) {
-        const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
-        const int outputs = a.T * width;
-        const int share = (outputs + a.KS - 1) / a.KS;
-        const int o_lo = ks * share, o_hi = min(outputs, o_lo + share);
-        const int round_outputs = kReduceWords / a.KS;
-        for (int base = o_lo; base < o_hi; base += round_outputs) {
-            const int n_out = min(round_outputs, o_hi - base);
-            __syncthreads();
-            // all of a thread's words are requested before any is examined: one round trip
-            uint32_t bits[kReducePerThread];
-            uint32_t *ptr[kReducePerThread];
-#pragma unroll
-            for (int u = 0; u < kReducePerThread; ++u) {
-                const int j = threadIdx.x + u * kDecThreads;
-                const bool on = j < n_out * a.KS;
-                // consecutive threads take consecutive outputs of one K-slice: coalesced requests
-                const int o = base + (on ? j % n_out : 0), k2 = on ? j / n_out : 0;
-                const int t = o / width, n = n_lo + o % width;
-                ptr[u] = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
-                bits[u] = on ? __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
-            }
-#pragma unroll
-            for (int u = 0; u < kReducePerThread; ++u) {
-                const int j = threadIdx.x + u * kDecThreads;
-                if (j < n_out * a.KS) {
-#ifndef PARO_EXP_NO_SPIN
-                    for (int spin = 0; bits[u] == 0u && spin < kSpinLimit; ++spin)
-                        bits[u] = __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#endif
-#ifndef PARO_EXP_NO_RESET
-                    __hip_atomic_store(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#endif
-                    // a word that never filled is reported as NaN, not as a silent zero
-                    s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
-                }
-            }
-            __syncthreads();
-            for (int i = threadIdx.x; i < n_out; i += kDecThreads) {
-                const int o = base + i;
-                const int t = o / width, n = n_lo + o % width;
-                float sum = 0.f;
-                for (int k2 = 0; k2 < a.KS; ++k2) sum += s_red[k2 * n_out + i];
-                if (a.bias) sum += (float)a.bias[n];
-                a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
-            }
-        }
-    }
-#endif
+    // ---- split-K: exchange with the other K-slices of this output range ----------------------
+    if constexpr (SPLIT) splitk_reduce<kDecThreads>(a, a.KS, ks, tile_lo, tile_hi, s_red);
 }
 
 DecodeGeometry decode_geometry(int c_in, int c_out, int T)
@@ -435,6 +436,174 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
     case 7: return launch_decode_k<7>(a, d, s);
     default: return launch_decode_k<8>(a, d, s);
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Wide variant: a block of 8 waves covers 8 K-slices (4096 channels) of the SAME tiles; the 8
+// partial tiles are summed through LDS, so layers with c_in <= 4096 need no exchange between
+// blocks at all, and wider ones exchange 8x fewer partial sums.  Used for the bare linear and
+// for 5..16 tokens, where partial sums (T x N fp32 per K-part) would otherwise rival the
+// weight stream.  The transform, if any, has run as a separate pass.
+// ------------------------------------------------------------------------------------------
+constexpr int kWideWaves = 8;
+constexpr int kWideThreads = kWideWaves * 64;
+
+template <bool SPLIT, bool T1>
+__global__ __launch_bounds__(kWideThreads) void decode_wide_kernel(DecodeArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float s_wide[];      // [n_iter][8 waves][256] + reduce scratch
+    const int kb = blockIdx.x, nb = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ks = kb * kWideWaves + wave;
+    const bool slice_ok = ks < a.KS;
+    const int tile_lo = nb * a.tiles_per_block;
+    const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
+    const int n_iter = tile_hi - tile_lo;                                  // <= kMaxIter
+    auto tile_of = [&](int i) { return (i < n_iter && slice_ok) ? tile_lo + i : -1; };
+    const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
+
+    Stage st0, st1, st2;
+    half8 xf[kSliceGroups][4];
+    const int ft = lane & 15, fkb = lane >> 4;
+    {
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
+        const uint32_t xoff = (ft < a.T && slice_ok) ? (uint32_t)(((size_t)ft * a.ldx + (size_t)ks * kSliceCh + fkb * 32) * 2) : kOob;
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                union { u32x4 u; half8 h; } v;
+                v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
+                xf[g2][j] = v.h;
+            }
+        load_stage(blob, a, tile_of(0), ks, lane, st0);
+        load_stage(blob, a, tile_of(1), ks, lane, st1);
+    }
+    float4v nb1[kSliceGroups], nb2[kSliceGroups];
+    {
+        const half8 cb1 = {-1024, -1024, -64, -64, -1024, -1024, -64, -64};
+        const half8 cb2 = {-1, -1, -1, -1, -1, -1, -1, -1};
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+            float4v s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb1, s1, 0, 0, 0);
+                s2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb2, s2, 0, 0, 0);
+            }
+            nb1[g2] = s1; nb2[g2] = s2;
+        }
+    }
+    auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
+    const DequantConsts dq = {to_vgpr(a.m_lo), to_vgpr(a.m_hi), to_vgpr(a.k_lo), to_vgpr(a.k_hi)};
+
+    // partial tile of (iteration i, this wave): element lane*4 + r <-> token 4*(lane/16)+r, row lane%16
+    auto emit = [&](const Stage &stg, int i) {
+        float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
+        float *dst = s_wide + ((size_t)i * kWideWaves + wave) * 256 + lane * 4;
+        if constexpr (T1) { if (lane < 16) dst[0] = tot[0]; }
+        else *(float4v *)dst = tot;
+    };
+#pragma unroll
+    for (int i = 0; i < kMaxIter; i += 3) {
+        load_stage(blob, a, tile_of(i + 2), ks, lane, st2);
+        emit(st0, i);
+        if (i + 1 >= n_iter) break;
+        load_stage(blob, a, tile_of(i + 3), ks, lane, st0);
+        emit(st1, i + 1);
+        if (i + 2 >= n_iter) break;
+        load_stage(blob, a, tile_of(i + 4), ks, lane, st1);
+        emit(st2, i + 2);
+        if (i + 3 >= n_iter) break;
+    }
+    __syncthreads();
+
+    // ---- sum the 8 K-slices; outputs indexed (i, t, n) with n fastest for coalesced stores -----
+    const int per_tile = a.T * kTileN;
+    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += kWideThreads) {
+        const int i = idx / per_tile, rem = idx % per_tile;
+        const int t = rem / kTileN, nn = rem % kTileN;
+        const int e = ((t >> 2) * 16 + nn) * 4 + (t & 3);
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWideWaves; ++w) sum += s_wide[((size_t)i * kWideWaves + w) * 256 + e];
+        const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
+        if constexpr (!SPLIT) {
+            if (a.bias) sum += (float)a.bias[n];
+            a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
+        } else {
+            uint32_t bits = __float_as_uint(sum);
+            if ((bits << 1) == 0u) bits = 0x80000000u;
+            __hip_atomic_store((uint32_t *)(a.partial + ((size_t)kb * a.T + t) * a.N + n), bits, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if constexpr (SPLIT)
+        splitk_reduce<kWideThreads>(a, gridDim.x, kb, tile_lo, tile_hi, s_wide + (size_t)kMaxIter * kWideWaves * 256);
+}
+
+struct WideGeometry { int kb, nb, tiles_per_block; size_t lds; };
+static WideGeometry wide_geometry(int c_in, int c_out)
+{
+    WideGeometry g;
+    const int KS = c_in / kGroup / kSliceGroups, NT = c_out / kTileN;
+    g.kb = (KS + kWideWaves - 1) / kWideWaves;
+    int nb = 256 / g.kb;                      // one 8-wave block per CU
+    if (nb < 1) nb = 1;
+    int tpb = (NT + nb - 1) / nb;
+    if (tpb > kMaxIter) tpb = kMaxIter;
+    g.tiles_per_block = tpb;
+    g.nb = (NT + tpb - 1) / tpb;
+    g.lds = ((size_t)kMaxIter * kWideWaves * 256 + kReduceWords) * sizeof(float);
+    return g;
+}
+
+size_t decode_wide_partial_bytes(int c_in, int c_out, int T)
+{
+    WideGeometry g = wide_geometry(c_in, c_out);
+    int t16 = T < 16 ? T : 16;
+    return g.kb > 1 ? (size_t)g.kb * t16 * c_out * sizeof(float) : 0;
+}
+
+hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                              int T, void *ws, hipStream_t s)
+{
+    if (packed_tiles_bytes(w.c_in, w.c_out) + packed_scales_bytes(w.c_in, w.c_out) + packed_zeros_bytes(w.c_in, w.c_out) >= (1ull << 31))
+        return hipErrorInvalidValue;   // 32-bit buffer offsets
+    WideGeometry g = wide_geometry(w.c_in, w.c_out);
+    if (g.kb > 64) return hipErrorInvalidValue;
+    DecodeArgs a;
+    a.blob = w.packed;
+    a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);
+    a.zeros_off = a.scales_off + (uint32_t)packed_scales_bytes(w.c_in, w.c_out);
+    a.blob_bytes = a.zeros_off + (uint32_t)packed_zeros_bytes(w.c_in, w.c_out);
+    a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
+    a.bias = (const _Float16 *)w.bias;
+    a.plan = nullptr;
+    a.partial = (float *)ws;
+    a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN;
+    a.KS = a.G / kSliceGroups;
+    a.tiles_per_block = g.tiles_per_block;
+    a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const void *fns[4] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
+                              (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>};
+        for (const void *f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds);
+            if (e != hipSuccess) return e;
+        }
+        attr_set = true;
+    }
+    const dim3 grid(g.kb, g.nb), block(kWideThreads);
+    if (T == 1) {
+        if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, true>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((decode_wide_kernel<false, true>), grid, block, g.lds, s, a);
+    } else {
+        if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, false>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((decode_wide_kernel<false, false>), grid, block, g.lds, s, a);
+    }
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------

@@ -65,7 +65,9 @@ WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
     WsLayout L{0, 0, 0};
     if (fast_weight(w)) {
         DecodeGeometry d = decode_geometry(w->c_in, w->c_out, T);
-        L.decode_bytes = round_up(d.counter_bytes + d.partial_bytes, 256);
+        size_t wide = decode_wide_partial_bytes(w->c_in, w->c_out, T);
+        size_t part = d.partial_bytes > wide ? d.partial_bytes : wide;
+        L.decode_bytes = round_up(part, 256);
     }
     L.xr_offset = L.decode_bytes;
     L.total = L.decode_bytes + (rot ? round_up((size_t)T * w->c_in * 2, 256) : 0);
@@ -85,7 +87,7 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
     if (T > kDecodeMaxTokens && gemm_supported(*w, ldx, ldy, T)) return from_hip(launch_gemm(*w, X, ldx, Y, ldy, T, s));
     for (int t0 = 0; t0 < T; t0 += 16) {
         int tc = T - t0 < 16 ? T - t0 : 16;
-        hipError_t e = launch_decode(nullptr, *w, X + (size_t)t0 * ldx, ldx, Y + (size_t)t0 * ldy, ldy, tc, ws, s);
+        hipError_t e = launch_decode_wide(*w, X + (size_t)t0 * ldx, ldx, Y + (size_t)t0 * ldy, ldy, tc, ws, s);
         if (e != hipSuccess) return PARO_ERR_HIP;
     }
     return PARO_OK;

@@ -101,6 +101,10 @@ struct DecodeGeometry {
 DecodeGeometry decode_geometry(int c_in, int c_out, int T);
 hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                          paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s);
+// Wide decode variant (bare linear, T <= 16): 8 K-slices per block, reduced through LDS.
+size_t decode_wide_partial_bytes(int c_in, int c_out, int T);
+hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                              int T, void *ws, hipStream_t s);
 hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                                  paro_half_t *Y, int64_t ldy, int T, hipStream_t s);
 
