@@ -1,21 +1,35 @@
 // Prefill-side W4A16 linear: Y[T x N] = X'[T x C] . W^[N x C]^T for many tokens (Eq. 2), the one
 // dense contraction of the path, on fp16 MFMA with fp32 accumulation.
 //
-// Block tile 256 (tokens) x 256 (outputs) x 64 (channels), 4 wavefronts as 2 x 2, each wave a
-// 128 x 128 sub-tile = 4 x 4 v_mfma_f32_32x32x16_f16 tiles (256 accumulator registers).
-// Per K-step a block fetches 32 KB of activations and 8 KB of packed INT4 codes; the codes are
-// dequantised ONCE per block into an fp16 LDS tile
+// Block tile BM (tokens: 256 or 128) x 256 (outputs) x 64 (channels), 4 wavefronts as 2 x 2,
+// each wave a (BM/2) x 128 sub-tile of v_mfma_f32_32x32x16_f16 tiles (up to 256 accumulator
+// registers).  Per K-step a block fetches BM x 128 B of activations and 8 KB of packed INT4
+// codes; the codes are dequantised ONCE per block into an fp16 LDS tile
 //      w^ = fp16( (q - z) * s )        ((q - z) exact in fp16, one rounding in the multiply:
 //                                        the same value paro_w4_dequant produces)
-// so the VALU cost per weight is amortised over the 256 token rows.  LDS is double-buffered
-// (2 x (36 + 36) KB): global loads for step s+1 are issued before the MFMAs of step s and
-// land in LDS after them, one barrier per K-step.  Rows are padded by 16 bytes so that the
-// 16-byte fragment reads of 32 consecutive rows spread over all banks.
+// so the VALU cost per weight is amortised over the block's token rows.
+//
+// Software pipeline.  There is one wave per SIMD, so nothing hides a stall: every K-step is
+// written as 4 phases (one per 16-channel MFMA step) of explicitly ordered slots
+//      slot = 1 MFMA + at most one LDS fragment read + at most one piece of staging work,
+// pinned with scheduling barriers so that the matrix pipe always has the next MFMA queued
+// while the vector/LDS/memory instructions of the slot issue in its shadow:
+//   - fragments of MFMA step kk+1 are read from LDS during the MFMAs of step kk (two register
+//     sets);
+//   - the global data of K-step s+1 sits in registers during K-step s, is dequantised /
+//     copied into the other LDS buffer piece by piece in phases 0..2, and each register is
+//     refilled at once with the load for K-step s+2 (a full K-step of latency allowance);
+//   - one barrier per K-step, after phase 2: by then every wave has finished reading the
+//     current buffer into registers and writing the next one, so phase 3 already reads the
+//     next K-step's first fragments.
+// LDS rows are padded by 16 bytes so that the 16-byte fragment reads of 32 consecutive rows
+// spread over all banks.
 //
 // Blocks are numbered so that the 32 blocks resident on one XCD (block id mod 8) form an
 // 8 (token tiles) x 4 (output tiles) patch that walks K in step: they share activation and
 // weight panels through that XCD's L2.
 #include "paro_internal.h"
+#include <type_traits>
 
 namespace paro {
 
@@ -24,7 +38,7 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kBN = 256, kBK = 64;
 constexpr int kLdsRow = kBK + 8;                    // halfs per padded LDS row
 constexpr int kGemmThreads = 256;
 constexpr int kPatchM = 8, kPatchN = 4;             // blocks of one XCD patch
@@ -37,6 +51,15 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc_g(const void *p, uint32_t byt
 __device__ inline half2v g_as_h2(uint32_t u) { union { uint32_t u; half2v h; } c; c.u = u; return c.h; }
 __device__ inline uint32_t g_as_u32(half2v h) { union { uint32_t u; half2v h; } c; c.h = h; return c.u; }
 
+template <int N, class F, int I = 0>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
+
 struct GemmArgs {
     const void *blob; uint32_t blob_bytes, scales_off, zeros_off;
     const _Float16 *X; int64_t ldx;
@@ -46,17 +69,38 @@ struct GemmArgs {
     int m_tiles, n_tiles;
 };
 
-struct BStage {       // packed codes and parameters of one K-step for this thread
-    u32x4 w[2];
-    uint32_t sc[2];   // fp16 scale (low half)
-    uint32_t zq[2];   // 4 zero nibbles of the slice
-};
+// Staging work of one K-step, cut into items that are spread over the MFMA slots of phases 0..2:
+//   0..15   dequantise half of one 8-code word pair: code = p * 8 + w4 * 2 + h   (p: which of the
+//           thread's two 16-byte code loads, w4: word, h: low / high byte pair)
+//   16..23  copy activation register r = code - 16 to LDS and refill it from global memory
+//   24, 25  refill the code / scale / zero registers of load p = code - 24
+// kALoads activation registers exist; the order interleaves LDS writes and global loads.
+template <int AL>
+__host__ __device__ constexpr int staging_item(int k)
+{
+    // per p: 4 x (deq half 0, deq half 1, [A copy]) then the refill of p
+    constexpr int per_p = 8 + AL / 2 + 1;
+    if (k < 0 || k >= 2 * per_p) return -1;
+    const int p = k / per_p, r = k % per_p;
+    if (r == per_p - 1) return 24 + p;
+    // positions: AL/2 A copies are placed after every (8 / (AL/2)) dequant halves
+    constexpr int stride = 8 / (AL / 2) + 1;          // AL = 8: 3 (2 halves + 1 copy); AL = 4: 5 (4 halves + 1 copy)
+    const int grp = r / stride, in = r % stride;
+    if (in == stride - 1) return 16 + p * (AL / 2) + grp;
+    const int hidx = grp * (stride - 1) + in;          // 0..7 = w4 * 2 + h
+    return p * 8 + hidx;
+}
 
+template <int MI>   // 32-row MFMA tiles per wave along the tokens: 4 (256-token block) or 2 (128)
 __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
 {
+    constexpr int BM = MI * 64;
+    constexpr int AL = BM / 32;                            // 16-byte activation loads per thread and K-step
+    constexpr int kSlots = MI * 4;                         // MFMAs per phase
+    constexpr int kItems = 2 * (8 + AL / 2 + 1);
     extern __shared__ __attribute__((aligned(16))) _Float16 smem[];
-    _Float16 *As = smem;                                   // [2][kBM][kLdsRow]
-    _Float16 *Bs = smem + 2 * kBM * kLdsRow;               // [2][kBN][kLdsRow]
+    _Float16 *As = smem;                                   // [2][BM][kLdsRow]
+    _Float16 *Bs = smem + 2 * BM * kLdsRow;                // [2][kBN][kLdsRow]
 
     // ---- block -> (m tile, n tile), XCD-aware --------------------------------------------------
     const int bid = blockIdx.x;
@@ -67,7 +111,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
     const int pm = gp % m_patches, pn = gp / m_patches;
     const int mt = pm * kPatchM + q % kPatchM, ntile = pn * kPatchN + q / kPatchM;
     if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
-    const int m0 = mt * kBM, n0 = ntile * kBN;
+    const int m0 = mt * BM, n0 = ntile * kBN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -75,98 +119,140 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
     const __amdgpu_buffer_rsrc_t xr = make_rsrc_g(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
     const __amdgpu_buffer_rsrc_t br = make_rsrc_g(a.blob, a.blob_bytes);
 
-    // per-thread load coordinates
-    // A: 8 x 16 B per thread: idx = tid + 256 p -> row idx/8, 16-byte column idx%8
-    // B: 2 x 16 B per thread: idx = tid + 256 p -> 16-row tile idx/32, lane-in-half idx%32
-    const int a_c16 = tid & 7, a_row = tid >> 3;           // + 32 p rows
-    const int b_l32 = tid & 31, b_rt = tid >> 5;           // + 8 p row tiles
+    // per-thread load coordinates; the K-step enters every address as a wave-uniform byte offset
+    // A: AL x 16 B per thread: row tid/8 + 32 r, 16-byte column tid%8
+    // B: 2 x 16 B per thread: 16-row tile tid/32 + 8 p, lane-in-half tid%32
+    const int a_c16 = tid & 7, a_row = tid >> 3;
+    const int b_l32 = tid & 31, b_rt = tid >> 5;
     const int b_n = b_l32 & 15, b_kq = b_l32 >> 4;         // row in tile, 32-channel quarter within the half
+    uint32_t a_voff[AL], bw_voff[2], bs_voff[2], bz_voff[2];
+#pragma unroll
+    for (int r = 0; r < AL; ++r) {
+        const int row = m0 + a_row + 32 * r;
+        a_voff[r] = row < a.T ? (uint32_t)(((size_t)row * a.ldx + a_c16 * 8) * 2) : kOobG;
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int nt = n0 / kTileN + b_rt + 8 * p;
+        const bool ok = nt * kTileN < a.N;
+        bw_voff[p] = ok ? ((uint32_t)nt * a.G * 64u + b_kq * 16 + b_n) * 16u : kOobG;
+        const uint32_t sidx = (uint32_t)nt * a.S * kTileN + b_n;
+        bs_voff[p] = ok ? a.scales_off + sidx * 8u : kOobG;
+        bz_voff[p] = ok ? a.zeros_off + sidx * 2u : kOobG;
+    }
+    const int a_lds = a_row * kLdsRow + a_c16 * 8;                          // + 32 r rows
+    int b_lds[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) b_lds[p] = ((b_rt + 8 * p) * kTileN + b_n) * kLdsRow + b_kq * 32;
 
-    u32x4 areg[8];
-    BStage bst;
-    auto load_global = [&](int ks) {
-        const int k0 = ks * kBK;
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const int row = m0 + a_row + 32 * p;
-            const uint32_t off = row < a.T ? (uint32_t)(((size_t)row * a.ldx + k0 + a_c16 * 8) * 2) : kOobG;
-            areg[p] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)off, 0, 0);
-        }
-        const int g = k0 / kGroup, half = (k0 / kBK) & 1;
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int nt = n0 / kTileN + b_rt + 8 * p;                  // 16-row tile of the weight
-            const bool ok = nt * kTileN < a.N;
-            const int ln = (half * 2 + b_kq) * 16 + b_n;                 // lane inside the 1 KB tile
-            const uint32_t off = ok ? (((uint32_t)nt * a.G + g) * 64u + ln) * 16u : kOobG;
-            bst.w[p] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)off, 0, 0);
-            const uint32_t sidx = ((uint32_t)nt * a.S + g / kSliceGroups) * kTileN + b_n;
-            bst.sc[p] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
-                br, ok ? (int)(a.scales_off + (sidx * 4u + (g % kSliceGroups)) * 2u) : (int)kOobG, 0, 0);
-            bst.zq[p] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
-                br, ok ? (int)(a.zeros_off + sidx * 2u) : (int)kOobG, 0, 0);
-        }
+    u32x4 areg[AL];
+    u32x4 bw[2];
+    uint32_t bsc[2], bzq[2];
+    const int n_ks = a.C / kBK;
+    auto load_a = [&](int r, int ks) {
+        areg[r] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)a_voff[r], ks * (kBK * 2), 0);
     };
-    auto store_lds = [&](int buf, int ks) {
-        _Float16 *Ab = As + (size_t)buf * kBM * kLdsRow, *Bb = Bs + (size_t)buf * kBN * kLdsRow;
-#pragma unroll
-        for (int p = 0; p < 8; ++p) *(u32x4 *)&Ab[(a_row + 32 * p) * kLdsRow + a_c16 * 8] = areg[p];
-        const int g = (ks * kBK) / kGroup;
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const uint32_t z = (bst.zq[p] >> (4 * (g % kSliceGroups))) & 15u;
-            const half2v nlo = g_as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
-            const half2v nhi = g_as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
-            const half2v s2 = g_as_h2(bst.sc[p] * 0x00010001u);
-            _Float16 *dst = &Bb[((b_rt + 8 * p) * kTileN + b_n) * kLdsRow + b_kq * 32];
-#pragma unroll
-            for (int w4 = 0; w4 < 4; ++w4) {
-                uint32_t u = bst.w[p][w4];
-                u32x4 o;
-                o[0] = g_as_u32((g_as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo) * s2);
-                o[1] = g_as_u32((g_as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi) * s2);
-                u >>= 8;
-                o[2] = g_as_u32((g_as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo) * s2);
-                o[3] = g_as_u32((g_as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi) * s2);
-                *(u32x4 *)&dst[w4 * 8] = o;
-            }
-        }
+    auto load_b = [&](int p, int ks) {
+        const int g = ks >> 1, half = ks & 1;
+        bw[p] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)bw_voff[p], g * 1024 + half * 512, 0);
+        bsc[p] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8) + (g & 3) * 2, 0);
+        bzq[p] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
+    };
+    half2v nlo[2], nhi[2], s2[2];
+    auto deq_consts = [&](int p, int ks) {
+        const int g = ks >> 1;
+        const uint32_t z = (bzq[p] >> (4 * (g & 3))) & 15u;
+        nlo[p] = g_as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
+        nhi[p] = g_as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
+        s2[p] = g_as_h2(bsc[p] * 0x00010001u);
+    };
+    // half h of word w4 of load p -> 4 fp16 weights (8 bytes) in the LDS tile
+    auto deq_half = [&](_Float16 *Bn, int p, int w4, int h) {
+        const uint32_t u = bw[p][w4] >> (8 * h);
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 o;
+        o[0] = g_as_u32((g_as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo[p]) * s2[p]);
+        o[1] = g_as_u32((g_as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi[p]) * s2[p]);
+        *(u32x2 *)&Bn[b_lds[p] + w4 * 8 + h * 4] = o;
     };
 
-    float16v acc[4][4];
+    float16v acc[MI][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int jn = 0; jn < 4; ++jn)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
-    const int n_ks = a.C / kBK;
-    load_global(0);
-    store_lds(0, 0);
+    // ---- prologue: K-step 0 into LDS buffer 0, K-step 1 into the registers -------------------
+#pragma unroll
+    for (int r = 0; r < AL; ++r) load_a(r, 0);
+    load_b(0, 0); load_b(1, 0);
+#pragma unroll
+    for (int r = 0; r < AL; ++r) *(u32x4 *)&As[a_lds + 32 * r * kLdsRow] = areg[r];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        deq_consts(p, 0);
+#pragma unroll
+        for (int w4 = 0; w4 < 4; ++w4) { deq_half(Bs, p, w4, 0); deq_half(Bs, p, w4, 1); }
+    }
+    {
+        const int k1 = n_ks > 1 ? 1 : 0;
+#pragma unroll
+        for (int r = 0; r < AL; ++r) load_a(r, k1);
+        load_b(0, k1); load_b(1, k1);
+    }
     __syncthreads();
 
     const int fr = lane & 31, fh = lane >> 5;
+    const int fa_off = (wm * (BM / 2) + fr) * kLdsRow + fh * 8;
+    const int fb_off = (wn * 128 + fr) * kLdsRow + fh * 8;
+    half8 fa[2][MI], fb[2][4];
+    // fragment `f` (0..MI-1: token tiles, MI..MI+3: output tiles) of MFMA step kk
+    auto read_frag = [&](const _Float16 *Ab, const _Float16 *Bb, int f, int kk, int set) {
+        if (f < MI) fa[set][f] = *(const half8 *)&Ab[fa_off + f * 32 * kLdsRow + kk * 16];
+        else fb[set][f - MI] = *(const half8 *)&Bb[fb_off + (f - MI) * 32 * kLdsRow + kk * 16];
+    };
+#pragma unroll
+    for (int f = 0; f < MI + 4; ++f) read_frag(As, Bs, f, 0, 0);
+
     for (int ks = 0; ks < n_ks; ++ks) {
         const int buf = ks & 1;
-        if (ks + 1 < n_ks) load_global(ks + 1);
-        const _Float16 *Ab = As + (size_t)buf * kBM * kLdsRow + (wm * 128 + fr) * kLdsRow + fh * 8;
-        const _Float16 *Bb = Bs + (size_t)buf * kBN * kLdsRow + (wn * 128 + fr) * kLdsRow + fh * 8;
-#pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            half8 af[4], bf[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *(const half8 *)&Ab[i * 32 * kLdsRow + kk * 16];
-#pragma unroll
-            for (int jn = 0; jn < 4; ++jn) bf[jn] = *(const half8 *)&Bb[jn * 32 * kLdsRow + kk * 16];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jn = 0; jn < 4; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[jn], acc[i][jn], 0, 0, 0);
-        }
-        if (ks + 1 < n_ks) store_lds(buf ^ 1, ks + 1);
-        __syncthreads();
+        const _Float16 *Ac = As + buf * BM * kLdsRow, *Bc = Bs + buf * kBN * kLdsRow;
+        _Float16 *An = As + (buf ^ 1) * BM * kLdsRow, *Bn = Bs + (buf ^ 1) * kBN * kLdsRow;
+        const int ks_store = ks + 1;                                      // K-step held in the registers
+        const int ks_load = ks + 2 < n_ks ? ks + 2 : n_ks - 1;            // clamped: the surplus data is never used
+        static_for<4>([&](auto PH) {
+            constexpr int ph = PH;
+            static_for<kSlots>([&](auto SL) {
+                constexpr int slot = SL;
+                constexpr int i = slot / 4, jn = slot % 4;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ph & 1][i], fb[ph & 1][jn], acc[i][jn], 0, 0, 0);
+                if constexpr (slot < MI + 4) {
+                    if constexpr (ph < 3) read_frag(Ac, Bc, slot, ph + 1, (ph + 1) & 1);
+                    else read_frag(An, Bn, slot, 0, 0);
+                }
+                if constexpr (ph < 3) {
+                    // item k is placed at slot floor(k * total_slots / kItems) of phases 0..2
+                    constexpr int gs = ph * kSlots + slot, total = 3 * kSlots;
+                    constexpr int k = (gs * kItems + total - 1) / total;
+                    constexpr int code = (k < kItems && k * total / kItems == gs) ? staging_item<AL>(k) : -1;
+                    if constexpr (code >= 0 && code < 16) {
+                        constexpr int p = code / 8, w4 = (code % 8) / 2, h = code % 2;
+                        if constexpr (w4 == 0 && h == 0) deq_consts(p, ks_store);
+                        deq_half(Bn, p, w4, h);
+                    } else if constexpr (code >= 16 && code < 24) {
+                        constexpr int r = code - 16;
+                        *(u32x4 *)&An[a_lds + 32 * r * kLdsRow] = areg[r];
+                        load_a(r, ks_load);
+                    } else if constexpr (code >= 24) {
+                        load_b(code - 24, ks_load);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            if constexpr (ph == 2) __syncthreads();
+        });
     }
 
     // ---- epilogue: + bias, fp16 store.  Lane (column fr, half fh) holds rows 8b + 4 fh + r. ------
@@ -176,10 +262,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
         const int n = n0 + wn * 128 + jn * 32 + fr;
         const float bv = (a.bias && n < a.N) ? (float)a.bias[n] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * 128 + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
+                const int m = m0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
                 union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(acc[i][jn][v] + bv);
                 const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.ldy + n) * 2) : kOobG;
                 __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
@@ -195,6 +281,27 @@ bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T)
            w.c_in % kBK == 0;
 }
 
+template <int MI>
+static hipError_t launch_gemm_mi(GemmArgs &a, hipStream_t s)
+{
+    constexpr int BM = MI * 64;
+    a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = (a.N + kBN - 1) / kBN;
+    const int m_patches = (a.m_tiles + kPatchM - 1) / kPatchM, n_patches = (a.n_tiles + kPatchN - 1) / kPatchN;
+    const int patches = m_patches * n_patches;
+    const int rounds = (patches + 7) / 8;                 // patches per XCD
+    const int blocks = rounds * 8 * kPatchM * kPatchN;
+    const size_t lds = (size_t)2 * (BM + kBN) * kLdsRow * sizeof(_Float16);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel<MI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_w4a16_kernel<MI>, dim3(blocks), dim3(kGemmThreads), lds, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T,
                        hipStream_t s)
 {
@@ -206,21 +313,13 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
-    a.m_tiles = (T + kBM - 1) / kBM; a.n_tiles = (w.c_out + kBN - 1) / kBN;
-    const int m_patches = (a.m_tiles + kPatchM - 1) / kPatchM, n_patches = (a.n_tiles + kPatchN - 1) / kPatchN;
-    const int patches = m_patches * n_patches;
-    const int rounds = (patches + 7) / 8;                 // patches per XCD
-    const int blocks = rounds * 8 * kPatchM * kPatchN;
-    const size_t lds = (size_t)2 * (kBM + kBN) * kLdsRow * sizeof(_Float16);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(gemm_w4a16_kernel, dim3(blocks), dim3(kGemmThreads), lds, s, a);
-    return hipGetLastError();
+    // 256-token tiles unless they leave compute units idle: fewer than one full wave of blocks
+    const long big_tiles = (long)((T + 255) / 256) * ((w.c_out + kBN - 1) / kBN);
+    int mi = big_tiles >= 256 ? 4 : 2;
+#ifdef PARO_GEMM_FORCE_MI
+    mi = PARO_GEMM_FORCE_MI;
+#endif
+    return mi == 4 ? launch_gemm_mi<4>(a, s) : launch_gemm_mi<2>(a, s);
 }
 
 }  // namespace paro
