@@ -40,7 +40,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBN = 256, kBK = 64;
 constexpr int kLdsRow = kBK + 8;                    // halfs per padded LDS row
-constexpr int kGemmThreads = 256;
 constexpr int kPatchM = 8, kPatchN = 4;             // blocks of one XCD patch
 
 constexpr uint32_t kOobG = 0x80000000u;
@@ -69,35 +68,46 @@ struct GemmArgs {
     int m_tiles, n_tiles;
 };
 
-// Staging work of one K-step, cut into items that are spread over the MFMA slots of phases 0..2:
+// Staging work of one K-step, cut into items that are spread over the MFMA slots:
 //   0..15   dequantise half of one 8-code word pair: code = p * 8 + w4 * 2 + h   (p: which of the
-//           thread's two 16-byte code loads, w4: word, h: low / high byte pair)
+//           thread's 16-byte code loads, w4: word, h: low / high byte pair)
 //   16..23  copy activation register r = code - 16 to LDS and refill it from global memory
 //   24, 25  refill the code / scale / zero registers of load p = code - 24
-// kALoads activation registers exist; the order interleaves LDS writes and global loads.
-template <int AL>
+// ALP activation registers per code load; the order interleaves LDS writes and global loads.
+template <int ALP, int PB>
 __host__ __device__ constexpr int staging_item(int k)
 {
-    // per p: 4 x (deq half 0, deq half 1, [A copy]) then the refill of p
-    constexpr int per_p = 8 + AL / 2 + 1;
-    if (k < 0 || k >= 2 * per_p) return -1;
+    // per p: 8 dequant halves with the A copies spread between them, then the refill of p
+    constexpr int per_p = 8 + ALP + 1;
+    if (k < 0 || k >= PB * per_p) return -1;
     const int p = k / per_p, r = k % per_p;
     if (r == per_p - 1) return 24 + p;
-    // positions: AL/2 A copies are placed after every (8 / (AL/2)) dequant halves
-    constexpr int stride = 8 / (AL / 2) + 1;          // AL = 8: 3 (2 halves + 1 copy); AL = 4: 5 (4 halves + 1 copy)
+    constexpr int stride = 8 / ALP + 1;               // ALP = 4: 2 halves + 1 copy; ALP = 2: 4 halves + 1 copy
     const int grp = r / stride, in = r % stride;
-    if (in == stride - 1) return 16 + p * (AL / 2) + grp;
+    if (in == stride - 1) return 16 + p * ALP + grp;
     const int hidx = grp * (stride - 1) + in;          // 0..7 = w4 * 2 + h
     return p * 8 + hidx;
 }
 
-template <int MI>   // 32-row MFMA tiles per wave along the tokens: 4 (256-token block) or 2 (128)
-__global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
+// MI x NI: 32x32 MFMA tiles per wave (tokens x outputs); WM x WN: waves per block.
+// Block tile = (WM MI 32) tokens x (WN NI 32 = 256) outputs.
+template <int MI, int NI, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 {
-    constexpr int BM = MI * 64;
-    constexpr int AL = BM / 32;                            // 16-byte activation loads per thread and K-step
-    constexpr int kSlots = MI * 4;                         // MFMAs per phase
-    constexpr int kItems = 2 * (8 + AL / 2 + 1);
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int BM = WM * MI * 32;
+    static_assert(WN * NI * 32 == kBN, "256 outputs per block");
+    constexpr int AL = BM * 8 / THREADS;                   // 16-byte activation loads per thread and K-step
+    constexpr int PB = 512 / THREADS;                      // 16-byte code loads per thread and K-step
+    constexpr int ALP = AL / PB;
+    static_assert(ALP == 2 || ALP == 4, "staging schedule");
+    constexpr int kSlots = MI * NI;                        // MFMAs per phase
+    constexpr int kItems = PB * (8 + ALP + 1);
+    // staging is packed into the first phases: the refill loads then have the rest of the K-step
+    // (plus a whole further K-step) before their data is needed
+    constexpr int kStagePhases = (2 * kSlots >= kItems && THREADS > 256) ? 2 : 3;
+    static_assert(kStagePhases * kSlots >= kItems, "one staging item per slot at most");
+    static_assert(MI + NI <= kSlots, "one fragment read per slot at most");
     extern __shared__ __attribute__((aligned(16))) _Float16 smem[];
     _Float16 *As = smem;                                   // [2][BM][kLdsRow]
     _Float16 *Bs = smem + 2 * BM * kLdsRow;                // [2][kBN][kLdsRow]
@@ -114,40 +124,41 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
     const int m0 = mt * BM, n0 = ntile * kBN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     const __amdgpu_buffer_rsrc_t xr = make_rsrc_g(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
     const __amdgpu_buffer_rsrc_t br = make_rsrc_g(a.blob, a.blob_bytes);
 
     // per-thread load coordinates; the K-step enters every address as a wave-uniform byte offset
-    // A: AL x 16 B per thread: row tid/8 + 32 r, 16-byte column tid%8
-    // B: 2 x 16 B per thread: 16-row tile tid/32 + 8 p, lane-in-half tid%32
+    // A: AL x 16 B per thread: row tid/8 + (THREADS/8) r, 16-byte column tid%8
+    // B: PB x 16 B per thread: 16-row tile tid/32 + (THREADS/32) p, lane-in-half tid%32
+    constexpr int kARows = THREADS / 8, kBTiles = THREADS / 32;
     const int a_c16 = tid & 7, a_row = tid >> 3;
     const int b_l32 = tid & 31, b_rt = tid >> 5;
     const int b_n = b_l32 & 15, b_kq = b_l32 >> 4;         // row in tile, 32-channel quarter within the half
-    uint32_t a_voff[AL], bw_voff[2], bs_voff[2], bz_voff[2];
+    uint32_t a_voff[AL], bw_voff[PB], bs_voff[PB], bz_voff[PB];
 #pragma unroll
     for (int r = 0; r < AL; ++r) {
-        const int row = m0 + a_row + 32 * r;
+        const int row = m0 + a_row + kARows * r;
         a_voff[r] = row < a.T ? (uint32_t)(((size_t)row * a.ldx + a_c16 * 8) * 2) : kOobG;
     }
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int nt = n0 / kTileN + b_rt + 8 * p;
+    for (int p = 0; p < PB; ++p) {
+        const int nt = n0 / kTileN + b_rt + kBTiles * p;
         const bool ok = nt * kTileN < a.N;
         bw_voff[p] = ok ? ((uint32_t)nt * a.G * 64u + b_kq * 16 + b_n) * 16u : kOobG;
         const uint32_t sidx = (uint32_t)nt * a.S * kTileN + b_n;
         bs_voff[p] = ok ? a.scales_off + sidx * 8u : kOobG;
         bz_voff[p] = ok ? a.zeros_off + sidx * 2u : kOobG;
     }
-    const int a_lds = a_row * kLdsRow + a_c16 * 8;                          // + 32 r rows
-    int b_lds[2];
+    const int a_lds = a_row * kLdsRow + a_c16 * 8;                          // + kARows r rows
+    int b_lds[PB];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) b_lds[p] = ((b_rt + 8 * p) * kTileN + b_n) * kLdsRow + b_kq * 32;
+    for (int p = 0; p < PB; ++p) b_lds[p] = ((b_rt + kBTiles * p) * kTileN + b_n) * kLdsRow + b_kq * 32;
 
     u32x4 areg[AL];
-    u32x4 bw[2];
-    uint32_t bsc[2], bzq[2];
+    u32x4 bw[PB];
+    uint16_t bsc[PB], bzq[PB];      // widened where they are used: no ALU op (hence no wait) at the load
     const int n_ks = a.C / kBK;
     auto load_a = [&](int r, int ks) {
         areg[r] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)a_voff[r], ks * (kBK * 2), 0);
@@ -155,66 +166,73 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
     auto load_b = [&](int p, int ks) {
         const int g = ks >> 1, half = ks & 1;
         bw[p] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)bw_voff[p], g * 1024 + half * 512, 0);
-        bsc[p] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8) + (g & 3) * 2, 0);
-        bzq[p] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
+        bsc[p] = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8) + (g & 3) * 2, 0);
+        bzq[p] = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
     };
-    half2v nlo[2], nhi[2], s2[2];
+    half2v nlo[PB], nhi[PB], s2[PB];
     auto deq_consts = [&](int p, int ks) {
         const int g = ks >> 1;
-        const uint32_t z = (bzq[p] >> (4 * (g & 3))) & 15u;
+        const uint32_t z = ((uint32_t)bzq[p] >> (4 * (g & 3))) & 15u;
         nlo[p] = g_as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
         nhi[p] = g_as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
-        s2[p] = g_as_h2(bsc[p] * 0x00010001u);
+        s2[p] = g_as_h2((uint32_t)bsc[p] * 0x00010001u);
     };
-    // half h of word w4 of load p -> 4 fp16 weights (8 bytes) in the LDS tile
+    // half h of word w4 of load p -> 4 fp16 weights; the second half stores the word's 8 weights
+    uint32_t dq_keep[2];
     auto deq_half = [&](_Float16 *Bn, int p, int w4, int h) {
         const uint32_t u = bw[p][w4] >> (8 * h);
-        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-        u32x2 o;
-        o[0] = g_as_u32((g_as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo[p]) * s2[p]);
-        o[1] = g_as_u32((g_as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi[p]) * s2[p]);
-        *(u32x2 *)&Bn[b_lds[p] + w4 * 8 + h * 4] = o;
+        const uint32_t o0 = g_as_u32((g_as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo[p]) * s2[p]);
+        const uint32_t o1 = g_as_u32((g_as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi[p]) * s2[p]);
+        if (h == 0) { dq_keep[0] = o0; dq_keep[1] = o1; }
+        else {
+            const u32x4 o = {dq_keep[0], dq_keep[1], o0, o1};
+            *(u32x4 *)&Bn[b_lds[p] + w4 * 8] = o;
+        }
     };
 
-    float16v acc[MI][4];
+    float16v acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int jn = 0; jn < 4; ++jn)
+        for (int jn = 0; jn < NI; ++jn)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
     // ---- prologue: K-step 0 into LDS buffer 0, K-step 1 into the registers -------------------
 #pragma unroll
     for (int r = 0; r < AL; ++r) load_a(r, 0);
-    load_b(0, 0); load_b(1, 0);
 #pragma unroll
-    for (int r = 0; r < AL; ++r) *(u32x4 *)&As[a_lds + 32 * r * kLdsRow] = areg[r];
+    for (int p = 0; p < PB; ++p) load_b(p, 0);
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int r = 0; r < AL; ++r) *(u32x4 *)&As[a_lds + kARows * r * kLdsRow] = areg[r];
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
         deq_consts(p, 0);
 #pragma unroll
         for (int w4 = 0; w4 < 4; ++w4) { deq_half(Bs, p, w4, 0); deq_half(Bs, p, w4, 1); }
     }
     {
+        // same order as in the steady state, so that the loop's load counting is exact from the start
         const int k1 = n_ks > 1 ? 1 : 0;
-#pragma unroll
-        for (int r = 0; r < AL; ++r) load_a(r, k1);
-        load_b(0, k1); load_b(1, k1);
+        static_for<kItems>([&](auto KI) {
+            constexpr int code = staging_item<ALP, PB>(KI);
+            if constexpr (code >= 16 && code < 24) load_a(code - 16, k1);
+            else if constexpr (code >= 24) load_b(code - 24, k1);
+        });
     }
     __syncthreads();
 
     const int fr = lane & 31, fh = lane >> 5;
-    const int fa_off = (wm * (BM / 2) + fr) * kLdsRow + fh * 8;
-    const int fb_off = (wn * 128 + fr) * kLdsRow + fh * 8;
-    half8 fa[2][MI], fb[2][4];
-    // fragment `f` (0..MI-1: token tiles, MI..MI+3: output tiles) of MFMA step kk
+    const int fa_off = (wm * MI * 32 + fr) * kLdsRow + fh * 8;
+    const int fb_off = (wn * NI * 32 + fr) * kLdsRow + fh * 8;
+    half8 fa[2][MI], fb[2][NI];
+    // fragment `f` (0..MI-1: token tiles, MI..MI+NI-1: output tiles) of MFMA step kk
     auto read_frag = [&](const _Float16 *Ab, const _Float16 *Bb, int f, int kk, int set) {
         if (f < MI) fa[set][f] = *(const half8 *)&Ab[fa_off + f * 32 * kLdsRow + kk * 16];
         else fb[set][f - MI] = *(const half8 *)&Bb[fb_off + (f - MI) * 32 * kLdsRow + kk * 16];
     };
 #pragma unroll
-    for (int f = 0; f < MI + 4; ++f) read_frag(As, Bs, f, 0, 0);
+    for (int f = 0; f < MI + NI; ++f) read_frag(As, Bs, f, 0, 0);
 
     for (int ks = 0; ks < n_ks; ++ks) {
         const int buf = ks & 1;
@@ -226,24 +244,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
             constexpr int ph = PH;
             static_for<kSlots>([&](auto SL) {
                 constexpr int slot = SL;
-                constexpr int i = slot / 4, jn = slot % 4;
+                constexpr int i = slot / NI, jn = slot % NI;
                 acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ph & 1][i], fb[ph & 1][jn], acc[i][jn], 0, 0, 0);
-                if constexpr (slot < MI + 4) {
+                if constexpr (slot < MI + NI) {
                     if constexpr (ph < 3) read_frag(Ac, Bc, slot, ph + 1, (ph + 1) & 1);
                     else read_frag(An, Bn, slot, 0, 0);
                 }
-                if constexpr (ph < 3) {
-                    // item k is placed at slot floor(k * total_slots / kItems) of phases 0..2
-                    constexpr int gs = ph * kSlots + slot, total = 3 * kSlots;
+                if constexpr (ph < kStagePhases) {
+                    // item k is placed at slot floor(k * total_slots / kItems) of the staging phases
+                    constexpr int gs = ph * kSlots + slot, total = kStagePhases * kSlots;
                     constexpr int k = (gs * kItems + total - 1) / total;
-                    constexpr int code = (k < kItems && k * total / kItems == gs) ? staging_item<AL>(k) : -1;
+                    constexpr int code = (k < kItems && k * total / kItems == gs) ? staging_item<ALP, PB>(k) : -1;
                     if constexpr (code >= 0 && code < 16) {
                         constexpr int p = code / 8, w4 = (code % 8) / 2, h = code % 2;
                         if constexpr (w4 == 0 && h == 0) deq_consts(p, ks_store);
                         deq_half(Bn, p, w4, h);
                     } else if constexpr (code >= 16 && code < 24) {
                         constexpr int r = code - 16;
-                        *(u32x4 *)&An[a_lds + 32 * r * kLdsRow] = areg[r];
+                        *(u32x4 *)&An[a_lds + kARows * r * kLdsRow] = areg[r];
                         load_a(r, ks_load);
                     } else if constexpr (code >= 24) {
                         load_b(code - 24, ks_load);
@@ -258,14 +276,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(GemmArgs a)
     // ---- epilogue: + bias, fp16 store.  Lane (column fr, half fh) holds rows 8b + 4 fh + r. ------
     const __amdgpu_buffer_rsrc_t yr = make_rsrc_g(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
 #pragma unroll
-    for (int jn = 0; jn < 4; ++jn) {
-        const int n = n0 + wn * 128 + jn * 32 + fr;
+    for (int jn = 0; jn < NI; ++jn) {
+        const int n = n0 + wn * NI * 32 + jn * 32 + fr;
         const float bv = (a.bias && n < a.N) ? (float)a.bias[n] : 0.f;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
+                const int m = m0 + wm * MI * 32 + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
                 union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(acc[i][jn][v] + bv);
                 const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.ldy + n) * 2) : kOobG;
                 __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
@@ -281,10 +299,10 @@ bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T)
            w.c_in % kBK == 0;
 }
 
-template <int MI>
-static hipError_t launch_gemm_mi(GemmArgs &a, hipStream_t s)
+template <int MI, int NI, int WM, int WN>
+static hipError_t launch_gemm_cfg(GemmArgs &a, hipStream_t s)
 {
-    constexpr int BM = MI * 64;
+    constexpr int BM = WM * MI * 32;
     a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = (a.N + kBN - 1) / kBN;
     const int m_patches = (a.m_tiles + kPatchM - 1) / kPatchM, n_patches = (a.n_tiles + kPatchN - 1) / kPatchN;
     const int patches = m_patches * n_patches;
@@ -293,12 +311,12 @@ static hipError_t launch_gemm_mi(GemmArgs &a, hipStream_t s)
     const size_t lds = (size_t)2 * (BM + kBN) * kLdsRow * sizeof(_Float16);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel<MI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel<MI, NI, WM, WN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_w4a16_kernel<MI>, dim3(blocks), dim3(kGemmThreads), lds, s, a);
+    hipLaunchKernelGGL((gemm_w4a16_kernel<MI, NI, WM, WN>), dim3(blocks), dim3(WM * WN * 64), lds, s, a);
     return hipGetLastError();
 }
 
@@ -315,11 +333,15 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
     // 256-token tiles unless they leave compute units idle: fewer than one full wave of blocks
     const long big_tiles = (long)((T + 255) / 256) * ((w.c_out + kBN - 1) / kBN);
-    int mi = big_tiles >= 256 ? 4 : 2;
-#ifdef PARO_GEMM_FORCE_MI
-    mi = PARO_GEMM_FORCE_MI;
+    bool big = big_tiles >= 256;
+#ifdef PARO_GEMM_FORCE_BIG
+    big = PARO_GEMM_FORCE_BIG;
 #endif
-    return mi == 4 ? launch_gemm_mi<4>(a, s) : launch_gemm_mi<2>(a, s);
+#ifdef PARO_GEMM_4WAVES
+    return big ? launch_gemm_cfg<4, 4, 2, 2>(a, s) : launch_gemm_cfg<2, 4, 2, 2>(a, s);
+#else
+    return big ? launch_gemm_cfg<4, 2, 2, 4>(a, s) : launch_gemm_cfg<2, 2, 2, 4>(a, s);
+#endif
 }
 
 }  // namespace paro
