@@ -210,12 +210,19 @@ __device__ inline void rotate_layers(const LanePlan<K> &P, float (&a)[TU], float
 constexpr int kRotWaves = 4;   // waves per block
 constexpr int kRotTU = 4;      // tokens in flight per wave
 
+// A wave owns one group and a run of tokens.  Global traffic is one coalesced 4-byte access per
+// lane, token and direction (a group row is 256 contiguous bytes); the permutation between
+// channel order and the plan's lane order goes through a wave-private LDS row (no block
+// barrier: LDS operations of one wave execute in issue order).  The loads of the next batch of
+// tokens are issued before the current batch is rotated.  Rows are read completely before any of
+// them is written, so X and Xr may be the same buffer.
 template <int K>
 __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const uint32_t *__restrict__ plan,
                                                                          const _Float16 *X, int64_t ldx,
                                                                          _Float16 *Xr, int64_t ldxr, int T,
                                                                          int tokens_per_wave)
 {
+    __shared__ _Float16 s_stage[kRotWaves][kRotTU][kGroup];
     const int g = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -223,27 +230,44 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
     if (t0 >= T) return;
     const int t1 = min(T, t0 + tokens_per_wave);
 
+    const uint32_t *xg = (const uint32_t *)(X + (size_t)g * kGroup) + lane;     // rows are 16-byte aligned
+    uint32_t *yg = (uint32_t *)(Xr + (size_t)g * kGroup) + lane;
+    uint32_t cur[kRotTU], nxt[kRotTU];
+#pragma unroll
+    for (int u = 0; u < kRotTU; ++u) cur[u] = xg[(size_t)min(t0 + u, t1 - 1) * (ldx / 2)];
+
     LanePlan<K> P;
     load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
+    _Float16(*st)[kGroup] = s_stage[wave];
 
-    const _Float16 *xg = X + (size_t)g * kGroup;
-    _Float16 *yg = Xr + (size_t)g * kGroup;
     for (int t = t0; t < t1; t += kRotTU) {
+#pragma unroll
+        for (int u = 0; u < kRotTU; ++u) nxt[u] = xg[(size_t)min(t + kRotTU + u, t1 - 1) * (ldx / 2)];
+#pragma unroll
+        for (int u = 0; u < kRotTU; ++u) *(uint32_t *)&st[u][2 * lane] = cur[u];
+        __builtin_amdgcn_wave_barrier();
         float a[kRotTU], b[kRotTU];
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) {
-            int tt = min(t + u, t1 - 1);
-            a[u] = (float)xg[(size_t)tt * ldx + P.in_a] * P.sia;
-            b[u] = (float)xg[(size_t)tt * ldx + P.in_b] * P.sib;
+            a[u] = (float)st[u][P.in_a] * P.sia;
+            b[u] = (float)st[u][P.in_b] * P.sib;
         }
         rotate_layers<K, kRotTU>(P, a, b);
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) {
-            if (t + u < t1) {
-                yg[(size_t)(t + u) * ldxr + P.out_a] = (_Float16)(a[u] * P.soa);
-                yg[(size_t)(t + u) * ldxr + P.out_b] = (_Float16)(b[u] * P.sob);
-            }
+            st[u][P.out_a] = (_Float16)(a[u] * P.soa);
+            st[u][P.out_b] = (_Float16)(b[u] * P.sob);
         }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < kRotTU; ++u) {
+            const uint32_t o = *(const uint32_t *)&st[u][2 * lane];
+            if (t + u < t1) yg[(size_t)(t + u) * (ldxr / 2)] = o;
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < kRotTU; ++u) cur[u] = nxt[u];
     }
 }
 
@@ -252,9 +276,13 @@ static hipError_t launch_rotate_k(const paro_rotation &rot, const paro_half_t *X
                                   int64_t ldxr, int T, hipStream_t s)
 {
     int G = rot.c_in / kGroup;
-    // enough waves to fill 256 CUs several times over, but at least kRotTU tokens per wave
-    int tpw = 8;
-    while (tpw > 1 && (int64_t)G * ((T + tpw - 1) / tpw) < 4096) tpw >>= 1;
+    // the plan (7.4 KB per wave at K = 8) is re-read by every wave: long token runs per wave, as
+    // long as there are still enough waves to fill 256 CUs several times over
+    int tpw = 32;
+    while (tpw > kRotTU && (int64_t)G * ((T + tpw - 1) / tpw) < 4096) tpw >>= 1;
+#ifdef PARO_ROT_TPW
+    tpw = PARO_ROT_TPW;
+#endif
     int waves_t = (T + tpw - 1) / tpw;
     dim3 grid(G, (waves_t + kRotWaves - 1) / kRotWaves);
     hipLaunchKernelGGL(rotate_planned_kernel<K>, grid, dim3(kRotWaves * 64), 0, s, (const uint32_t *)rot.plan,
