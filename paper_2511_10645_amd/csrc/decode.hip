@@ -152,10 +152,10 @@ __device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGrou
 // written and read with agent-scope accesses and reset to empty by its reader.  A reader polls
 // a word until it fills; the writers are the blocks dispatched next to it, which never wait on
 // anything before writing.  The poll is bounded; a word that never fills is reported as NaN.
-template <int THREADS>
 __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, int tile_lo, int tile_hi, float *s_red)
 {
 #ifndef PARO_EXP_NO_FINALIZE
+    const int THREADS = blockDim.x;                 // >= 256: kReducePerThread requests per thread cover a round
     const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
     const int outputs = a.T * width;
     const int share = (outputs + parts - 1) / parts;
@@ -165,7 +165,7 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
         const int n_out = min(round_outputs, o_hi - base);
         __syncthreads();
         // all of a thread's words are requested before any is examined: one round trip
-        constexpr int PER = kReduceWords / THREADS;
+        constexpr int PER = kReducePerThread;
         uint32_t bits[PER];
         uint32_t *ptr[PER];
 #pragma unroll
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
     }
 
     // ---- split-K: exchange with the other K-slices of this output range ----------------------
-    if constexpr (SPLIT) splitk_reduce<kDecThreads>(a, a.KS, ks, tile_lo, tile_hi, s_red);
+    if constexpr (SPLIT) splitk_reduce(a, a.KS, ks, tile_lo, tile_hi, s_red);
 }
 
 DecodeGeometry decode_geometry(int c_in, int c_out, int T)
@@ -445,7 +445,10 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
 // for 5..16 tokens, where partial sums (T x N fp32 per K-part) would otherwise rival the
 // weight stream.  The transform, if any, has run as a separate pass.
 // ------------------------------------------------------------------------------------------
-constexpr int kWideWaves = 8;
+#ifndef PARO_WIDE_WAVES
+#define PARO_WIDE_WAVES 12
+#endif
+constexpr int kWideWaves = PARO_WIDE_WAVES;     // most K-slices (waves) of one block
 constexpr int kWideThreads = kWideWaves * 64;
 
 template <bool SPLIT, bool T1>
@@ -454,7 +457,8 @@ __global__ __launch_bounds__(kWideThreads) void decode_wide_kernel(DecodeArgs a)
     extern __shared__ __attribute__((aligned(16))) float s_wide[];      // [n_iter][8 waves][256] + reduce scratch
     const int kb = blockIdx.x, nb = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int ks = kb * kWideWaves + wave;
+    const int nw = blockDim.x >> 6;                                        // K-slices (waves) per block, <= 8
+    const int ks = kb * nw + wave;
     const bool slice_ok = ks < a.KS;
     const int tile_lo = nb * a.tiles_per_block;
     const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
@@ -500,7 +504,7 @@ __global__ __launch_bounds__(kWideThreads) void decode_wide_kernel(DecodeArgs a)
     // partial tile of (iteration i, this wave): element lane*4 + r <-> token 4*(lane/16)+r, row lane%16
     auto emit = [&](const Stage &stg, int i) {
         float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
-        float *dst = s_wide + ((size_t)i * kWideWaves + wave) * 256 + lane * 4;
+        float *dst = s_wide + ((size_t)i * nw + wave) * 256 + lane * 4;
         if constexpr (T1) { if (lane < 16) dst[0] = tot[0]; }
         else *(float4v *)dst = tot;
     };
@@ -520,13 +524,12 @@ __global__ __launch_bounds__(kWideThreads) void decode_wide_kernel(DecodeArgs a)
 
     // ---- sum the 8 K-slices; outputs indexed (i, t, n) with n fastest for coalesced stores -----
     const int per_tile = a.T * kTileN;
-    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += kWideThreads) {
+    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += blockDim.x) {
         const int i = idx / per_tile, rem = idx % per_tile;
         const int t = rem / kTileN, nn = rem % kTileN;
         const int e = ((t >> 2) * 16 + nn) * 4 + (t & 3);
         float sum = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWideWaves; ++w) sum += s_wide[((size_t)i * kWideWaves + w) * 256 + e];
+        for (int w = 0; w < nw; ++w) sum += s_wide[((size_t)i * nw + w) * 256 + e];
         const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
         if constexpr (!SPLIT) {
             if (a.bias) sum += (float)a.bias[n];
@@ -539,22 +542,25 @@ __global__ __launch_bounds__(kWideThreads) void decode_wide_kernel(DecodeArgs a)
         }
     }
     if constexpr (SPLIT)
-        splitk_reduce<kWideThreads>(a, gridDim.x, kb, tile_lo, tile_hi, s_wide + (size_t)kMaxIter * kWideWaves * 256);
+        splitk_reduce(a, gridDim.x, kb, tile_lo, tile_hi, s_wide + (size_t)kMaxIter * nw * 256);
 }
 
-struct WideGeometry { int kb, nb, tiles_per_block; size_t lds; };
+struct WideGeometry { int kb, nb, waves, tiles_per_block; size_t lds; };
 static WideGeometry wide_geometry(int c_in, int c_out)
 {
     WideGeometry g;
     const int KS = c_in / kGroup / kSliceGroups, NT = c_out / kTileN;
-    g.kb = (KS + kWideWaves - 1) / kWideWaves;
-    int nb = 256 / g.kb;                      // one 8-wave block per CU
+    // up to 12 slices fit one block (3 waves per SIMD): no exchange between blocks at all.  Beyond
+    // that the slices are spread evenly over blocks of at most 8 waves.
+    g.kb = KS <= kWideWaves ? 1 : (KS + 7) / 8;
+    g.waves = (KS + g.kb - 1) / g.kb;
+    int nb = (g.waves > 8 ? 256 : 2048 / g.waves) / g.kb;   // about 8 waves per CU; one block per CU beyond 8 waves
     if (nb < 1) nb = 1;
     int tpb = (NT + nb - 1) / nb;
     if (tpb > kMaxIter) tpb = kMaxIter;
     g.tiles_per_block = tpb;
     g.nb = (NT + tpb - 1) / tpb;
-    g.lds = ((size_t)kMaxIter * kWideWaves * 256 + kReduceWords) * sizeof(float);
+    g.lds = ((size_t)kMaxIter * g.waves * 256 + kReduceWords) * sizeof(float);
     return g;
 }
 
@@ -590,12 +596,13 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
         const void *fns[4] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
                               (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>};
         for (const void *f : fns) {
-            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds);
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)(((size_t)kMaxIter * kWideWaves * 256 + kReduceWords) * sizeof(float)));
             if (e != hipSuccess) return e;
         }
         attr_set = true;
     }
-    const dim3 grid(g.kb, g.nb), block(kWideThreads);
+    const dim3 grid(g.kb, g.nb), block(g.waves * 64);
     if (T == 1) {
         if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, true>), grid, block, g.lds, s, a);
         else          hipLaunchKernelGGL((decode_wide_kernel<false, true>), grid, block, g.lds, s, a);
