@@ -134,6 +134,24 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
                                 const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                                 int32_t T, void *ws, size_t ws_bytes, void *stream);
 
+/* Offline, weight side (Eq. 8 then Eq. 1; Section 2.1 group rule) ----------------------------
+ * Quantise a dense fp16 weight W[c_out][c_in] (row n = output channel n at W + n*ldw, device)
+ * into the interchange layout of paro_w4_weight:
+ *      w'_n = R_K ... R_1 . diag(1/ch_scale) . w_n      (the weight-side counterpart of what
+ *                                                         paro_rotate_scale does to activations;
+ *                                                         scale_order 1: diag(1/ch_scale) last)
+ *      per 128 input channels of a row:  s = (max - min)/15,  z = -round(min/s),
+ *                                        q = clamp(round(w'/s) + z, 0, 15)          (Eq. 1, b = 4)
+ * rot == NULL quantises W as it is.  A rotation needs its plan (PARO_ERR_UNSUPPORTED otherwise).
+ * Arithmetic: rotation in fp32; s, z, q decided in fp32 with the fp16-rounded scale that is
+ * stored, round-half-to-even; s >= 2^-14; z clamped to 0..15.
+ * Outputs (device, written completely): qweight [c_out][c_in/8], scales [c_in/128][c_out],
+ * qzeros [c_in/128][c_out/8].  c_in % 128 == 0, c_out % 8 == 0, ldw >= c_in and even, W 4-byte
+ * aligned.  Enqueues on `stream`; no workspace. */
+paro_status paro_w4_quantize(const paro_rotation *rot, const paro_half_t *W, int64_t ldw,
+                             int32_t c_in, int32_t c_out, uint32_t *qweight, paro_half_t *scales,
+                             uint32_t *qzeros, void *stream);
+
 /* Test hooks for the bit-exact gate --------------------------------------------------- */
 
 /* codes[n][c] = q[n, c] as bytes 0..15 (from w->packed if set, else from w->qweight). */

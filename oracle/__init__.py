@@ -130,6 +130,50 @@ def rotate_inplace(u, pairs, theta, group=128) -> np.ndarray:
     return u
 
 
+def weight_transform(w16, pairs, theta, ch_scale16=None, group=128, scale_order=0) -> np.ndarray:
+    """wt = R_K ... R_1 . diag(1/ch_scale) . w per output row and group, fp64 [N][C]  (Eq. 8, weight side).
+
+    ``pairs`` / ``theta`` None: no rotation (scaling only, or the identity).
+    """
+    wb = _bits(w16)
+    N, C = wb.shape
+    if pairs is None:
+        pairs = np.zeros((C // group, 0, 1, 2), dtype=np.int16)
+        theta = np.zeros((C // group, 0, 1), dtype=np.float32)
+    pairs = _c(pairs, np.int16)
+    theta = _c(theta, np.float32)
+    G, K, P, two = pairs.shape
+    assert two == 2 and G * group == C and theta.shape == (G, K, P)
+    sb = _bits(ch_scale16)
+    wt = np.empty((N, C), dtype=np.float64)
+    L = lib()
+    L.oracle_weight_transform.restype = ctypes.c_int
+    rc = L.oracle_weight_transform(_p(wb, ctypes.c_uint16), ctypes.c_int64(C), ctypes.c_int32(N), ctypes.c_int32(C),
+                                   ctypes.c_int32(group), ctypes.c_int32(K), ctypes.c_int32(P),
+                                   _p(pairs, ctypes.c_int16), _p(theta, ctypes.c_float),
+                                   _p(sb, ctypes.c_uint16), ctypes.c_int32(scale_order),
+                                   _p(wt, ctypes.c_double), ctypes.c_int64(C))
+    if rc != 0:
+        raise ValueError("pair index out of range")
+    return wt
+
+
+def rtn_quantize(wt: np.ndarray, group=128):
+    """Eq. 1 per (row, group): returns codes uint8 [N][C], scales fp16 [G][N], zeros uint8 [G][N]."""
+    wt = _c(wt, np.float64)
+    N, C = wt.shape
+    G = C // group
+    codes = np.empty((N, C), dtype=np.uint8)
+    scales = np.empty((G, N), dtype=np.uint16)
+    zeros = np.empty((G, N), dtype=np.uint8)
+    L = lib()
+    L.oracle_rtn_quantize.restype = None
+    L.oracle_rtn_quantize(_p(wt, ctypes.c_double), ctypes.c_int64(C), ctypes.c_int32(N), ctypes.c_int32(C),
+                          ctypes.c_int32(group), _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint16),
+                          _p(zeros, ctypes.c_uint8))
+    return codes, scales.view(np.float16), zeros
+
+
 def unpack_codes(qweight: np.ndarray) -> np.ndarray:
     q = _c(qweight, np.uint32)
     N, C8 = q.shape

@@ -24,6 +24,8 @@
  *                                           inverse scale first, then the
  *                                           rotations, layer 1 first
  *   Def. 1                                 : pairs of one layer are disjoint
+ *   Eq. 1, Eq. 8 (weight side)             : W' = R_K ... R_1 . diag(alpha) . W per
+ *                                           output row, then RTN per group
  *
  * Readings where the paper leaves a choice
  *   - theta on the activation side.  Eq. 5 right-multiplies a row vector by
@@ -44,6 +46,8 @@
  * explicit dense-matrix formulation multiplied by a library matmul; theta = 0,
  * scale = 1 reduces to numpy's X @ W^T; brute-force Eq. 2 on tiny unquantised
  * inputs; exhaustive unpack; exhaustive fp64->fp16 rounding against numpy.
+ * Weight side: hand-computed RTN groups, the s/2 error bound of Eq. 1, and
+ * transformed weights times transformed activations reproducing W.x (Eq. 2).
  * The paper's accuracy tables are not on this path: parity unpinned for them.
  */
 #include <math.h>
@@ -166,6 +170,82 @@ int oracle_rotate_scale(const uint16_t *x16, int64_t ldx, int32_t T, int32_t C,
         for (int32_t t = 0; t < T; ++t)
             for (int32_t c = 0; c < C; ++c) u[(int64_t)t * ldu + c] *= oracle_fp16_to_f64(ch_scale16[c]);
     return 0;
+}
+
+/* ---- weight side: equivalent transform (Eq. 8) and RTN quantiser (Eq. 1) -- */
+
+/*
+ * wt[n][c] = ( R_K ... R_1 . diag(alpha) . w_n )[c]      (scale_order == 0, the paper: Eq. 8)
+ *          = ( diag(alpha) . R_K ... R_1 . w_n )[c]      (scale_order == 1)
+ * with alpha = 1 / ch_scale: the weight-side counterpart of oracle_rotate_scale, so that
+ * wt_n . u = w_n . x when u is the transformed activation vector (Eq. 2).  w16: fp16 bits,
+ * row n (one output channel, C input channels) at w16 + n*ldw.
+ */
+int oracle_weight_transform(const uint16_t *w16, int64_t ldw, int32_t N, int32_t C,
+                            int32_t group, int32_t n_layers, int32_t ppl,
+                            const int16_t *pairs, const float *theta,
+                            const uint16_t *ch_scale16, int32_t scale_order,
+                            double *wt, int64_t ldwt)
+{
+    for (int32_t n = 0; n < N; ++n)
+        for (int32_t c = 0; c < C; ++c) {
+            double v = oracle_fp16_to_f64(w16[(int64_t)n * ldw + c]);
+            if (scale_order == 0 && ch_scale16) v /= oracle_fp16_to_f64(ch_scale16[c]);
+            wt[(int64_t)n * ldwt + c] = v;
+        }
+    if (n_layers > 0) {
+        int rc = oracle_rotate_inplace(wt, ldwt, N, C, group, n_layers, ppl, pairs, theta);
+        if (rc) return rc;
+    }
+    if (scale_order == 1 && ch_scale16)
+        for (int32_t n = 0; n < N; ++n)
+            for (int32_t c = 0; c < C; ++c) wt[(int64_t)n * ldwt + c] /= oracle_fp16_to_f64(ch_scale16[c]);
+    return 0;
+}
+
+/*
+ * Eq. 1 with b = 4, one (s, z) per `group` consecutive input channels of one output row:
+ *      s = (max - min) / 15,   z = -round(min / s),   q = clamp(round(w / s) + z, 0, 15).
+ * Readings (the paper gives the formula only):
+ *   - the decisions that produce integers are taken in fp32 on the fp32-rounded input (the
+ *     paper names no precision; this is the precision of the GPU quantiser), division and
+ *     round-half-to-even (rintf) as written;
+ *   - the scale is stored as fp16, and z and q are computed with the STORED value, so that
+ *     (q - z) * s reproduces w to within s/2 wherever nothing was clamped;
+ *   - s has the floor 2^-14 (smallest normal fp16), which also covers constant groups;
+ *   - z is an INT4 value: clamped to 0..15.
+ * codes: [N][C] bytes; scales16: [G][N] fp16 bits; zeros: [G][N] bytes.
+ */
+void oracle_rtn_quantize(const double *wt, int64_t ldwt, int32_t N, int32_t C, int32_t group,
+                         uint8_t *codes, uint16_t *scales16, uint8_t *zeros)
+{
+    int32_t G = C / group;
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < N; ++n)
+        for (int32_t g = 0; g < G; ++g) {
+            const double *wg = wt + (int64_t)n * ldwt + (int64_t)g * group;
+            float mn = (float)wg[0], mx = (float)wg[0];
+            for (int32_t c = 1; c < group; ++c) {
+                float v = (float)wg[c];
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+            float s32 = (mx - mn) / 15.0f;
+            if (!(s32 >= 6.103515625e-05f)) s32 = 6.103515625e-05f;
+            uint16_t sb = oracle_f64_to_fp16((double)s32);
+            float s = (float)oracle_fp16_to_f64(sb);
+            float zf = -rintf(mn / s);
+            if (zf < 0.0f) zf = 0.0f;
+            if (zf > 15.0f) zf = 15.0f;
+            scales16[(int64_t)g * N + n] = sb;
+            zeros[(int64_t)g * N + n] = (uint8_t)zf;
+            for (int32_t c = 0; c < group; ++c) {
+                float q = rintf((float)wg[c] / s) + zf;
+                if (q < 0.0f) q = 0.0f;
+                if (q > 15.0f) q = 15.0f;
+                codes[(int64_t)n * C + (int64_t)g * group + c] = (uint8_t)q;
+            }
+        }
 }
 
 /* ---- INT4 unpack and dequantisation (Eq. 1 inverted, group rule) --------- */

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     paro_validate_pairs_host,
     paro_version,
     paro_w4_dequant,
+    paro_w4_quantize,
     paro_w4_repack,
     paro_w4_unpack_codes,
     paro_w4_unpack_zeros,

@@ -69,11 +69,12 @@ def lib():
         L.paro_w4_unpack_codes.argtypes = [wp, vp, vp]
         L.paro_w4_unpack_zeros.argtypes = [wp, vp, vp]
         L.paro_w4_dequant.argtypes = [wp, vp, vp]
+        L.paro_w4_quantize.argtypes = [rp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.paro_tune_decode_waves.argtypes = [ctypes.c_int]
         L.paro_tune_decode_waves.restype = None
         for name in ("paro_validate_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
-                     "paro_w4_dequant"):
+                     "paro_w4_dequant", "paro_w4_quantize"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -152,6 +153,17 @@ class W4Weight:
         self.c = _CW4Weight(self.c_in, self.c_out, group, _ptr(self.qweight), _ptr(self.scales), _ptr(self.qzeros),
                             _ptr(self.bias), None)
 
+    @classmethod
+    def from_device(cls, qweight: torch.Tensor, scales: torch.Tensor, qzeros: torch.Tensor, bias=None, group: int = 128):
+        """Wrap interchange-layout tensors that already live on the device (int32 / fp16 / int32)."""
+        w = cls.__new__(cls)
+        w.c_out, c8 = qweight.shape
+        w.c_in = c8 * 8
+        assert scales.shape == (w.c_in // group, w.c_out) and qzeros.shape == (w.c_in // group, w.c_out // 8)
+        w.qweight, w.scales, w.qzeros, w.bias, w.packed = qweight, scales, qzeros, bias, None
+        w.c = _CW4Weight(w.c_in, w.c_out, group, _ptr(qweight), _ptr(scales), _ptr(qzeros), _ptr(bias), None)
+        return w
+
     def ref(self):
         return ctypes.byref(self.c)
 
@@ -188,6 +200,19 @@ def paro_w4_repack(w: W4Weight) -> None:
     _check(lib().paro_w4_repack(w.ref(), blob.data_ptr(), _stream()), "paro_w4_repack")
     w.packed = blob
     w.c.packed = blob.data_ptr()
+
+
+def paro_w4_quantize(rot: Rotation | None, W: torch.Tensor, group: int = 128) -> W4Weight:
+    """Transform (Eq. 8, weight side) and RTN-quantise (Eq. 1) a dense fp16 weight [c_out][c_in]."""
+    assert W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
+    c_out, c_in = W.shape
+    qweight = torch.empty((c_out, c_in // 8), dtype=torch.int32, device=W.device)
+    scales = torch.empty((c_in // group, c_out), dtype=torch.float16, device=W.device)
+    qzeros = torch.empty((c_in // group, c_out // 8), dtype=torch.int32, device=W.device)
+    _check(lib().paro_w4_quantize(rot.ref() if rot is not None else None, W.data_ptr(), W.stride(0), c_in, c_out,
+                                  qweight.data_ptr(), scales.data_ptr(), qzeros.data_ptr(), _stream()),
+           "paro_w4_quantize")
+    return W4Weight.from_device(qweight, scales, qzeros, group=group)
 
 
 def paro_workspace_bytes(rot: Rotation | None, w: W4Weight, T: int) -> int:

@@ -257,6 +257,22 @@ paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *strea
     return from_hip(launch_dequant(*w, W, (hipStream_t)stream));
 }
 
+paro_status paro_w4_quantize(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int32_t c_in, int32_t c_out,
+                             uint32_t *qweight, paro_half_t *scales, uint32_t *qzeros, void *stream)
+{
+    if (!W || !qweight || !scales || !qzeros) return PARO_ERR_NULL;
+    if (c_in <= 0 || c_out <= 0 || c_in % paro::kGroup || c_out % 8 || ldw < c_in) return PARO_ERR_SHAPE;
+    if (ldw % 2 || !aligned(W, 4) || !aligned(qweight, 4) || !aligned(scales, 2) || !aligned(qzeros, 4))
+        return PARO_ERR_ALIGN;
+    if (rot) {
+        paro_status st = check_rotation(rot);
+        if (st != PARO_OK) return st;
+        if (rot->c_in != c_in) return PARO_ERR_SHAPE;
+        if (!rot->plan) return PARO_ERR_UNSUPPORTED;
+    }
+    return from_hip(paro::launch_quantize(rot, W, ldw, c_out, c_in, qweight, scales, qzeros, (hipStream_t)stream));
+}
+
 // Tuning knob (process-wide, not thread-safe): target number of wavefronts of a decode launch.
 void paro_tune_decode_waves(int waves) { paro::set_decode_target_waves(waves); }
 

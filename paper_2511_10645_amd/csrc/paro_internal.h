@@ -108,6 +108,10 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
 hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                                  paro_half_t *Y, int64_t ldy, int T, hipStream_t s);
 
+// Weight-side transform + RTN quantiser (rot == nullptr: no transform; otherwise rot->plan is set).
+hipError_t launch_quantize(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int N, int C, uint32_t *qweight,
+                           paro_half_t *scales, uint32_t *qzeros, hipStream_t s);
+
 // Prefill-side linear (MFMA GEMM on the repacked weight), any T.
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T);
 hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,

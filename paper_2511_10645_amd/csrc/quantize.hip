@@ -1,0 +1,122 @@
+// Weight side of the method, offline: the equivalent transform of Eq. 8 applied to every output
+// row of a dense fp16 weight, then the round-to-nearest INT4 quantiser of Eq. 1 with one
+// (scale, zero) per 128 input channels (Section 2.1), written in the interchange layout that
+// paro_w4_repack and the linear kernels consume.
+//
+//      w'_n = R_K ... R_1 . diag(1 / ch_scale) . w_n          (scale_order 0; Eq. 8, weight side)
+//      s = (max - min) / 15,  z = -round(min / s),  q = clamp(round(w' / s) + z, 0, 15)
+//
+// so that  sum_c (q - z) s . x'_c  ~  w_n . x  for the activations x' = R_K ... R_1 . S . x that
+// paro_rotate_scale produces (Eq. 2).  One wavefront per (row, group), exactly as the
+// activation kernel: the lane's two fp32 registers hold the pair being rotated; the group's
+// minimum and maximum are wave reductions.  The integer decisions are taken in fp32 with the
+// fp16-rounded scale that is stored (IEEE division, round-half-to-even); the scale has the
+// floor 2^-14; the zero point is clamped to 0..15.  A block handles 8 consecutive rows of one
+// group, so that their 8 zero points fill one output word.
+#include "paro_internal.h"
+#include "rotate_lane.h"
+
+namespace paro {
+
+constexpr int kQuantRows = 8;      // rows (waves) per block = zero points per packed word
+
+// K >= 0: rotation with K layers from the plan; K < 0: no transform (plain RTN).
+template <int K>
+__global__ __launch_bounds__(kQuantRows * 64) void quantize_rows_kernel(const uint32_t *__restrict__ plan,
+                                                                         const _Float16 *__restrict__ W, int64_t ldw,
+                                                                         int N, int C, uint32_t *__restrict__ qweight,
+                                                                         _Float16 *__restrict__ scales,
+                                                                         uint32_t *__restrict__ qzeros)
+{
+    __shared__ _Float16 s_stage[kQuantRows][kGroup];
+    __shared__ uint8_t s_codes[kQuantRows][kGroup];
+    __shared__ uint32_t s_z[kQuantRows];
+    __shared__ _Float16 s_s[kQuantRows];
+    const int g = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = blockIdx.y * kQuantRows + wave;      // N is a multiple of 8
+
+    // the row's 128 channels of this group, two per lane in channel order
+    const uint32_t raw = *((const uint32_t *)(W + (size_t)n * ldw + (size_t)g * kGroup) + lane);
+    float va, vb;
+    int ch_a, ch_b;
+    if constexpr (K >= 0) {
+        LanePlan<K> P;
+        load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
+        *(uint32_t *)&s_stage[wave][2 * lane] = raw;
+        __builtin_amdgcn_wave_barrier();
+        // the plan carries the activation-side multipliers; the weights take their reciprocals
+        float a[1] = {(float)s_stage[wave][P.in_a] * (1.0f / P.sia)};
+        float b[1] = {(float)s_stage[wave][P.in_b] * (1.0f / P.sib)};
+        rotate_layers<K, 1>(P, a, b);
+        va = a[0] * (1.0f / P.soa); vb = b[0] * (1.0f / P.sob);
+        ch_a = P.out_a; ch_b = P.out_b;
+    } else {
+        union { uint32_t u; _Float16 h[2]; } c; c.u = raw;
+        va = (float)c.h[0]; vb = (float)c.h[1];
+        ch_a = 2 * lane; ch_b = 2 * lane + 1;
+    }
+
+    // Eq. 1 on the group
+    float mn = fminf(va, vb), mx = fmaxf(va, vb);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, off, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    }
+    float s32 = (mx - mn) / 15.0f;
+    if (!(s32 >= 6.103515625e-05f)) s32 = 6.103515625e-05f;
+    const _Float16 s16 = (_Float16)s32;
+    const float s = (float)s16;
+    float zf = -rintf(mn / s);
+    zf = fminf(fmaxf(zf, 0.0f), 15.0f);
+    const float qa = fminf(fmaxf(rintf(va / s) + zf, 0.0f), 15.0f);
+    const float qb = fminf(fmaxf(rintf(vb / s) + zf, 0.0f), 15.0f);
+    s_codes[wave][ch_a] = (uint8_t)qa;
+    s_codes[wave][ch_b] = (uint8_t)qb;
+    if (lane == 0) { s_z[wave] = (uint32_t)zf; s_s[wave] = s16; }
+    __syncthreads();
+
+    if (lane < kGroup / 8) {        // 16 words of 8 codes, code k of a word in bits 4k..4k+3
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) word |= (uint32_t)s_codes[wave][lane * 8 + k] << (4 * k);
+        qweight[(size_t)n * (C / 8) + (size_t)g * (kGroup / 8) + lane] = word;
+    }
+    if (threadIdx.x < kQuantRows) scales[(size_t)g * N + (size_t)blockIdx.y * kQuantRows + threadIdx.x] = s_s[threadIdx.x];
+    if (threadIdx.x == 0) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < kQuantRows; ++k) word |= s_z[k] << (4 * k);
+        qzeros[(size_t)g * (N / 8) + blockIdx.y] = word;
+    }
+}
+
+template <int K>
+static hipError_t launch_quantize_k(const uint32_t *plan, const paro_half_t *W, int64_t ldw, int N, int C,
+                                    uint32_t *qweight, paro_half_t *scales, uint32_t *qzeros, hipStream_t s)
+{
+    hipLaunchKernelGGL(quantize_rows_kernel<K>, dim3(C / kGroup, N / kQuantRows), dim3(kQuantRows * 64), 0, s, plan,
+                       (const _Float16 *)W, ldw, N, C, qweight, (_Float16 *)scales, qzeros);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int N, int C, uint32_t *qweight,
+                           paro_half_t *scales, uint32_t *qzeros, hipStream_t s)
+{
+    if (!rot) return launch_quantize_k<-1>(nullptr, W, ldw, N, C, qweight, scales, qzeros, s);
+    const uint32_t *plan = (const uint32_t *)rot->plan;
+    switch (rot->n_layers) {
+    case 0: return launch_quantize_k<0>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 1: return launch_quantize_k<1>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 2: return launch_quantize_k<2>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 3: return launch_quantize_k<3>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 4: return launch_quantize_k<4>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 5: return launch_quantize_k<5>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 6: return launch_quantize_k<6>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    case 7: return launch_quantize_k<7>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    default: return launch_quantize_k<8>(plan, W, ldw, N, C, qweight, scales, qzeros, s);
+    }
+}
+
+}  // namespace paro

@@ -202,3 +202,17 @@ def make_custom(seed: int, tokens: int, c_in: int, c_out: int, n_layers: int = N
     zeros = rs.integers(0, 16, size=(g, c_out), dtype=np.uint8)
     return LinearInputs(LinearShape(f"custom{seed}", c_in, c_out), tokens, x.astype(np.float16), pairs, theta,
                         ch_scale, codes, pack_nibbles_u32(codes), scales, zeros, pack_nibbles_u32(zeros), out_ch)
+
+
+def make_dense_weight(seed: int, c_out: int, c_in: int, sigma: float = 0.02, outlier_frac: float = 0.005,
+                      outlier_mult: float = 20.0) -> np.ndarray:
+    """Dense fp16 weight [c_out][c_in] for the weight-side quantiser: N(0, sigma) with a fraction of
+    isolated elements multiplied by ``outlier_mult`` (stands in for the outlier-heavy pre-trained
+    weights the method targets; real checkpoints are not available)."""
+    rs = np.random.Generator(np.random.PCG64(seed))
+    w = rs.standard_normal((c_out, c_in), dtype=np.float32) * np.float32(sigma)
+    n_out = int(round(outlier_frac * w.size))
+    if n_out:
+        idx = rs.choice(w.size, size=n_out, replace=False)
+        w.reshape(-1)[idx] *= np.float32(outlier_mult)
+    return w.astype(np.float16)

@@ -114,3 +114,19 @@ def test_prepare_calls_argument_errors():
     assert L.paro_w4_repack(ctypes.byref(_w(qweight=None, packed=FAKE)), FAKE, None) == E_NULL
     assert L.paro_w4_unpack_codes(ctypes.byref(_w()), None, None) == E_NULL
     assert L.paro_w4_dequant(ctypes.byref(_w()), FAKE + 2, None) == E_ALIGN
+
+
+def test_quantize_argument_errors():
+    L = paro.lib()
+    qz = lambda rot=None, W=FAKE, ldw=512, c_in=512, c_out=64, qw=FAKE, sc=FAKE, z=FAKE: L.paro_w4_quantize(
+        None if rot is None else ctypes.byref(rot), W, ldw, c_in, c_out, qw, sc, z, None)
+    assert qz(W=None) == E_NULL
+    assert qz(qw=None) == E_NULL
+    assert qz(c_in=500) == E_SHAPE
+    assert qz(c_out=60) == E_SHAPE
+    assert qz(ldw=256) == E_SHAPE
+    assert qz(ldw=513) == E_ALIGN
+    assert qz(W=FAKE + 2) == E_ALIGN
+    assert qz(rot=_rot(c_in=1024)) == E_SHAPE            # rot.c_in != c_in
+    assert qz(rot=_rot()) == E_UNSUP                      # a rotation without its plan
+    assert qz(rot=_rot(n_layers=9)) == E_UNSUP
