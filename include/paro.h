@@ -91,6 +91,21 @@ const char *paro_status_string(paro_status s);
 paro_status paro_validate_pairs_host(const int16_t *pairs_host, int32_t n_groups, int32_t n_layers,
                                      int32_t pairs_per_layer, int32_t group);
 
+/* Selection of independent channel pairs for a series of K rotations of one channel group
+ * (Algorithm A1, Section 4.1.2), on the HOST.  The algorithm's one random draw, the shuffle of
+ * all g(g-1)/2 pairs, is an input: `order_host` is a permutation of 0..g(g-1)/2-1 over the
+ * pairs (i, j), 0 <= i < j < g, numbered in lexicographic order ((0,1) = 0, (0,2) = 1, ...).
+ * For each rotation in turn the shuffled list is scanned from its start and a pair is taken when
+ * neither of its channels is used yet in this rotation and the pair was not taken by an earlier
+ * rotation, until `pairs_per_rotation` pairs are found or the list ends.
+ * pairs_out_host: [n_rotations][pairs_per_rotation][2] int16, selection order, i < j; slots that
+ * stay empty hold (0, 0), the no-op spelling of paro_rotation.  counts_out_host (nullable):
+ * [n_rotations] pairs found.  2 <= group <= 1024, pairs_per_rotation <= group/2.
+ * Returns PARO_OK, PARO_ERR_NULL, PARO_ERR_SHAPE, PARO_ERR_PAIRS (order is not a permutation). */
+paro_status paro_select_pairs_host(const int32_t *order_host, int32_t group, int32_t n_rotations,
+                                   int32_t pairs_per_rotation, int16_t *pairs_out_host,
+                                   int32_t *counts_out_host);
+
 /* One-time preparation (model-load side) ------------------------------------------------ */
 
 /* Size in bytes of the rotation plan for `rot` (0 on invalid arguments). */

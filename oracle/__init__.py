@@ -248,3 +248,34 @@ def linear_samples(u, qweight, scales16, qzeros, t_idx, n_idx, bias16=None, grou
                                 _p(t_idx, ctypes.c_int32), _p(n_idx, ctypes.c_int32), ctypes.c_int64(t_idx.size),
                                 _p(y, ctypes.c_double), _p(ww, ctypes.c_double))
     return y, ww
+
+
+def select_pairs(order, group: int, n_rotations: int, pairs_per_rotation: int):
+    """Selection of independent channel pairs, Algorithm A1 (Section 4.1.2), step by step.
+
+    ``order``: the algorithm's shuffle, given as a permutation of the pair numbers of
+    P = {(i, j) | 0 <= i < j < g} in lexicographic order.  A is the g x g availability matrix
+    shared by all rotations (a pair is blocked once selected); A_rot is its copy for one
+    rotation, in which the rows and columns of both channels of a selected pair are blocked.
+    Returns (list of K lists of (i, j) in selection order).  Pure Python: small inputs only.
+    """
+    g = group
+    P = [(i, j) for i in range(g) for j in range(i + 1, g)]
+    P_shuffled = [P[int(k)] for k in order]
+    A = np.ones((g, g), dtype=np.uint8)
+    np.fill_diagonal(A, 0)
+    out = []
+    for _r in range(n_rotations):
+        A_rot = A.copy()
+        P_r = []
+        for (i, j) in P_shuffled:
+            if len(P_r) == pairs_per_rotation:
+                break
+            if A_rot[i, j] == 0:
+                continue
+            P_r.append((i, j))
+            A_rot[i, :] = 0; A_rot[:, i] = 0
+            A_rot[j, :] = 0; A_rot[:, j] = 0
+            A[i, j] = 0; A[j, i] = 0
+        out.append(P_r)
+    return out

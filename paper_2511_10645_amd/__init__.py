@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     paro_rotate_scale,
     paro_rotated_linear,
     paro_rotation_plan_build,
+    paro_select_pairs_host,
     paro_status_string,
     paro_tune_decode_waves,
     paro_validate_pairs_host,

@@ -55,6 +55,7 @@ def lib():
         L.paro_status_string.restype = ctypes.c_char_p
         L.paro_status_string.argtypes = [ctypes.c_int]
         L.paro_validate_pairs_host.argtypes = [vp, i32, i32, i32, i32]
+        L.paro_select_pairs_host.argtypes = [vp, i32, i32, i32, vp, vp]
         L.paro_rotation_plan_bytes.restype = sz
         L.paro_rotation_plan_bytes.argtypes = [rp]
         L.paro_rotation_plan_build.argtypes = [rp, vp, vp]
@@ -72,7 +73,7 @@ def lib():
         L.paro_w4_quantize.argtypes = [rp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.paro_tune_decode_waves.argtypes = [ctypes.c_int]
         L.paro_tune_decode_waves.restype = None
-        for name in ("paro_validate_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
+        for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize"):
             getattr(L, name).restype = ctypes.c_int
@@ -111,6 +112,17 @@ def paro_validate_pairs_host(pairs: np.ndarray, group: int = 128) -> int:
 
 def paro_tune_decode_waves(blocks: int) -> None:
     lib().paro_tune_decode_waves(int(blocks))
+
+
+def paro_select_pairs_host(order: np.ndarray, group: int, n_rotations: int, pairs_per_rotation: int):
+    """Algorithm A1 on a host permutation of the group's pairs; returns (pairs [K][N][2] int16, counts [K])."""
+    o = np.ascontiguousarray(order, dtype=np.int32)
+    assert o.shape == (group * (group - 1) // 2,)
+    pairs = np.empty((n_rotations, pairs_per_rotation, 2), dtype=np.int16)
+    counts = np.empty(n_rotations, dtype=np.int32)
+    _check(lib().paro_select_pairs_host(o.ctypes.data, group, n_rotations, pairs_per_rotation, pairs.ctypes.data,
+                                        counts.ctypes.data), "paro_select_pairs_host")
+    return pairs, counts
 
 
 class Rotation:

@@ -1,6 +1,8 @@
 // C ABI of libparo (include/paro.h): argument validation on the host, then dispatch to the
 // kernels.  No device memory is allocated or retained here.
 #include "paro_internal.h"
+#include <algorithm>
+#include <vector>
 
 using namespace paro;
 
@@ -131,6 +133,44 @@ paro_status paro_validate_pairs_host(const int16_t *pairs_host, int32_t n_groups
             used[i >> 3] |= (uint8_t)(1u << (i & 7));
             used[j >> 3] |= (uint8_t)(1u << (j & 7));
         }
+    }
+    return PARO_OK;
+}
+
+paro_status paro_select_pairs_host(const int32_t *order_host, int32_t group, int32_t n_rotations,
+                                   int32_t pairs_per_rotation, int16_t *pairs_out_host, int32_t *counts_out_host)
+{
+    if (!order_host || !pairs_out_host) return PARO_ERR_NULL;
+    if (group < 2 || group > 1024 || n_rotations < 0 || pairs_per_rotation < 0 || pairs_per_rotation > group / 2)
+        return PARO_ERR_SHAPE;
+    const int32_t n_pairs = group * (group - 1) / 2;
+    // pair number -> (i, j): row i of the upper triangle starts at i*g - i(i+1)/2
+    std::vector<int16_t> pi((size_t)n_pairs), pj((size_t)n_pairs);
+    for (int32_t i = 0, k = 0; i < group; ++i)
+        for (int32_t j = i + 1; j < group; ++j, ++k) { pi[(size_t)k] = (int16_t)i; pj[(size_t)k] = (int16_t)j; }
+    std::vector<uint8_t> seen((size_t)n_pairs, 0);
+    for (int32_t k = 0; k < n_pairs; ++k) {
+        const int32_t e = order_host[k];
+        if (e < 0 || e >= n_pairs || seen[(size_t)e]) return PARO_ERR_PAIRS;
+        seen[(size_t)e] = 1;
+    }
+    std::vector<uint8_t> taken((size_t)n_pairs, 0);      // pair used by an earlier rotation
+    std::vector<uint8_t> busy((size_t)group);            // channel used in the current rotation
+    for (int32_t r = 0; r < n_rotations; ++r) {
+        std::fill(busy.begin(), busy.end(), (uint8_t)0);
+        int16_t *out = pairs_out_host + (size_t)r * pairs_per_rotation * 2;
+        int32_t cnt = 0;
+        for (int32_t k = 0; k < n_pairs && cnt < pairs_per_rotation; ++k) {
+            const int32_t e = order_host[k];
+            const int i = pi[(size_t)e], j = pj[(size_t)e];
+            if (taken[(size_t)e] || busy[(size_t)i] || busy[(size_t)j]) continue;
+            out[2 * cnt] = (int16_t)i; out[2 * cnt + 1] = (int16_t)j;
+            ++cnt;
+            busy[(size_t)i] = busy[(size_t)j] = 1;
+            taken[(size_t)e] = 1;
+        }
+        if (counts_out_host) counts_out_host[r] = cnt;
+        for (int32_t k = cnt; k < pairs_per_rotation; ++k) { out[2 * k] = 0; out[2 * k + 1] = 0; }
     }
     return PARO_OK;
 }

@@ -216,3 +216,9 @@ def make_dense_weight(seed: int, c_out: int, c_in: int, sigma: float = 0.02, out
         idx = rs.choice(w.size, size=n_out, replace=False)
         w.reshape(-1)[idx] *= np.float32(outlier_mult)
     return w.astype(np.float16)
+
+
+def make_pair_order(seed: int, group: int = GROUP) -> np.ndarray:
+    """The shuffle that Algorithm A1 draws: a seeded permutation of the g(g-1)/2 pair numbers."""
+    rs = np.random.Generator(np.random.PCG64(seed))
+    return rs.permutation(group * (group - 1) // 2).astype(np.int32)
