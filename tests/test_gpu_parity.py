@@ -177,10 +177,14 @@ def _assert_linear(got16, y, allowed, note):
     dict(T=23, c_in=2048, c_out=16 * 21),
     dict(T=300, c_in=1024, c_out=16 * 21),      # MFMA GEMM path, ragged token and output tiles
     dict(T=257, c_in=512, c_out=16 * 33),
+    dict(T=17, c_in=1024, c_out=16 * 21),       # first token count on the GEMM path
+    dict(T=1, c_in=6144, c_out=16 * 37),        # 12 K-slices: the widest single-block reduction
+    dict(T=5, c_in=6656, c_out=16 * 11),        # 13 K-slices: spread over two blocks of 7 waves, partials exchanged
+    dict(T=16, c_in=5120, c_out=16 * 19),       # 10 K-slices, a full 16-token pass
 ])
 def test_bare_linear(P, packed, case):
     li = pin.make_custom(700 + case["T"], case["T"], case["c_in"], case["c_out"], n_outlier=3)
-    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] in (3, 300) else None
+    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] in (3, 5, 300) else None
     u = li.x.astype(np.float64)
     y, allowed = _linear_ref(li, u, bias)
     w = make_w(P, li, packed=packed, bias=bias)
@@ -197,6 +201,9 @@ def test_bare_linear(P, packed, case):
     dict(T=7, c_in=1024, c_out=16 * 13, plan=True, packed=True),
     dict(T=16, c_in=1536, c_out=256, plan=True, packed=True),
     dict(T=40, c_in=512, c_out=16 * 5, plan=True, packed=True),
+    dict(T=4, c_in=6656, c_out=16 * 11, plan=True, packed=True),     # fused, 13 K-slices exchanged
+    dict(T=5, c_in=6656, c_out=16 * 11, plan=True, packed=True),     # rotation pass + wide kernel over two blocks
+    dict(T=16, c_in=6144, c_out=16 * 37, plan=True, packed=True),
     dict(T=2, c_in=1024, c_out=64, plan=False, packed=True),
     dict(T=2, c_in=640, c_out=64, plan=True, packed=False),
     dict(T=3, c_in=512, c_out=64, plan=False, packed=False),
