@@ -27,7 +27,9 @@
 //
 // Blocks are numbered so that the 32 blocks resident on one XCD (block id mod 8) form an
 // 8 (token tiles) x 4 (output tiles) patch that walks K in step: they share activation and
-// weight panels through that XCD's L2.
+// weight panels through that XCD's L2.  With fewer than 8 token tiles the patch is narrower
+// in tokens and wider in outputs, so that no block id of a patch is left without work, and
+// with fewer than 256 tiles the patches shrink so that all 8 XCDs still get one.
 #include "paro_internal.h"
 #include <type_traits>
 
@@ -40,7 +42,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBN = 256, kBK = 64;
 constexpr int kLdsRow = kBK + 8;                    // halfs per padded LDS row
-constexpr int kPatchM = 8, kPatchN = 4;             // blocks of one XCD patch
+constexpr int kPatchBlocks = 32;                    // most blocks of one XCD patch (8 x 4 token x output tiles)
 
 constexpr uint32_t kOobG = 0x80000000u;
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc_g(const void *p, uint32_t bytes)
@@ -66,6 +68,7 @@ struct GemmArgs {
     const _Float16 *bias;
     int T, C, N, G, S;          // S = G / 4 K-slices of the scales/zeros tiling
     int m_tiles, n_tiles;
+    int patch_m, patch_n;       // token tiles x output tiles of the patch of blocks one XCD works on
 };
 
 // Staging work of one K-step, cut into items that are spread over the MFMA slots:
@@ -115,11 +118,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
     // ---- block -> (m tile, n tile), XCD-aware --------------------------------------------------
     const int bid = blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
-    const int patch = j / (kPatchM * kPatchN), q = j % (kPatchM * kPatchN);
-    const int m_patches = (a.m_tiles + kPatchM - 1) / kPatchM;
+    const int pb = a.patch_m * a.patch_n;
+    const int patch = j / pb, q = j % pb;
+    const int m_patches = (a.m_tiles + a.patch_m - 1) / a.patch_m;
     const int gp = patch * 8 + xcd;                        // global patch index
     const int pm = gp % m_patches, pn = gp / m_patches;
-    const int mt = pm * kPatchM + q % kPatchM, ntile = pn * kPatchN + q / kPatchM;
+    const int mt = pm * a.patch_m + q % a.patch_m, ntile = pn * a.patch_n + q / a.patch_m;
     if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
     const int m0 = mt * BM, n0 = ntile * kBN;
 
@@ -299,15 +303,35 @@ bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T)
            w.c_in % kBK == 0;
 }
 
+// Rough duration of the GEMM in microseconds, for the choice between it and repeated passes of the
+// streaming decode kernel at moderate token counts.  A block walks c_in / 64 K-steps; measured
+// per K-step and round of blocks: ~0.95 us with 128-token tiles, ~1.9 us with 256-token tiles.
+double gemm_estimate_us(const paro_w4_weight &w, int T)
+{
+    const long n_tiles = (w.c_out + kBN - 1) / kBN;
+    const long big_tiles = (long)((T + 255) / 256) * n_tiles;
+    const bool big = big_tiles >= 256;
+    const long blocks = big ? big_tiles : (long)((T + 127) / 128) * n_tiles;
+    const long rounds = (blocks + 255) / 256;
+    return (double)(w.c_in / kBK) * (double)rounds * (big ? 1.9 : 0.95);
+}
+
 template <int MI, int NI, int WM, int WN>
 static hipError_t launch_gemm_cfg(GemmArgs &a, hipStream_t s)
 {
     constexpr int BM = WM * MI * 32;
     a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = (a.N + kBN - 1) / kBN;
-    const int m_patches = (a.m_tiles + kPatchM - 1) / kPatchM, n_patches = (a.n_tiles + kPatchN - 1) / kPatchN;
+    // 32 blocks per patch when there is work for all 8 XCDs at that size; smaller patches
+    // otherwise, so that a small grid is still spread over every XCD's L2 and memory channels
+    int pb = kPatchBlocks;
+    while (pb > 1 && (long)a.m_tiles * a.n_tiles < 8L * pb) pb >>= 1;
+    a.patch_m = 1;
+    while (a.patch_m * 2 <= pb && a.patch_m * 2 <= 8 && a.patch_m * 2 <= a.m_tiles) a.patch_m <<= 1;
+    a.patch_n = pb / a.patch_m;
+    const int m_patches = (a.m_tiles + a.patch_m - 1) / a.patch_m, n_patches = (a.n_tiles + a.patch_n - 1) / a.patch_n;
     const int patches = m_patches * n_patches;
     const int rounds = (patches + 7) / 8;                 // patches per XCD
-    const int blocks = rounds * 8 * kPatchM * kPatchN;
+    const int blocks = rounds * 8 * pb;
     const size_t lds = (size_t)2 * (BM + kBN) * kLdsRow * sizeof(_Float16);
     static bool attr_set = false;
     if (!attr_set) {

@@ -13,7 +13,10 @@ void set_decode_target_waves(int blocks);
 namespace {
 
 constexpr int kFuseMaxTokens = 4;     // rotation runs inside the decode kernel up to this many tokens
-constexpr int kDecodeMaxTokens = 16;  // above this the MFMA GEMM takes over from the streaming decode kernel
+#ifndef PARO_DECODE_MAX_TOKENS
+#define PARO_DECODE_MAX_TOKENS 16
+#endif
+constexpr int kDecodeMaxTokens = PARO_DECODE_MAX_TOKENS;  // above this the MFMA GEMM takes over from the streaming decode kernel
 
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -86,7 +89,14 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
         if (!(w->qweight && w->scales && w->qzeros)) return PARO_ERR_UNSUPPORTED;
         return from_hip(launch_linear_generic(*w, X, ldx, Y, ldy, T, s));
     }
-    if (T > kDecodeMaxTokens && gemm_supported(*w, ldx, ldy, T)) return from_hip(launch_gemm(*w, X, ldx, Y, ldy, T, s));
+    if (T > kDecodeMaxTokens && gemm_supported(*w, ldx, ldy, T)) {
+        // Moderate token counts leave most of the chip idle in the GEMM (few token tiles), while the
+        // streaming kernel re-reads the weights once per 16 tokens at HBM speed: take the cheaper.
+        // Measured per 16-token pass: ~5 us plus the tile bytes at ~6 TB/s.
+        const double passes = (double)((T + kDecodeMaxTokens - 1) / kDecodeMaxTokens);
+        const double stream_us = passes * (5.0 + (double)packed_tiles_bytes(w->c_in, w->c_out) / 6.0e6);
+        if (T >= 512 || gemm_estimate_us(*w, T) <= stream_us) return from_hip(launch_gemm(*w, X, ldx, Y, ldy, T, s));
+    }
     for (int t0 = 0; t0 < T; t0 += 16) {
         int tc = T - t0 < 16 ? T - t0 : 16;
         hipError_t e = launch_decode_wide(*w, X + (size_t)t0 * ldx, ldx, Y + (size_t)t0 * ldy, ldy, tc, ws, s);

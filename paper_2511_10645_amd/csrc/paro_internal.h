@@ -114,6 +114,7 @@ hipError_t launch_quantize(const paro_rotation *rot, const paro_half_t *W, int64
 
 // Prefill-side linear (MFMA GEMM on the repacked weight), any T.
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T);
+double gemm_estimate_us(const paro_w4_weight &w, int T);
 hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                        int T, hipStream_t s);
 

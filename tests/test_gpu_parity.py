@@ -177,7 +177,7 @@ def _assert_linear(got16, y, allowed, note):
     dict(T=23, c_in=2048, c_out=16 * 21),
     dict(T=300, c_in=1024, c_out=16 * 21),      # MFMA GEMM path, ragged token and output tiles
     dict(T=257, c_in=512, c_out=16 * 33),
-    dict(T=17, c_in=1024, c_out=16 * 21),       # first token count on the GEMM path
+    dict(T=17, c_in=1024, c_out=16 * 21),       # two passes of the streaming kernel (16 + 1 tokens)
     dict(T=1, c_in=6144, c_out=16 * 37),        # 12 K-slices: the widest single-block reduction
     dict(T=5, c_in=6656, c_out=16 * 11),        # 13 K-slices: spread over two blocks of 7 waves, partials exchanged
     dict(T=16, c_in=5120, c_out=16 * 19),       # 10 K-slices, a full 16-token pass
