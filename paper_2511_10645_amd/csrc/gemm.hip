@@ -67,7 +67,8 @@ struct GemmArgs {
     _Float16 *Y; int64_t ldy;
     const _Float16 *bias;
     int T, C, N, G, S;          // S = G / 4 K-slices of the scales/zeros tiling
-    int m_tiles, n_tiles;
+    int m_tiles, n_tiles;       // tiles of this launch
+    int n_tile0;                // first 256-output tile of this launch
     int patch_m, patch_n;       // token tiles x output tiles of the patch of blocks one XCD works on
 };
 
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
     const int pm = gp % m_patches, pn = gp / m_patches;
     const int mt = pm * a.patch_m + q % a.patch_m, ntile = pn * a.patch_n + q / a.patch_m;
     if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
-    const int m0 = mt * BM, n0 = ntile * kBN;
+    const int m0 = mt * BM, n0 = (a.n_tile0 + ntile) * kBN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -316,11 +317,12 @@ double gemm_estimate_us(const paro_w4_weight &w, int T)
     return (double)(w.c_in / kBK) * (double)rounds * (big ? 1.9 : 0.95);
 }
 
+// output tiles [n_tile0, n_tile0 + n_count) x all token tiles
 template <int MI, int NI, int WM, int WN>
-static hipError_t launch_gemm_cfg(GemmArgs &a, hipStream_t s)
+static hipError_t launch_gemm_cfg(GemmArgs &a, int n_tile0, int n_count, hipStream_t s)
 {
     constexpr int BM = WM * MI * 32;
-    a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = (a.N + kBN - 1) / kBN;
+    a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = n_count; a.n_tile0 = n_tile0;
     // 32 blocks per patch when there is work for all 8 XCDs at that size; smaller patches
     // otherwise, so that a small grid is still spread over every XCD's L2 and memory channels
     int pb = kPatchBlocks;
@@ -355,17 +357,32 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
-    // 256-token tiles unless they leave compute units idle: fewer than one full wave of blocks
-    const long big_tiles = (long)((T + 255) / 256) * ((w.c_out + kBN - 1) / kBN);
-    bool big = big_tiles >= 256;
-#ifdef PARO_GEMM_FORCE_BIG
-    big = PARO_GEMM_FORCE_BIG;
-#endif
+    // 256-token tiles unless they leave compute units idle.  Fewer than one full round of 256
+    // blocks: 128-token tiles throughout.  Otherwise, when the last round would be at most half
+    // full, that remainder (a range of output tiles) is launched separately with 128-token tiles:
+    // e.g. 896 tiles = 3 rounds of 256-token tiles + one round of 256 half-size tiles instead of 4.
+    const int n_all = (w.c_out + kBN - 1) / kBN, m_big = (T + 255) / 256;
+    const long big_tiles = (long)m_big * n_all;
 #ifdef PARO_GEMM_4WAVES
-    return big ? launch_gemm_cfg<4, 4, 2, 2>(a, s) : launch_gemm_cfg<2, 4, 2, 2>(a, s);
+    auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 4, 2, 2>(a, n0, n, s); };
+    auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 4, 2, 2>(a, n0, n, s); };
 #else
-    return big ? launch_gemm_cfg<4, 2, 2, 4>(a, s) : launch_gemm_cfg<2, 2, 2, 4>(a, s);
+    auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 2, 2, 4>(a, n0, n, s); };
+    auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 2, 2, 4>(a, n0, n, s); };
 #endif
+    if (big_tiles < 256) return small(0, n_all);
+    const long full = big_tiles / 256, rem = big_tiles - full * 256;
+#ifndef PARO_GEMM_NO_TAIL_SPLIT
+    if (rem > 0 && rem <= 128) {
+        const int n_main = (int)(full * 256 / m_big);
+        if (n_main > 0 && n_main < n_all) {
+            hipError_t e = big(0, n_main);
+            if (e != hipSuccess) return e;
+            return small(n_main, n_all - n_main);
+        }
+    }
+#endif
+    return big(0, n_all);
 }
 
 }  // namespace paro
