@@ -70,6 +70,8 @@ struct GemmArgs {
     int m_tiles, n_tiles;       // tiles of this launch
     int n_tile0;                // first 256-output tile of this launch
     int patch_m, patch_n;       // token tiles x output tiles of the patch of blocks one XCD works on
+    uint32_t m_lo, m_hi, k_lo, k_hi;   // 0x000F000F, 0x00F000F0, 0x64006400, 0x54005400: passed as arguments and
+                                       // moved to VGPRs so that (u & mask) | magic becomes one v_and_or_b32
 };
 
 // Staging work of one K-step, cut into items that are spread over the MFMA slots:
@@ -183,11 +185,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
         s2[p] = g_as_h2((uint32_t)bsc[p] * 0x00010001u);
     };
     // half h of word w4 of load p -> 4 fp16 weights; the second half stores the word's 8 weights
+    auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
+    const uint32_t c_mlo = to_vgpr(a.m_lo), c_mhi = to_vgpr(a.m_hi), c_klo = to_vgpr(a.k_lo), c_khi = to_vgpr(a.k_hi);
     uint32_t dq_keep[2];
     auto deq_half = [&](_Float16 *Bn, int p, int w4, int h) {
         const uint32_t u = bw[p][w4] >> (8 * h);
-        const uint32_t o0 = g_as_u32((g_as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo[p]) * s2[p]);
-        const uint32_t o1 = g_as_u32((g_as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi[p]) * s2[p]);
+        const uint32_t o0 = g_as_u32((g_as_h2((u & c_mlo) | c_klo) + nlo[p]) * s2[p]);
+        const uint32_t o1 = g_as_u32((g_as_h2((u & c_mhi) | c_khi) + nhi[p]) * s2[p]);
         if (h == 0) { dq_keep[0] = o0; dq_keep[1] = o1; }
         else {
             const u32x4 o = {dq_keep[0], dq_keep[1], o0, o1};
@@ -357,6 +361,7 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
+    a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
     // 256-token tiles unless they leave compute units idle.  Fewer than one full round of 256
     // blocks: 128-token tiles throughout.  Otherwise, when the last round would be at most half
     // full, that remainder (a range of output tiles) is launched separately with 128-token tiles:
