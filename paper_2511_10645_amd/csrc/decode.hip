@@ -149,8 +149,11 @@ __device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGrou
 // the range are cut into `parts` contiguous shares; block `part` sums the partials of its share
 // in a fixed order (deterministic), adds the bias and stores fp16.  No fences and no counters:
 // every partial word is its own full/empty flag (0 = empty; a value is never stored as +0),
-// written and read with agent-scope accesses and reset to empty by its reader.  A reader polls
-// a word until it fills; the writers are the blocks dispatched next to it, which never wait on
+// written with agent-scope stores and taken by its reader with an agent-scope atomic exchange
+// against 0, which reads the word and leaves it empty in one operation (an exchange that finds
+// 0 changes nothing and is repeated).  Measured: the returning atomic comes back faster than an
+// agent-scope load (the fused launches lose 0.3-0.7 us), while atomics on the writer side would
+// serialise.  The writers are the blocks dispatched next to the reader, which never wait on
 // anything before writing.  The poll is bounded; a word that never fills is reported as NaN.
 __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, int tile_lo, int tile_hi, float *s_red)
 {
@@ -176,15 +179,14 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
             const int o = base + (on ? j % n_out : 0), k2 = on ? j / n_out : 0;
             const int t = o / width, n = n_lo + o % width;
             ptr[u] = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
-            bits[u] = on ? __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
+            bits[u] = on ? __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
         }
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int j = threadIdx.x + u * THREADS;
             if (j < n_out * parts) {
                 for (int spin = 0; bits[u] == 0u && spin < kSpinLimit; ++spin)
-                    bits[u] = __hip_atomic_load(ptr[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    bits[u] = __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
             }
         }
@@ -321,9 +323,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
     const __amdgpu_buffer_rsrc_t pr = make_rsrc(a.partial, SPLIT ? (uint32_t)((size_t)a.KS * a.T * a.N * 4) : 0u);
     const __amdgpu_buffer_rsrc_t br = make_rsrc(a.bias, a.bias ? (uint32_t)a.N * 2u : 0u);      // no bias: reads 0
     auto emit = [&](const Stage &stg, int tile) {
-#ifdef PARO_EXP_WAIT0
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
         float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
         const uint32_t n = (uint32_t)tile * kTileN + n_in_tile;
         if constexpr (!SPLIT) {
