@@ -2,24 +2,29 @@
 // fused in front (Eq. 2 with T of Eq. 8).  HBM-bound: the packed INT4 weights are streamed
 // exactly once, as 1 KB tiles, and everything else is arranged around that stream.
 //
-// Work split.  The input channels are cut into K-slices of 4 groups (512 channels).  A block
-// owns ONE K-slice and a range of 16-row output tiles; its waves share the slice and take
-// different tiles.  A wave therefore needs the activations of 512 channels only, and keeps
-// them as MFMA A-fragments in registers for the whole stream (tokens padded to 16).  With the
-// rotation fused, each of the block's 4 waves rotates one of the slice's 4 groups (one
-// wavefront per (token, group), see rotate.hip) - the prologue costs one group-rotation per
-// wave however wide the layer is, and runs while the first weight tiles are in flight.
+// The input channels are cut into K-slices of 4 groups (512 channels).  A wave needs the
+// activations of one slice only and keeps them as MFMA A-fragments in registers for its whole
+// stream (tokens padded to 16).  Two kernels share the stream code:
+//
+//  - decode_kernel (rotation fused, up to 4 tokens): a block owns ONE K-slice and a range of
+//    16-row output tiles; its 4 waves share the slice and take different tiles.  Each wave
+//    rotates one of the slice's 4 groups (one wavefront per (token, group), see rotate.hip) -
+//    the prologue costs one group-rotation per wave however wide the layer is, and runs while
+//    the first weight tiles are in flight.  The K-slices' partial sums are exchanged between
+//    blocks at the end.
+//  - decode_wide_kernel (bare, up to 16 tokens): a block takes ALL K-slices of its tile range,
+//    one per wave, and sums them through LDS; no exchange between blocks up to 6144 channels.
 //
 // Inner loop per 16x128 tile and lane: one 16-byte load (32 codes), v_and_or_b32 with the fp16
 // magic numbers 1024 / 64 (the code lands in the mantissa: 5 VALU ops per 8 weights), four
 // v_mfma_f32_16x16x32_f16 whose accumulator starts at the bias / zero-point correction (see
 // tile_dot), then the group's scale is applied once to the fp32 sum:  y += s * sum_k (q - z) x'.
 //
-// Split-K reduction: each block stores fp32 partial tiles to the workspace, then sums its
-// share of the output range over the KS partials in a fixed order (deterministic), adds the
-// bias and rounds to fp16.  Agent-scope release/acquire fences would cost an L2 write-back and
+// Split-K exchange: blocks store fp32 partial tiles to the workspace, then each sums its share
+// of the output range over the partials in a fixed order (deterministic), adds the bias and
+// rounds to fp16.  Agent-scope release/acquire fences would cost an L2 write-back and
 // invalidate per wave on this multi-XCD part (measured: +40..85 us per launch), so none are
-// used: each partial word is its own full/empty flag.
+// used: each partial word is its own full/empty flag (see splitk_reduce).
 #include "paro_internal.h"
 
 namespace paro {
@@ -203,8 +208,7 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
 #endif
 }
 
-// K >= 0: rotation with K layers fused; K < 0: bare linear on X.  SPLIT: more than one K-slice.
-// T1: exactly one token.
+// K: rotation layers fused in front.  SPLIT: more than one K-slice.  T1: exactly one token.
 template <int K, bool SPLIT, bool T1>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
 {
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
     half8 xf[kSliceGroups][4];
     const int ft = lane & 15, fkb = lane >> 4;
     const size_t c0 = (size_t)ks * kSliceCh;
-    if constexpr (K >= 0) {
+    {
         // wave w rotates group w of the slice for all T tokens
         const int gi = wave;
         const uint32_t *gplan = a.plan + ((size_t)ks * kSliceGroups + gi) * plan_group_dwords(K);
@@ -279,20 +283,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
                 if (ft < a.T) v = *(const half8 *)&s_x[ft][g2 * kGroup + fkb * 32 + j * 8];
                 xf[g2][j] = v;
             }
-    } else {
-        // rows >= T lie beyond the resource: they read as zero
-        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
-        const uint32_t xoff = ft < a.T ? (uint32_t)(((size_t)ft * a.ldx + c0 + fkb * 32) * 2) : kOob;
-#pragma unroll
-        for (int g2 = 0; g2 < kSliceGroups; ++g2)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                union { u32x4 u; half8 h; } v;
-                v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
-                xf[g2][j] = v.h;
-            }
-        load_stage(blob, a, tile_of(0), ks, lane, st0);
-        load_stage(blob, a, tile_of(1), ks, lane, st1);
     }
 
     // per token and group: nb1 = -sum_k b_k x'_k, nb2 = -sum_k x'_k, as MFMAs against constant
@@ -407,6 +397,7 @@ static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, 
 hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                          paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s)
 {
+    if (!rot || !rot->plan) return hipErrorInvalidValue;
     DecodeGeometry d = decode_geometry(w.c_in, w.c_out, T);
     if (d.ks > kReduceWords) return hipErrorInvalidValue;
     if (packed_tiles_bytes(w.c_in, w.c_out) + packed_scales_bytes(w.c_in, w.c_out) + packed_zeros_bytes(w.c_in, w.c_out) >= (1ull << 31))
@@ -418,12 +409,11 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
     a.blob_bytes = a.zeros_off + (uint32_t)packed_zeros_bytes(w.c_in, w.c_out);
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
-    a.plan = rot ? (const uint32_t *)rot->plan : nullptr;
+    a.plan = (const uint32_t *)rot->plan;
     a.partial = (float *)ws;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN; a.KS = d.ks;
     a.tiles_per_block = d.tiles_per_block;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
-    if (!rot) return launch_decode_k<-1>(a, d, s);
     switch (rot->n_layers) {
     case 0: return launch_decode_k<0>(a, d, s);
     case 1: return launch_decode_k<1>(a, d, s);
