@@ -321,3 +321,31 @@ def test_config0_tiny_full(P):
     ws = P.Workspace(P.paro_workspace_bytes(rot, w, 1))
     got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
     _assert_linear(got, y, allowed, "config0 fused")
+
+
+def test_one_workspace_shared_by_many_calls(P):
+    """A model allocates one workspace and runs every linear through it.  The split-K exchange
+    leaves it clean after each call, whatever shape, token count or path came before."""
+    import torch
+    say("shared workspace sequence")
+    cases = []
+    for seed, (T, c_in, c_out) in enumerate([(1, 2048, 16 * 50), (4, 1024, 16 * 13), (1, 6656, 16 * 11), (16, 1536, 256),
+                                             (2, 512, 512), (7, 6656, 16 * 11), (1, 1024, 64), (40, 512, 16 * 5)]):
+        li = pin.make_custom(1200 + seed, T, c_in, c_out, n_outlier=2)
+        u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+        y_rot, allowed_rot = _linear_ref(li, u)
+        y_bare, allowed_bare = _linear_ref(li, li.x.astype(np.float64))
+        cases.append(dict(T=T, li=li, rot=make_rot(P, li), w=make_w(P, li), x=dev(li.x),
+                          y_rot=y_rot, a_rot=allowed_rot, y_bare=y_bare, a_bare=allowed_bare))
+    need = max(P.paro_workspace_bytes(c["rot"], c["w"], c["T"]) for c in cases)
+    ws = P.Workspace(need)
+    rs = np.random.default_rng(77)
+    for it in range(60):
+        c = cases[int(rs.integers(len(cases)))]
+        if rs.integers(2):
+            got = P.paro_rotated_linear(c["rot"], c["w"], c["x"], ws).cpu().numpy()
+            _assert_linear(got, c["y_rot"], c["a_rot"], f"seq {it} rotated T={c['T']} C={c['li'].c_in}")
+        else:
+            got = P.paro_w4a16_linear(c["w"], c["x"], ws).cpu().numpy()
+            _assert_linear(got, c["y_bare"], c["a_bare"], f"seq {it} bare T={c['T']} C={c['li'].c_in}")
+    torch.cuda.synchronize()
