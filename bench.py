@@ -226,6 +226,68 @@ def main() -> int:
         prefill["overhead_pct_vs_bare_w4a16"] = round(100.0 * (tot_us - tot_us_bare) / tot_us_bare, 2)
         prefill["tokens_per_s_layer"] = round(Tp / (tot_us * 1e-6), 1)
 
+    # ---- per-linear transforms (the method gives q / k / v and gate / up their own): one launch --------
+    multi = None
+    if not args.no_prefill and args.config == 1:
+        multi = {}
+        xm = lin[0]["x"]
+        for name, outs in (("qkv", (4096, 1024, 1024)), ("gate_up", (14336, 14336))):
+            rots_m, pools = [], []
+            n_cp = max(2, -(-args.pool_mb * (1 << 20) // (sum(outs) * 4096 // 2)))
+            for k, n_out in enumerate(outs):
+                pairs, theta, chs = pin.make_rotation(1, k, 4096)
+                r = paro.Rotation(pairs, theta, chs)
+                paro.paro_rotation_plan_build(r)
+                rots_m.append(r)
+                w0 = paro.W4Weight(pin.pack_nibbles_u32(np.random.default_rng(k).integers(0, 16, (n_out, 4096), dtype=np.uint8)),
+                                   np.full((32, n_out), 0.01, dtype=np.float16),
+                                   np.zeros((32, n_out // 8), dtype=np.uint32))
+                paro.paro_w4_repack(w0)
+                w0.drop_interchange()
+                cps = [w0]
+                for _ in range(n_cp - 1):
+                    c = paro.W4Weight.__new__(paro.W4Weight)
+                    c.c_in, c.c_out = w0.c_in, w0.c_out
+                    c.qweight = c.scales = c.qzeros = c.bias = None
+                    c.packed = w0.packed.clone()
+                    c.c = type(w0.c)(c.c_in, c.c_out, 128, None, None, None, None, c.packed.data_ptr())
+                    cps.append(c)
+                pools.append(cps)
+            ys_m = [torch.empty((T, n_out), dtype=torch.float16, device=dev) for n_out in outs]
+            ws_s = paro.Workspace(max(paro.paro_workspace_bytes(r, p[0], T) for r, p in zip(rots_m, pools)))
+            ws_m = paro.Workspace(paro.paro_workspace_bytes_multi(rots_m, [p[0] for p in pools], T))
+
+            def run_sep(i):
+                for k in range(len(outs)):
+                    paro.paro_rotated_linear(rots_m[k], pools[k][i % n_cp], xm, ws_s, ys_m[k])
+
+            def run_one(i):
+                paro.paro_rotated_linear_multi(rots_m, [p[i % n_cp] for p in pools], xm, ws_m, ys_m)
+
+            res = {}
+            for label, fn in (("us_separate_launches", run_sep), ("us_one_launch", run_one)):
+                g = torch.cuda.CUDAGraph()
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    fn(0)
+                    torch.cuda.synchronize()
+                    with torch.cuda.graph(g, stream=side):
+                        for i in range(args.steps):
+                            fn(i)
+                torch.cuda.current_stream().wait_stream(side)
+                g.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                res[label] = round(e0.elapsed_time(e1) / args.steps * 1e3, 3)
+            res["parts"] = [f"4096->{n}" for n in outs]
+            multi[name] = res
+            del pools, rots_m, ys_m
+
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -262,7 +324,7 @@ def main() -> int:
         "overhead_pct_vs_bare_w4a16": round(overhead_pct, 2),
         "ms_per_step_bare": round(ms_bare_step, 6),
         "per_linear": per,
-        "prefill": prefill,
+        "prefill": prefill, "own_transform_per_projection": multi,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

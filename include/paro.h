@@ -149,6 +149,22 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
                                 const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                                 int32_t T, void *ws, size_t ws_bytes, void *stream);
 
+/* Several linears that read the SAME activations, each with its own transform: in the method every
+ * linear owns its pairs, angles and scales (Section 4.1, App. A.4), so the q / k / v projections
+ * (or gate / up) of a decoder layer need three (two) transforms of one X.  Part p computes
+ * Y[p] = W^_p . (R_p . S_p . x) (+ b_p) exactly as paro_rotated_linear(rots[p], weights[p], X, Y[p]).
+ * n_parts in 1..4; all parts share c_in.  With T <= 4, every rotation planned, every weight
+ * repacked and equal layer counts the parts run as ONE launch (results are bit-identical to the
+ * separate calls); otherwise the call is the sequence of separate calls.  rots, weights, Y and
+ * ldy are HOST arrays of n_parts entries (device pointers inside, as in the single call).
+ * ws: device, zero-filled once, >= paro_workspace_bytes_multi(...) bytes, 256-byte aligned. */
+size_t paro_workspace_bytes_multi(int32_t n_parts, const paro_rotation *const *rots,
+                                  const paro_w4_weight *const *weights, int32_t T);
+paro_status paro_rotated_linear_multi(int32_t n_parts, const paro_rotation *const *rots,
+                                      const paro_w4_weight *const *weights, const paro_half_t *X, int64_t ldx,
+                                      paro_half_t *const *Y, const int64_t *ldy, int32_t T, void *ws,
+                                      size_t ws_bytes, void *stream);
+
 /* Offline, weight side (Eq. 8 then Eq. 1; Section 2.1 group rule) ----------------------------
  * Quantise a dense fp16 weight W[c_out][c_in] (row n = output channel n at W + n*ldw, device)
  * into the interchange layout of paro_w4_weight:

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     lib_path,
     paro_rotate_scale,
     paro_rotated_linear,
+    paro_rotated_linear_multi,
     paro_rotation_plan_build,
     paro_select_pairs_host,
     paro_status_string,
@@ -25,5 +26,6 @@ from .binding import (  # noqa: F401
     paro_w4_unpack_zeros,
     paro_w4a16_linear,
     paro_workspace_bytes,
+    paro_workspace_bytes_multi,
     Workspace,
 )

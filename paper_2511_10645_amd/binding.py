@@ -71,11 +71,14 @@ def lib():
         L.paro_w4_unpack_zeros.argtypes = [wp, vp, vp]
         L.paro_w4_dequant.argtypes = [wp, vp, vp]
         L.paro_w4_quantize.argtypes = [rp, vp, i64, i32, i32, vp, vp, vp, vp]
+        L.paro_workspace_bytes_multi.restype = sz
+        L.paro_workspace_bytes_multi.argtypes = [i32, vp, vp, i32]
+        L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
         L.paro_tune_decode_waves.argtypes = [ctypes.c_int]
         L.paro_tune_decode_waves.restype = None
         for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
-                     "paro_w4_dequant", "paro_w4_quantize"):
+                     "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -282,3 +285,27 @@ def paro_w4_dequant(w: W4Weight) -> torch.Tensor:
     out = torch.empty((w.c_out, w.c_in), dtype=torch.float16, device=(w.packed if w.qweight is None else w.qweight).device)
     _check(lib().paro_w4_dequant(w.ref(), out.data_ptr(), _stream()), "paro_w4_dequant")
     return out
+
+
+def _ptr_array(objs):
+    arr = (ctypes.c_void_p * len(objs))(*[ctypes.addressof(o.c) for o in objs])
+    return arr
+
+
+def paro_workspace_bytes_multi(rots, weights, T: int) -> int:
+    assert len(rots) == len(weights)
+    return lib().paro_workspace_bytes_multi(len(rots), _ptr_array(rots), _ptr_array(weights), T)
+
+
+def paro_rotated_linear_multi(rots, weights, x: torch.Tensor, ws: Workspace, ys=None):
+    """Several linears on the same x, each with its own transform (q / k / v, gate / up); returns the list of outputs."""
+    T, ldx = _rows(x)
+    n = len(rots)
+    assert n == len(weights)
+    if ys is None:
+        ys = [torch.empty((T, w.c_out), dtype=torch.float16, device=x.device) for w in weights]
+    y_ptrs = (ctypes.c_void_p * n)(*[y.data_ptr() for y in ys])
+    ldys = (ctypes.c_int64 * n)(*[_rows(y)[1] for y in ys])
+    _check(lib().paro_rotated_linear_multi(n, _ptr_array(rots), _ptr_array(weights), x.data_ptr(), ldx, y_ptrs, ldys, T,
+                                           ws.buf.data_ptr(), ws.nbytes, _stream()), "paro_rotated_linear_multi")
+    return ys

@@ -210,11 +210,9 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
 
 // K: rotation layers fused in front.  SPLIT: more than one K-slice.  T1: exactly one token.
 template <int K, bool SPLIT, bool T1>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
+__device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, const int nb,
+                                            _Float16 (*s_x)[kSliceCh + kXPad], float *s_red)
 {
-    __shared__ _Float16 s_x[16][kSliceCh + kXPad];
-    __shared__ float s_red[kReduceWords];
-    const int ks = blockIdx.x, nb = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tile_lo = nb * a.tiles_per_block;
     const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
@@ -357,7 +355,40 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
     if constexpr (SPLIT) splitk_reduce(a, a.KS, ks, tile_lo, tile_hi, s_red);
 }
 
-DecodeGeometry decode_geometry(int c_in, int c_out, int T)
+template <int K, bool SPLIT, bool T1>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
+{
+    __shared__ _Float16 s_x[16][kSliceCh + kXPad];
+    __shared__ float s_red[kReduceWords];
+    decode_body<K, SPLIT, T1>(a, blockIdx.x, blockIdx.y, s_x, s_red);
+}
+
+// Several linears that read the same activations, each with its own transform (every linear of
+// the method has its own pairs, angles and scales - q / k / v or gate / up of a decoder layer),
+// in one launch: the block rows (blockIdx.y) are divided among the parts, and a block runs the
+// single-linear body on its part's arguments.
+constexpr int kMaxParts = 4;
+struct MultiArgs {
+    DecodeArgs part[kMaxParts];
+    int nb_end[kMaxParts];      // block rows [nb_end[p-1], nb_end[p]) belong to part p
+    int n_parts;
+};
+
+template <int K, bool SPLIT, bool T1>
+__global__ __launch_bounds__(kDecThreads) void decode_multi_kernel(MultiArgs m)
+{
+    __shared__ _Float16 s_x[16][kSliceCh + kXPad];
+    __shared__ float s_red[kReduceWords];
+    const int by = blockIdx.y;
+    int p = 0, lo = 0;
+#pragma unroll
+    for (int q = 0; q + 1 < kMaxParts; ++q)
+        if (q + 1 < m.n_parts && by >= m.nb_end[q]) { p = q + 1; lo = m.nb_end[q]; }
+    decode_body<K, SPLIT, T1>(m.part[p], blockIdx.x, by - lo, s_x, s_red);
+}
+
+// target_blocks > 0: block budget given by the caller (one part of a multi-linear launch)
+DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
 {
     DecodeGeometry d;
     int G = c_in / kGroup, NT = c_out / kTileN;
@@ -365,7 +396,7 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T)
     d.waves = kDecWaves;
     // measured on MI355X: one 4-wave block per CU for the small linears (the prologue is repeated
     // less often), two per CU once the weight stream exceeds ~24 MB
-    int target = g_decode_target_blocks;
+    int target = target_blocks > 0 ? target_blocks : g_decode_target_blocks;
     if (target <= 0) target = packed_tiles_bytes(c_in, c_out) >= (24u << 20) ? 512 : 256;
     int nb = target / d.ks;
     if (nb < 1) nb = 1;
@@ -394,15 +425,15 @@ static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, 
     return hipGetLastError();
 }
 
-hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
-                         paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s)
+static hipError_t fill_decode_args(DecodeArgs &a, DecodeGeometry &d, const paro_rotation *rot, const paro_w4_weight &w,
+                                   const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T, void *partial,
+                                   int target_blocks = 0)
 {
     if (!rot || !rot->plan) return hipErrorInvalidValue;
-    DecodeGeometry d = decode_geometry(w.c_in, w.c_out, T);
+    d = decode_geometry(w.c_in, w.c_out, T, target_blocks);
     if (d.ks > kReduceWords) return hipErrorInvalidValue;
     if (packed_tiles_bytes(w.c_in, w.c_out) + packed_scales_bytes(w.c_in, w.c_out) + packed_zeros_bytes(w.c_in, w.c_out) >= (1ull << 31))
         return hipErrorInvalidValue;   // 32-bit buffer offsets
-    DecodeArgs a;
     a.blob = w.packed;
     a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);
     a.zeros_off = a.scales_off + (uint32_t)packed_scales_bytes(w.c_in, w.c_out);
@@ -410,10 +441,20 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
     a.plan = (const uint32_t *)rot->plan;
-    a.partial = (float *)ws;
+    a.partial = (float *)partial;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN; a.KS = d.ks;
     a.tiles_per_block = d.tiles_per_block;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
+    return hipSuccess;
+}
+
+hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
+                         paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s)
+{
+    DecodeArgs a;
+    DecodeGeometry d;
+    hipError_t e = fill_decode_args(a, d, rot, w, X, ldx, Y, ldy, T, ws);
+    if (e != hipSuccess) return e;
     switch (rot->n_layers) {
     case 0: return launch_decode_k<0>(a, d, s);
     case 1: return launch_decode_k<1>(a, d, s);
@@ -424,6 +465,77 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
     case 6: return launch_decode_k<6>(a, d, s);
     case 7: return launch_decode_k<7>(a, d, s);
     default: return launch_decode_k<8>(a, d, s);
+    }
+}
+
+template <int K>
+static hipError_t launch_multi_k(const MultiArgs &m, int ks, int nb_total, int T, hipStream_t s)
+{
+    const dim3 grid(ks, nb_total), block(kDecThreads);
+    if (T == 1) {
+        if (ks > 1) hipLaunchKernelGGL((decode_multi_kernel<K, true, true>), grid, block, 0, s, m);
+        else        hipLaunchKernelGGL((decode_multi_kernel<K, false, true>), grid, block, 0, s, m);
+    } else {
+        if (ks > 1) hipLaunchKernelGGL((decode_multi_kernel<K, true, false>), grid, block, 0, s, m);
+        else        hipLaunchKernelGGL((decode_multi_kernel<K, false, false>), grid, block, 0, s, m);
+    }
+    return hipGetLastError();
+}
+
+// The parts of one launch share the block budget of a single linear of their combined size, in
+// proportion to their outputs.
+static int multi_part_target(int n_parts, const paro_w4_weight *const *w, int p)
+{
+    size_t n_all = 0;
+    for (int q = 0; q < n_parts; ++q) n_all += (size_t)w[q]->c_out;
+    int target = g_decode_target_blocks;
+    if (target <= 0) target = packed_tiles_bytes(w[0]->c_in, (int)n_all) >= (24u << 20) ? 512 : 256;
+    const int ks = w[p]->c_in / kGroup / kSliceGroups;
+    int mine = (int)(((size_t)target * w[p]->c_out + n_all / 2) / n_all);
+    return mine < ks ? ks : mine;
+}
+
+// workspace of the one-launch path: the parts' split-K partials one after the other
+size_t decode_multi_bytes(int n_parts, const paro_w4_weight *const *w, int T)
+{
+    size_t total = 0;
+    for (int p = 0; p < n_parts; ++p)
+        total += (decode_geometry(w[p]->c_in, w[p]->c_out, T, multi_part_target(n_parts, w, p)).partial_bytes + 255) / 256 * 256;
+    return total;
+}
+
+// All parts: same c_in and layer count, plan and repacked weight present, T <= 4.
+hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, const paro_w4_weight *const *w,
+                               const paro_half_t *X, int64_t ldx, paro_half_t *const *Y, const int64_t *ldy, int T,
+                               void *ws, hipStream_t s)
+{
+    if (n_parts < 1 || n_parts > kMaxParts) return hipErrorInvalidValue;
+    MultiArgs m;
+    m.n_parts = n_parts;
+    int nb_total = 0, ks = 0;
+    size_t off = 0;
+    for (int p = 0; p < n_parts; ++p) {
+        DecodeGeometry d;
+        hipError_t e = fill_decode_args(m.part[p], d, rot[p], *w[p], X, ldx, Y[p], ldy[p], T, (char *)ws + off,
+                                        multi_part_target(n_parts, w, p));
+        if (e != hipSuccess) return e;
+        if (p && (d.ks != ks || rot[p]->n_layers != rot[0]->n_layers)) return hipErrorInvalidValue;
+        ks = d.ks;
+        nb_total += d.nb;
+        m.nb_end[p] = nb_total;
+        off += (d.partial_bytes + 255) / 256 * 256;
+    }
+    for (int p = n_parts; p < kMaxParts; ++p) { m.part[p] = m.part[0]; m.nb_end[p] = nb_total; }
+    switch (rot[0]->n_layers) {
+    case 0: return launch_multi_k<0>(m, ks, nb_total, T, s);
+    case 1: return launch_multi_k<1>(m, ks, nb_total, T, s);
+    case 2: return launch_multi_k<2>(m, ks, nb_total, T, s);
+    case 3: return launch_multi_k<3>(m, ks, nb_total, T, s);
+    case 4: return launch_multi_k<4>(m, ks, nb_total, T, s);
+    case 5: return launch_multi_k<5>(m, ks, nb_total, T, s);
+    case 6: return launch_multi_k<6>(m, ks, nb_total, T, s);
+    case 7: return launch_multi_k<7>(m, ks, nb_total, T, s);
+    default: return launch_multi_k<8>(m, ks, nb_total, T, s);
     }
 }
 

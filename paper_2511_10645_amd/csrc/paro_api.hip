@@ -307,6 +307,68 @@ paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *strea
     return from_hip(launch_dequant(*w, W, (hipStream_t)stream));
 }
 
+static bool multi_one_launch(int32_t n, const paro_rotation *const *rots, const paro_w4_weight *const *ws_, int32_t T)
+{
+    if (T > kFuseMaxTokens) return false;
+    for (int p = 0; p < n; ++p)
+        if (!fast_weight(ws_[p]) || !rots[p]->plan || rots[p]->n_layers != rots[0]->n_layers) return false;
+    return true;
+}
+
+static paro_status check_multi(int32_t n, const paro_rotation *const *rots, const paro_w4_weight *const *ws_)
+{
+    if (!rots || !ws_) return PARO_ERR_NULL;
+    if (n < 1 || n > 4) return PARO_ERR_SHAPE;
+    for (int p = 0; p < n; ++p) {
+        paro_status st = check_rotation(rots[p]);
+        if (st != PARO_OK) return st;
+        st = check_weight(ws_[p], false);
+        if (st != PARO_OK) return st;
+        if (rots[p]->c_in != ws_[p]->c_in || ws_[p]->c_in != ws_[0]->c_in) return PARO_ERR_SHAPE;
+    }
+    return PARO_OK;
+}
+
+size_t paro_workspace_bytes_multi(int32_t n_parts, const paro_rotation *const *rots,
+                                  const paro_w4_weight *const *weights, int32_t T)
+{
+    if (check_multi(n_parts, rots, weights) != PARO_OK || T <= 0) return 0;
+    size_t need = 0;
+    for (int p = 0; p < n_parts; ++p) {
+        size_t one = ws_layout(rots[p], weights[p], T).total;
+        if (one > need) need = one;
+    }
+    if (multi_one_launch(n_parts, rots, weights, T)) {
+        size_t m = paro::decode_multi_bytes(n_parts, weights, T);
+        if (m > need) need = m;
+    }
+    return need;
+}
+
+paro_status paro_rotated_linear_multi(int32_t n_parts, const paro_rotation *const *rots,
+                                      const paro_w4_weight *const *weights, const paro_half_t *X, int64_t ldx,
+                                      paro_half_t *const *Y, const int64_t *ldy, int32_t T, void *ws, size_t ws_bytes,
+                                      void *stream)
+{
+    paro_status st = check_multi(n_parts, rots, weights);
+    if (st != PARO_OK) return st;
+    if (!Y || !ldy) return PARO_ERR_NULL;
+    for (int p = 0; p < n_parts; ++p) {
+        st = check_io(X, ldx, weights[p]->c_in, Y[p], ldy[p], weights[p]->c_out, T, 8);
+        if (st != PARO_OK) return st;
+    }
+    const size_t need = paro_workspace_bytes_multi(n_parts, rots, weights, T);
+    if (need && (!ws || ws_bytes < need)) return PARO_ERR_WORKSPACE;
+    if (need && !aligned(ws, 256)) return PARO_ERR_ALIGN;
+    if (multi_one_launch(n_parts, rots, weights, T))
+        return from_hip(paro::launch_decode_multi(n_parts, rots, weights, X, ldx, Y, ldy, T, ws, (hipStream_t)stream));
+    for (int p = 0; p < n_parts; ++p) {
+        st = paro_rotated_linear(rots[p], weights[p], X, ldx, Y[p], ldy[p], T, ws, ws_bytes, stream);
+        if (st != PARO_OK) return st;
+    }
+    return PARO_OK;
+}
+
 paro_status paro_w4_quantize(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int32_t c_in, int32_t c_out,
                              uint32_t *qweight, paro_half_t *scales, uint32_t *qzeros, void *stream)
 {

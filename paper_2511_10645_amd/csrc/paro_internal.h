@@ -98,9 +98,15 @@ struct DecodeGeometry {
     size_t partial_bytes;   // fp32 partial sums [ks][T][c_out] (0 when ks == 1)
     size_t counter_bytes;   // unused (0)
 };
-DecodeGeometry decode_geometry(int c_in, int c_out, int T);
+DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks = 0);
 hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                          paro_half_t *Y, int64_t ldy, int T, void *ws, hipStream_t s);
+// Several linears on the same activations, each with its own transform, in one launch (T <= 4;
+// every part planned and repacked, same c_in and layer count).  Workspace: decode_multi_bytes.
+size_t decode_multi_bytes(int n_parts, const paro_w4_weight *const *w, int T);
+hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, const paro_w4_weight *const *w,
+                               const paro_half_t *X, int64_t ldx, paro_half_t *const *Y, const int64_t *ldy, int T,
+                               void *ws, hipStream_t s);
 // Wide decode variant (bare linear, T <= 16): 8 K-slices per block, reduced through LDS.
 size_t decode_wide_partial_bytes(int c_in, int c_out, int T);
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,

@@ -130,3 +130,33 @@ def test_quantize_argument_errors():
     assert qz(rot=_rot(c_in=1024)) == E_SHAPE            # rot.c_in != c_in
     assert qz(rot=_rot()) == E_UNSUP                      # a rotation without its plan
     assert qz(rot=_rot(n_layers=9)) == E_UNSUP
+
+
+def test_multi_argument_errors():
+    L = paro.lib()
+    r1, r2 = _rot(c_in=1024), _rot(c_in=1024)
+    w1, w2 = _w(c_in=1024, packed=FAKE), _w(c_in=1024, c_out=64, packed=FAKE)
+    RA = (ctypes.c_void_p * 2)(ctypes.addressof(r1), ctypes.addressof(r2))
+    WA = (ctypes.c_void_p * 2)(ctypes.addressof(w1), ctypes.addressof(w2))
+    YA = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    LD = (ctypes.c_int64 * 2)(512, 64)
+    L.paro_workspace_bytes_multi.restype = ctypes.c_size_t
+    L.paro_workspace_bytes_multi.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
+    need = L.paro_workspace_bytes_multi(2, RA, WA, 1)
+    single = max(L.paro_workspace_bytes(ctypes.byref(r1), ctypes.byref(w1), 1), L.paro_workspace_bytes(ctypes.byref(r2), ctypes.byref(w2), 1))
+    assert need >= single > 0
+    call = lambda n=2, ra=RA, wa=WA, X=FAKE, ya=YA, ld=LD, T=1, ws=FAKE, nbytes=1 << 30: L.paro_rotated_linear_multi(
+        n, ra, wa, X, 1024, ya, ld, T, ws, nbytes, None)
+    assert call(n=0) == E_SHAPE
+    assert call(n=5) == E_SHAPE
+    assert call(ra=None) == E_NULL
+    assert call(ya=None) == E_NULL
+    assert call(ws=None, nbytes=0) == E_WS
+    assert call(nbytes=need - 1) == E_WS
+    r3 = _rot(c_in=512)
+    RB = (ctypes.c_void_p * 2)(ctypes.addressof(r1), ctypes.addressof(r3))
+    assert call(ra=RB) == E_SHAPE                                   # a part whose rotation does not fit its weight
+    w3 = _w(c_in=512, packed=FAKE)
+    WB = (ctypes.c_void_p * 2)(ctypes.addressof(w1), ctypes.addressof(w3))
+    assert call(ra=RB, wa=WB) == E_SHAPE                            # parts with different c_in
+    assert L.paro_workspace_bytes_multi(2, RB, WB, 1) == 0
