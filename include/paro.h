@@ -183,6 +183,18 @@ paro_status paro_w4_quantize(const paro_rotation *rot, const paro_half_t *W, int
                              int32_t c_in, int32_t c_out, uint32_t *qweight, paro_half_t *scales,
                              uint32_t *qzeros, void *stream);
 
+/* Activation side of the W4A4 extension (App. A.3: Y' = Q(X T^-1) . Q(T W) + b): the transform of
+ * paro_rotate_scale followed at once by a 4-bit quantiser of the transformed activations.  The
+ * paper names no activation quantiser, so Eq. 1 (b = 4) is applied per token and 128-channel
+ * group with the decisions of paro_w4_quantize (fp32, stored fp16 scale, round-half-to-even,
+ * scale floor 2^-14, zero point clamped to 0..15).  The rotation needs its plan.
+ * codes [T][c_in/8] (bits 4k..4k+3 of word w hold channel 8w+k), scales [T][c_in/128] fp16,
+ * zeros [T][c_in/128] bytes; all device, written completely.  X as in paro_rotate_scale.
+ * No INT4 x INT4 contraction is part of this library: the call ends at the quantised activations. */
+paro_status paro_rotate_scale_quantize_int4(const paro_rotation *rot, const paro_half_t *X, int64_t ldx,
+                                            int32_t T, uint32_t *codes, paro_half_t *scales,
+                                            uint8_t *zeros, void *stream);
+
 /* Test hooks for the bit-exact gate --------------------------------------------------- */
 
 /* codes[n][c] = q[n, c] as bytes 0..15 (from w->packed if set, else from w->qweight). */

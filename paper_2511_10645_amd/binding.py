@@ -71,6 +71,7 @@ def lib():
         L.paro_w4_unpack_zeros.argtypes = [wp, vp, vp]
         L.paro_w4_dequant.argtypes = [wp, vp, vp]
         L.paro_w4_quantize.argtypes = [rp, vp, i64, i32, i32, vp, vp, vp, vp]
+        L.paro_rotate_scale_quantize_int4.argtypes = [rp, vp, i64, i32, vp, vp, vp, vp]
         L.paro_workspace_bytes_multi.restype = sz
         L.paro_workspace_bytes_multi.argtypes = [i32, vp, vp, i32]
         L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
@@ -78,7 +79,8 @@ def lib():
         L.paro_tune_decode_waves.restype = None
         for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
-                     "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi"):
+                     "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
+                     "paro_rotate_scale_quantize_int4"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -309,3 +311,15 @@ def paro_rotated_linear_multi(rots, weights, x: torch.Tensor, ws: Workspace, ys=
     _check(lib().paro_rotated_linear_multi(n, _ptr_array(rots), _ptr_array(weights), x.data_ptr(), ldx, y_ptrs, ldys, T,
                                            ws.buf.data_ptr(), ws.nbytes, _stream()), "paro_rotated_linear_multi")
     return ys
+
+
+def paro_rotate_scale_quantize_int4(rot: Rotation, X: torch.Tensor):
+    """Transform, then INT4-quantise per (token, group): returns (codes int32 [T][C/8], scales fp16 [T][G], zeros uint8 [T][G])."""
+    T, ldx = _rows(X)
+    C, G = rot.c_in, rot.c_in // 128
+    codes = torch.empty((T, C // 8), dtype=torch.int32, device=X.device)
+    scales = torch.empty((T, G), dtype=torch.float16, device=X.device)
+    zeros = torch.empty((T, G), dtype=torch.uint8, device=X.device)
+    _check(lib().paro_rotate_scale_quantize_int4(rot.ref(), X.data_ptr(), ldx, T, codes.data_ptr(), scales.data_ptr(),
+                                                 zeros.data_ptr(), _stream()), "paro_rotate_scale_quantize_int4")
+    return codes, scales, zeros

@@ -118,6 +118,10 @@ hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, 
 hipError_t launch_quantize(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int N, int C, uint32_t *qweight,
                            paro_half_t *scales, uint32_t *qzeros, hipStream_t s);
 
+// Transformed activations quantised to INT4 per (token, group) right after the rotation (rot.plan set).
+hipError_t launch_quantize_act(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
+                               paro_half_t *scales, uint8_t *zeros, hipStream_t s);
+
 // Prefill-side linear (MFMA GEMM on the repacked weight), any T.
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T);
 double gemm_estimate_us(const paro_w4_weight &w, int T);

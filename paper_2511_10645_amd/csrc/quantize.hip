@@ -119,4 +119,87 @@ hipError_t launch_quantize(const paro_rotation *rot, const paro_half_t *W, int64
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Activation side of the W4A4 extension (App. A.3: Y' = Q(X T^-1) . Q(T W) + b): the transformed
+// activations are quantised to INT4 right after the rotation, while they are still in the
+// wave's registers.  The paper names no activation quantiser of its own, so Eq. 1 (b = 4) is
+// applied per token and 128-channel group, with the same decisions as on the weight side.
+// One wavefront per (token, group); outputs per token: codes [c_in/8] words, scale and zero
+// point per group.
+// ------------------------------------------------------------------------------------------
+constexpr int kActWaves = 4;
+
+template <int K>
+__global__ __launch_bounds__(kActWaves * 64) void quantize_act_kernel(const uint32_t *__restrict__ plan,
+                                                                       const _Float16 *__restrict__ X, int64_t ldx, int T,
+                                                                       int C, uint32_t *__restrict__ codes,
+                                                                       _Float16 *__restrict__ scales,
+                                                                       uint8_t *__restrict__ zeros)
+{
+    __shared__ _Float16 s_stage[kActWaves][kGroup];
+    __shared__ uint8_t s_codes[kActWaves][kGroup];
+    const int g = blockIdx.x, G = C / kGroup;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.y * kActWaves + wave;
+    if (t >= T) return;
+
+    LanePlan<K> P;
+    load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
+    *(uint32_t *)&s_stage[wave][2 * lane] = *((const uint32_t *)(X + (size_t)t * ldx + (size_t)g * kGroup) + lane);
+    __builtin_amdgcn_wave_barrier();
+    float a[1] = {(float)s_stage[wave][P.in_a] * P.sia};
+    float b[1] = {(float)s_stage[wave][P.in_b] * P.sib};
+    rotate_layers<K, 1>(P, a, b);
+    const float va = a[0] * P.soa, vb = b[0] * P.sob;
+
+    float mn = fminf(va, vb), mx = fmaxf(va, vb);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, off, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    }
+    float s32 = (mx - mn) / 15.0f;
+    if (!(s32 >= 6.103515625e-05f)) s32 = 6.103515625e-05f;
+    const _Float16 s16 = (_Float16)s32;
+    const float s = (float)s16;
+    float zf = -rintf(mn / s);
+    zf = fminf(fmaxf(zf, 0.0f), 15.0f);
+    s_codes[wave][P.out_a] = (uint8_t)fminf(fmaxf(rintf(va / s) + zf, 0.0f), 15.0f);
+    s_codes[wave][P.out_b] = (uint8_t)fminf(fmaxf(rintf(vb / s) + zf, 0.0f), 15.0f);
+    __builtin_amdgcn_wave_barrier();
+    if (lane < kGroup / 8) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) word |= (uint32_t)s_codes[wave][lane * 8 + k] << (4 * k);
+        codes[(size_t)t * (C / 8) + (size_t)g * (kGroup / 8) + lane] = word;
+    }
+    if (lane == 0) { scales[(size_t)t * G + g] = s16; zeros[(size_t)t * G + g] = (uint8_t)zf; }
+}
+
+template <int K>
+static hipError_t launch_quantize_act_k(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T,
+                                        uint32_t *codes, paro_half_t *scales, uint8_t *zeros, hipStream_t s)
+{
+    hipLaunchKernelGGL(quantize_act_kernel<K>, dim3(rot.c_in / kGroup, (T + kActWaves - 1) / kActWaves),
+                       dim3(kActWaves * 64), 0, s, (const uint32_t *)rot.plan, (const _Float16 *)X, ldx, T, rot.c_in, codes,
+                       (_Float16 *)scales, zeros);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_act(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
+                               paro_half_t *scales, uint8_t *zeros, hipStream_t s)
+{
+    switch (rot.n_layers) {
+    case 0: return launch_quantize_act_k<0>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 1: return launch_quantize_act_k<1>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 2: return launch_quantize_act_k<2>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 3: return launch_quantize_act_k<3>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 4: return launch_quantize_act_k<4>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 5: return launch_quantize_act_k<5>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 6: return launch_quantize_act_k<6>(rot, X, ldx, T, codes, scales, zeros, s);
+    case 7: return launch_quantize_act_k<7>(rot, X, ldx, T, codes, scales, zeros, s);
+    default: return launch_quantize_act_k<8>(rot, X, ldx, T, codes, scales, zeros, s);
+    }
+}
+
 }  // namespace paro

@@ -160,3 +160,17 @@ def test_multi_argument_errors():
     WB = (ctypes.c_void_p * 2)(ctypes.addressof(w1), ctypes.addressof(w3))
     assert call(ra=RB, wa=WB) == E_SHAPE                            # parts with different c_in
     assert L.paro_workspace_bytes_multi(2, RB, WB, 1) == 0
+
+
+def test_activation_quantize_argument_errors():
+    L = paro.lib()
+    q = lambda r, X=FAKE, ldx=512, T=1, c=FAKE, s=FAKE, z=FAKE: L.paro_rotate_scale_quantize_int4(
+        ctypes.byref(r), X, ldx, T, c, s, z, None)
+    assert L.paro_rotate_scale_quantize_int4(None, FAKE, 512, 1, FAKE, FAKE, FAKE, None) == E_NULL
+    assert q(_rot(), X=None) == E_NULL
+    assert q(_rot(), z=None) == E_NULL
+    assert q(_rot(), T=0) == E_SHAPE
+    assert q(_rot(), ldx=256) == E_SHAPE
+    assert q(_rot(), ldx=513) == E_ALIGN
+    assert q(_rot()) == E_UNSUP                       # no plan
+    assert q(_rot(n_layers=9, plan=FAKE)) == E_UNSUP

@@ -145,3 +145,44 @@ def test_quantize_then_linear_end_to_end(P):
     say(f"  relative output error: {errs}")
     assert errs["rotated"] < 0.9 * errs["plain"], errs
     assert errs["rotated"] < 0.2
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=501, T=1, c_in=512, n_layers=8, ppl=64, order=0),
+    dict(seed=502, T=7, c_in=1536, n_layers=8, ppl=64, order=1),
+    dict(seed=503, T=33, c_in=256, n_layers=3, ppl=17, order=0),
+    dict(seed=504, T=5, c_in=512, n_layers=0, ppl=1, order=0),
+    dict(seed=505, T=16, c_in=4096, n_layers=8, ppl=64, order=0),
+])
+def test_activation_int4_after_rotation(P, case):
+    """Transformed activations quantised per (token, group) by Eq. 1: same gate as the rotated weights."""
+    import torch
+    say(f"activation int4 {case}")
+    li = pin.make_custom(case["seed"], case["T"], case["c_in"], 8, n_layers=case["n_layers"], pairs_per_layer=case["ppl"],
+                         n_outlier=3)
+    rot = P.Rotation(li.pairs, li.theta, li.ch_scale, scale_order=case["order"])
+    P.paro_rotation_plan_build(rot)
+    codes_t, scales_t, zeros_t = P.paro_rotate_scale_quantize_int4(rot, torch.as_tensor(li.x).cuda())
+    torch.cuda.synchronize()
+    codes = oracle.unpack_codes(codes_t.cpu().numpy().view(np.uint32))                  # [T][C]
+    scales = scales_t.cpu().numpy()                                                      # [T][G]
+    zeros = zeros_t.cpu().numpy()
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale, scale_order=case["order"])
+    rc, rs, rz = oracle.rtn_quantize(u)                                                  # scales / zeros [G][T]
+    T, C = u.shape
+    G = C // 128
+    ds = np.abs(scales.view(np.uint16).astype(np.int32) - rs.T.view(np.uint16).astype(np.int32))
+    assert ds.max() <= 1, ds.max()
+    u4 = u.reshape(T, G, 128)
+    s = scales.astype(np.float64)[:, :, None]
+    z = zeros.astype(np.float64)[:, :, None]
+    tol = 0.5 + 2.0 ** -18 * np.linalg.norm(u4, axis=2, keepdims=True) / s + 1e-6 * 16
+    assert np.all(np.abs(z - np.clip(-u4.min(axis=2, keepdims=True) / s, 0, 15)) <= tol)
+    c4 = codes.reshape(T, G, 128).astype(np.float64)
+    assert np.all(np.abs(c4 - np.clip(u4 / s + z, 0, 15)) <= tol)
+    same = ((ds == 0) & (zeros == rz.T))[:, :, None]
+    agree = (c4 == rc.reshape(T, G, 128))[np.broadcast_to(same, c4.shape)]
+    assert agree.mean() > 0.999, agree.mean()
+    if case["n_layers"] == 0 and case["order"] == 0:
+        # no rotation: products of two fp16 values are exact in fp32, every decision is unique
+        assert np.array_equal(codes, rc) and np.array_equal(zeros, rz.T)
