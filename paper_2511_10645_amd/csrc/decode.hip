@@ -209,16 +209,16 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
 }
 
 // K: rotation layers fused in front.  SPLIT: more than one K-slice.  T1: exactly one token.
-template <int K, bool SPLIT, bool T1>
+template <int K, bool SPLIT, bool T1, int W = kDecWaves>
 __device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, const int nb,
                                             _Float16 (*s_x)[kSliceCh + kXPad], float *s_red)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tile_lo = nb * a.tiles_per_block;
     const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
-    const int n_iter = (tile_hi - tile_lo + kDecWaves - 1) / kDecWaves;      // same for all waves of the block
+    const int n_iter = (tile_hi - tile_lo + W - 1) / W;      // same for all waves of the block
     auto tile_of = [&](int i) {                                              // -1: nothing to do
-        int t = tile_lo + wave + i * kDecWaves;
+        int t = tile_lo + wave + i * W;
         return (i < n_iter && t < tile_hi) ? t : -1;
     };
     const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
@@ -230,13 +230,15 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, c
     const int ft = lane & 15, fkb = lane >> 4;
     const size_t c0 = (size_t)ks * kSliceCh;
     {
-        // wave w rotates group w of the slice for all T tokens
-        const int gi = wave;
+        // wave w < 4 rotates group w of the slice for all T tokens; further waves only stream
+        const int gi = wave & (kSliceGroups - 1);
+        const bool rw = W == kSliceGroups || wave < kSliceGroups;
         const uint32_t *gplan = a.plan + ((size_t)ks * kSliceGroups + gi) * plan_group_dwords(K);
         // natural-order load first (independent of the plan), staged through LDS
-        for (int t = 0; t < a.T; ++t)
-            *(uint32_t *)&s_x[t][gi * kGroup + 2 * lane] =
-                *(const uint32_t *)(a.X + (size_t)t * a.ldx + c0 + gi * kGroup + 2 * lane);
+        if (rw)
+            for (int t = 0; t < a.T; ++t)
+                *(uint32_t *)&s_x[t][gi * kGroup + 2 * lane] =
+                    *(const uint32_t *)(a.X + (size_t)t * a.ldx + c0 + gi * kGroup + 2 * lane);
         uint32_t io = gplan[lane];
         float sia = __uint_as_float(gplan[64 + lane]), sib = __uint_as_float(gplan[128 + lane]);
         float soa = __uint_as_float(gplan[192 + lane]), sob = __uint_as_float(gplan[256 + lane]);
@@ -252,7 +254,7 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, c
         load_stage(blob, a, tile_of(0), ks, lane, st0);
         load_stage(blob, a, tile_of(1), ks, lane, st1);
         const int in_a = io & 0xff, in_b = (io >> 8) & 0xff, out_a = (io >> 16) & 0xff, out_b = io >> 24;
-        for (int t = 0; t < a.T; ++t) {
+        for (int t = 0; t < (rw ? a.T : 0); ++t) {
             float va = (float)s_x[t][gi * kGroup + in_a] * sia;
             float vb = (float)s_x[t][gi * kGroup + in_b] * sib;
 #pragma unroll
@@ -355,12 +357,12 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, c
     if constexpr (SPLIT) splitk_reduce(a, a.KS, ks, tile_lo, tile_hi, s_red);
 }
 
-template <int K, bool SPLIT, bool T1>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a)
+template <int K, bool SPLIT, bool T1, int W = kDecWaves>
+__global__ __launch_bounds__(W * 64) void decode_kernel(DecodeArgs a)
 {
     __shared__ _Float16 s_x[16][kSliceCh + kXPad];
     __shared__ float s_red[kReduceWords];
-    decode_body<K, SPLIT, T1>(a, blockIdx.x, blockIdx.y, s_x, s_red);
+    decode_body<K, SPLIT, T1, W>(a, blockIdx.x, blockIdx.y, s_x, s_red);
 }
 
 // Several linears that read the same activations, each with its own transform (every linear of
@@ -393,18 +395,32 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
     DecodeGeometry d;
     int G = c_in / kGroup, NT = c_out / kTileN;
     d.ks = G / kSliceGroups;
-    d.waves = kDecWaves;
+    // measured: with many K-slices (few tiles per slice and block) one 8-wave block per CU beats
+    // two 4-wave blocks (14336 -> 4096, one token: 10.4 against 11.2 us); single launches only
+    d.waves = (T == 1 && d.ks >= 16 && target_blocks == 0 && g_decode_target_blocks == 0) ? 2 * kDecWaves : kDecWaves;
     // measured on MI355X: one 4-wave block per CU for the small linears (the prologue is repeated
     // less often), two per CU once the weight stream exceeds ~24 MB
     int target = target_blocks > 0 ? target_blocks : g_decode_target_blocks;
     if (target <= 0) target = packed_tiles_bytes(c_in, c_out) >= (24u << 20) ? 512 : 256;
+    if (d.waves > kDecWaves) target = 256;
     int nb = target / d.ks;
     if (nb < 1) nb = 1;
     int tpb = (NT + nb - 1) / nb;
-    tpb = (tpb + kDecWaves - 1) / kDecWaves * kDecWaves;     // whole rounds of the block's waves
-    if (tpb > kMaxIter * kDecWaves) tpb = kMaxIter * kDecWaves;
+    tpb = (tpb + d.waves - 1) / d.waves * d.waves;           // whole rounds of the block's waves
+    if (tpb > kMaxIter * d.waves) tpb = kMaxIter * d.waves;
     d.tiles_per_block = tpb;
     d.nb = (NT + tpb - 1) / tpb;
+    if (d.waves > kDecWaves && d.ks * d.nb > 256) {           // would not fit one round of 8-wave blocks
+        d.waves = kDecWaves;
+        target = packed_tiles_bytes(c_in, c_out) >= (24u << 20) ? 512 : 256;
+        nb = target / d.ks;
+        if (nb < 1) nb = 1;
+        tpb = (NT + nb - 1) / nb;
+        tpb = (tpb + d.waves - 1) / d.waves * d.waves;
+        if (tpb > kMaxIter * d.waves) tpb = kMaxIter * d.waves;
+        d.tiles_per_block = tpb;
+        d.nb = (NT + tpb - 1) / tpb;
+    }
     int t16 = T < 16 ? T : 16;
     d.partial_bytes = d.ks > 1 ? (size_t)d.ks * t16 * c_out * sizeof(float) : 0;
     d.counter_bytes = 0;
@@ -414,7 +430,11 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
 template <int K>
 static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, hipStream_t s)
 {
-    const dim3 grid(d.ks, d.nb), block(kDecThreads);
+    const dim3 grid(d.ks, d.nb), block(d.waves * 64);
+    if (d.waves == 2 * kDecWaves) {      // only chosen for one token and many K-slices
+        hipLaunchKernelGGL((decode_kernel<K, true, true, 2 * kDecWaves>), grid, block, 0, s, a);
+        return hipGetLastError();
+    }
     if (a.T == 1) {
         if (d.ks > 1) hipLaunchKernelGGL((decode_kernel<K, true, true>), grid, block, 0, s, a);
         else          hipLaunchKernelGGL((decode_kernel<K, false, true>), grid, block, 0, s, a);
