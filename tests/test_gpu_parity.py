@@ -349,3 +349,42 @@ def test_one_workspace_shared_by_many_calls(P):
             got = P.paro_w4a16_linear(c["w"], c["x"], ws).cpu().numpy()
             _assert_linear(got, c["y_bare"], c["a_bare"], f"seq {it} bare T={c['T']} C={c['li'].c_in}")
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case", [
+    dict(T=1, c_in=1024, c_out=16 * 13, K=8, ppl=64, order=1),      # scale after the rotation
+    dict(T=3, c_in=512, c_out=64, K=3, ppl=17, order=0),            # few layers, partial matchings, sentinels
+    dict(T=2, c_in=1024, c_out=128, K=0, ppl=1, order=0),           # no rotation layer: scaling only
+    dict(T=12, c_in=1024, c_out=16 * 13, K=5, ppl=40, order=1),     # unfused path (rotation pass + wide kernel)
+])
+def test_rotated_linear_transform_variants(P, case):
+    li = pin.make_custom(1500 + case["K"] + case["T"], case["T"], case["c_in"], case["c_out"], n_layers=case["K"],
+                         pairs_per_layer=case["ppl"], n_outlier=2)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale, scale_order=case["order"])
+    y, allowed = _linear_ref(li, u)
+    rot = make_rot(P, li, scale_order=case["order"])
+    w = make_w(P, li)
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, case["T"]))
+    got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
+    _assert_linear(got, y, allowed, f"variants {case}")
+
+
+def test_selected_pairs_through_the_gpu_path(P):
+    """Algorithm A1's pairs (host) -> plan -> GPU rotation and fused linear, against the oracle."""
+    say("pair selection end to end")
+    c_in, c_out, T, K = 512, 16 * 9, 2, 8
+    G = c_in // 128
+    pairs = np.stack([P.paro_select_pairs_host(pin.make_pair_order(1600 + g), 128, K, 64)[0] for g in range(G)])
+    li = pin.make_custom(1601, T, c_in, c_out)
+    assert P.paro_validate_pairs_host(pairs) == 0
+    rot = P.Rotation(pairs, li.theta, li.ch_scale)
+    P.paro_rotation_plan_build(rot)
+    ref = oracle.rotate_scale(li.x, pairs, li.theta, li.ch_scale)
+    got = P.paro_rotate_scale(rot, dev(li.x)).cpu().numpy()
+    ok, stats = rotation_check(got, ref)
+    assert ok, stats
+    y = oracle.linear(ref, li.qweight, li.scales, li.qzeros)
+    allowed = linear_allowed(oracle.row_sqnorms(li.qweight, li.scales, li.qzeros), ref)
+    w = make_w(P, li)
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, T))
+    _assert_linear(P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy(), y, allowed, "selected pairs")
