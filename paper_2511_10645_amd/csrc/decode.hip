@@ -423,7 +423,6 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
     }
     int t16 = T < 16 ? T : 16;
     d.partial_bytes = d.ks > 1 ? (size_t)d.ks * t16 * c_out * sizeof(float) : 0;
-    d.counter_bytes = 0;
     return d;
 }
 
@@ -560,11 +559,12 @@ hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, con
 }
 
 // ------------------------------------------------------------------------------------------
-// Wide variant: a block of 8 waves covers 8 K-slices (4096 channels) of the SAME tiles; the 8
-// partial tiles are summed through LDS, so layers with c_in <= 4096 need no exchange between
-// blocks at all, and wider ones exchange 8x fewer partial sums.  Used for the bare linear and
-// for 5..16 tokens, where partial sums (T x N fp32 per K-part) would otherwise rival the
-// weight stream.  The transform, if any, has run as a separate pass.
+// Wide variant: the waves of a block cover different K-slices (one each, up to 12 = 6144
+// channels) of the SAME tiles; their partial tiles are summed through LDS, so such layers need no
+// exchange between blocks at all, and wider ones (slices spread evenly over blocks of at most 8
+// waves) exchange correspondingly fewer partial sums.  Used for the bare linear and for 5..16
+// tokens, where partial sums (T x N fp32 per K-part) would otherwise rival the weight stream.
+// The transform, if any, has run as a separate pass.
 // ------------------------------------------------------------------------------------------
 #ifndef PARO_WIDE_WAVES
 #define PARO_WIDE_WAVES 12

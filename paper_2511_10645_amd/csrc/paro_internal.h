@@ -88,15 +88,14 @@ hipError_t launch_unpack_codes(const paro_w4_weight &w, uint8_t *codes, hipStrea
 hipError_t launch_unpack_zeros(const paro_w4_weight &w, uint8_t *zeros, hipStream_t s);
 hipError_t launch_dequant(const paro_w4_weight &w, paro_half_t *W, hipStream_t s);
 
-// Decode-side linear (T <= 16 per pass).  rot == nullptr: bare linear on X.
+// Decode-side linear with the rotation fused (K-major kernel, T <= 4 at the call sites; the
+// kernel itself takes up to 16 tokens).
 struct DecodeGeometry {
     int ks;           // K-slices (grid.x)
     int nb;           // N-blocks per slice (grid.y)
-    int waves;        // waves per block
+    int waves;        // waves per block (4, or 8 for one token and many K-slices)
     int tiles_per_block;
-    int tpw;          // tiles per wave (template parameter of the kernel)
     size_t partial_bytes;   // fp32 partial sums [ks][T][c_out] (0 when ks == 1)
-    size_t counter_bytes;   // unused (0)
 };
 DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks = 0);
 hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
@@ -107,7 +106,8 @@ size_t decode_multi_bytes(int n_parts, const paro_w4_weight *const *w, int T);
 hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, const paro_w4_weight *const *w,
                                const paro_half_t *X, int64_t ldx, paro_half_t *const *Y, const int64_t *ldy, int T,
                                void *ws, hipStream_t s);
-// Wide decode variant (bare linear, T <= 16): 8 K-slices per block, reduced through LDS.
+// Wide decode kernel (bare linear, T <= 16): all K-slices of a tile range in one block (up to 12),
+// reduced through LDS; wider layers spread the slices over several blocks and exchange partials.
 size_t decode_wide_partial_bytes(int c_in, int c_out, int T);
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                               int T, void *ws, hipStream_t s);
