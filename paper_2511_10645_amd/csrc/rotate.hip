@@ -174,24 +174,33 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
     __shared__ _Float16 s_stage[kRotWaves][kRotTU][kGroup];
     const int g = blockIdx.x;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int t0 = (blockIdx.y * kRotWaves + wave) * tokens_per_wave;
     if (t0 >= T) return;
-    const int t1 = min(T, t0 + tokens_per_wave);
+    const int n_tok = min(T, t0 + tokens_per_wave) - t0;
 
-    const uint32_t *xg = (const uint32_t *)(X + (size_t)g * kGroup) + lane;     // rows are 16-byte aligned
-    uint32_t *yg = (uint32_t *)(Xr + (size_t)g * kGroup) + lane;
+    // The wave's rows through raw buffer resources based at its first row: offsets are 32-bit
+    // (a scalar row offset plus the lane's 4 bytes, in the range-checked vector offset), and rows
+    // beyond the run read as zero and are not written - no 64-bit address arithmetic, no clamps,
+    // no predication.
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<_Float16 *>(X + (size_t)t0 * ldx + (size_t)g * kGroup), 0, (int)((size_t)(n_tok - 1) * ldx * 2 + kGroup * 2),
+        0x00020000);
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(
+        Xr + (size_t)t0 * ldxr + (size_t)g * kGroup, 0, (int)((size_t)(n_tok - 1) * ldxr * 2 + kGroup * 2), 0x00020000);
+    const int row_x = (int)(ldx * 2), row_y = (int)(ldxr * 2);         // bytes per token row
+    const int v4 = lane * 4;
     uint32_t cur[kRotTU], nxt[kRotTU];
 #pragma unroll
-    for (int u = 0; u < kRotTU; ++u) cur[u] = xg[(size_t)min(t0 + u, t1 - 1) * (ldx / 2)];
+    for (int u = 0; u < kRotTU; ++u) cur[u] = __builtin_amdgcn_raw_buffer_load_b32(xr, v4 + u * row_x, 0, 0);
 
     LanePlan<K> P;
     load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
     _Float16(*st)[kGroup] = s_stage[wave];
 
-    for (int t = t0; t < t1; t += kRotTU) {
+    for (int t = 0; t < n_tok; t += kRotTU) {
 #pragma unroll
-        for (int u = 0; u < kRotTU; ++u) nxt[u] = xg[(size_t)min(t + kRotTU + u, t1 - 1) * (ldx / 2)];
+        for (int u = 0; u < kRotTU; ++u) nxt[u] = __builtin_amdgcn_raw_buffer_load_b32(xr, v4 + (t + kRotTU + u) * row_x, 0, 0);
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) *(uint32_t *)&st[u][2 * lane] = cur[u];
         __builtin_amdgcn_wave_barrier();
@@ -210,10 +219,8 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int u = 0; u < kRotTU; ++u) {
-            const uint32_t o = *(const uint32_t *)&st[u][2 * lane];
-            if (t + u < t1) yg[(size_t)(t + u) * (ldxr / 2)] = o;
-        }
+        for (int u = 0; u < kRotTU; ++u)
+            __builtin_amdgcn_raw_buffer_store_b32(*(const uint32_t *)&st[u][2 * lane], yr, v4 + (t + u) * row_y, 0, 0);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) cur[u] = nxt[u];
