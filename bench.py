@@ -188,13 +188,14 @@ def main() -> int:
 
     # ---- prefill side (config 3: 2048 tokens): rotation pass + MFMA GEMM per linear ----------------
     prefill = None
-    if not args.no_prefill and args.config == 1:
-        Tp = pin.CONFIGS[3].tokens[0]
+    if not args.no_prefill and args.config in (1, 4):
+        pcfg = 3 if args.config == 1 else 4             # config 3 = the 8B shapes at 2048 tokens; config 4 has its own 4096
+        Tp = pin.CONFIGS[pcfg].tokens[-1]
         prefill = {"tokens": Tp, "per_linear": {}}
         tot_fl = tot_us = tot_us_bare = 0.0
         for k, L in enumerate(lin):
             shp = L["shape"]
-            xp = torch.as_tensor(pin.make_x(3, k, Tp, shp.c_in, pin.CONFIGS[3].n_outlier(shp.c_in))[0]).to(dev)
+            xp = torch.as_tensor(pin.make_x(pcfg, k, Tp, shp.c_in, pin.CONFIGS[pcfg].n_outlier(shp.c_in))[0]).to(dev)
             xr = torch.empty_like(xp)
             yp = torch.empty((Tp, shp.c_out), dtype=torch.float16, device=dev)
             wsp = paro.Workspace(paro.paro_workspace_bytes(L["rot"], L["w"], Tp))
