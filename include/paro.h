@@ -195,6 +195,18 @@ paro_status paro_rotate_scale_quantize_int4(const paro_rotation *rot, const paro
                                             int32_t T, uint32_t *codes, paro_half_t *scales,
                                             uint8_t *zeros, void *stream);
 
+/* The same activation side (App. A.3) with a microscaling FP4 quantiser, the 4-bit type the
+ * matrix cores of gfx950 take directly (MXFP4 of the OCP Microscaling Formats specification):
+ * every 32 consecutive channels of a token share the scale 2^e, e = floor(log2(max|v|)) - 2,
+ * e >= -127, stored as the byte e + 127 (an all-zero block stores 0); each value is the E2M1 code
+ * of v / 2^e, round to nearest, ties to the even code, saturating at 6 (magnitudes by code 0..7:
+ * 0, 0.5, 1, 1.5, 2, 3, 4, 6; bit 3 = sign).  Inputs must be finite.  The rotation needs its plan.
+ * codes [T][c_in/8] (bits 4k..4k+3 of word w hold channel 8w+k), scales [T][c_in/32] bytes; all
+ * device, written completely.  X as in paro_rotate_scale.  The call ends at the quantised
+ * activations, as paro_rotate_scale_quantize_int4 does. */
+paro_status paro_rotate_scale_quantize_mxfp4(const paro_rotation *rot, const paro_half_t *X, int64_t ldx,
+                                             int32_t T, uint32_t *codes, uint8_t *scales, void *stream);
+
 /* Test hooks for the bit-exact gate --------------------------------------------------- */
 
 /* codes[n][c] = q[n, c] as bytes 0..15 (from w->packed if set, else from w->qweight). */

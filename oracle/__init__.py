@@ -174,6 +174,21 @@ def rtn_quantize(wt: np.ndarray, group=128):
     return codes, scales.view(np.float16), zeros
 
 
+def mxfp4_quantize(u: np.ndarray):
+    """OCP MXFP4 conversion of fp64 rows (rounded to fp32 first): codes uint8 [T][C] (E2M1, bit 3 = sign),
+    scales uint8 [T][C/32] (E8M0: shared exponent + 127)."""
+    u = _c(u, np.float64)
+    T, C = u.shape
+    assert C % 32 == 0
+    codes = np.empty((T, C), dtype=np.uint8)
+    scales = np.empty((T, C // 32), dtype=np.uint8)
+    L = lib()
+    L.oracle_mxfp4_quantize.restype = None
+    L.oracle_mxfp4_quantize(_p(u, ctypes.c_double), ctypes.c_int64(C), ctypes.c_int32(T), ctypes.c_int32(C),
+                            _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8))
+    return codes, scales
+
+
 def unpack_codes(qweight: np.ndarray) -> np.ndarray:
     q = _c(qweight, np.uint32)
     N, C8 = q.shape

@@ -248,6 +248,56 @@ void oracle_rtn_quantize(const double *wt, int64_t ldwt, int32_t N, int32_t C, i
         }
 }
 
+/*
+ * Microscaling FP4 (MXFP4: 32 consecutive values share one power-of-two scale stored as an
+ * E8M0 byte, each value is an FP4 E2M1 code), the conversion the OCP Microscaling Formats
+ * specification gives for a block V:
+ *      shared_exp = floor(log2(max |V_i|)) - 2          (2 = largest E2M1 exponent), >= -127
+ *      code_i     = E2M1( V_i / 2^shared_exp ), round to nearest, ties to even, saturating at 6
+ * E2M1 magnitudes by code 0..7: 0, 0.5, 1, 1.5, 2, 3, 4, 6; bit 3 is the sign.  An all-zero
+ * block gets the smallest scale (byte 0) and zero codes.  Input rows are fp64 and are rounded to
+ * fp32 first (the precision the GPU holds them in); everything after that is exact.
+ * codes: [T][C] bytes (0..15); scales: [T][C/32] bytes (shared_exp + 127).
+ */
+void oracle_mxfp4_quantize(const double *u, int64_t ldu, int32_t T, int32_t C, uint8_t *codes, uint8_t *scales)
+{
+    static const double grid[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+#pragma omp parallel for schedule(static)
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t b = 0; b < C / 32; ++b) {
+            const double *v = u + (int64_t)t * ldu + (int64_t)b * 32;
+            double amax = 0.0;
+            for (int i = 0; i < 32; ++i) {
+                double a = fabs((double)(float)v[i]);
+                if (a > amax) amax = a;
+            }
+            int shared = -127;
+            if (amax > 0.0) {
+                int e;
+                (void)frexp(amax, &e);               /* amax = m * 2^e, 0.5 <= m < 1  =>  floor(log2) = e - 1 */
+                shared = (e - 1) - 2;
+                if (shared < -127) shared = -127;
+            }
+            scales[(int64_t)t * (C / 32) + b] = (uint8_t)(shared + 127);
+            for (int i = 0; i < 32; ++i) {
+                double r = ldexp((double)(float)v[i], -shared);
+                double a = fabs(r);
+                int code = 7;                        /* saturate */
+                if (a <= 6.0) {
+                    /* nearest grid point, ties to the code with an even mantissa bit (even code) */
+                    double best = 1e300;
+                    code = 0;
+                    for (int k = 0; k < 8; ++k) {
+                        double d = fabs(a - grid[k]);
+                        if (d < best || (d == best && (k & 1) == 0)) { best = d; code = k; }
+                    }
+                }
+                if (r < 0.0 || (r == 0.0 && signbit(r))) code |= 8;
+                codes[(int64_t)t * C + (int64_t)b * 32 + i] = (uint8_t)code;
+            }
+        }
+}
+
 /* ---- INT4 unpack and dequantisation (Eq. 1 inverted, group rule) --------- */
 
 void oracle_unpack_codes(const uint32_t *qweight, int32_t N, int32_t C, uint8_t *codes)

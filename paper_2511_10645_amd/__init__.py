@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     lib_path,
     paro_rotate_scale,
     paro_rotate_scale_quantize_int4,
+    paro_rotate_scale_quantize_mxfp4,
     paro_rotated_linear,
     paro_rotated_linear_multi,
     paro_rotation_plan_build,

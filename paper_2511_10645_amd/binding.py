@@ -72,6 +72,7 @@ def lib():
         L.paro_w4_dequant.argtypes = [wp, vp, vp]
         L.paro_w4_quantize.argtypes = [rp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.paro_rotate_scale_quantize_int4.argtypes = [rp, vp, i64, i32, vp, vp, vp, vp]
+        L.paro_rotate_scale_quantize_mxfp4.argtypes = [rp, vp, i64, i32, vp, vp, vp]
         L.paro_workspace_bytes_multi.restype = sz
         L.paro_workspace_bytes_multi.argtypes = [i32, vp, vp, i32]
         L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
@@ -80,7 +81,7 @@ def lib():
         for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
-                     "paro_rotate_scale_quantize_int4"):
+                     "paro_rotate_scale_quantize_int4", "paro_rotate_scale_quantize_mxfp4"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -323,3 +324,14 @@ def paro_rotate_scale_quantize_int4(rot: Rotation, X: torch.Tensor):
     _check(lib().paro_rotate_scale_quantize_int4(rot.ref(), X.data_ptr(), ldx, T, codes.data_ptr(), scales.data_ptr(),
                                                  zeros.data_ptr(), _stream()), "paro_rotate_scale_quantize_int4")
     return codes, scales, zeros
+
+
+def paro_rotate_scale_quantize_mxfp4(rot: Rotation, X: torch.Tensor):
+    """Transform, then MXFP4-quantise per (token, 32 channels): returns (codes int32 [T][C/8], scales uint8 [T][C/32])."""
+    T, ldx = _rows(X)
+    C = rot.c_in
+    codes = torch.empty((T, C // 8), dtype=torch.int32, device=X.device)
+    scales = torch.empty((T, C // 32), dtype=torch.uint8, device=X.device)
+    _check(lib().paro_rotate_scale_quantize_mxfp4(rot.ref(), X.data_ptr(), ldx, T, codes.data_ptr(), scales.data_ptr(),
+                                                  _stream()), "paro_rotate_scale_quantize_mxfp4")
+    return codes, scales

@@ -397,6 +397,18 @@ paro_status paro_rotate_scale_quantize_int4(const paro_rotation *rot, const paro
     return from_hip(paro::launch_quantize_act(*rot, X, ldx, T, codes, scales, zeros, (hipStream_t)stream));
 }
 
+paro_status paro_rotate_scale_quantize_mxfp4(const paro_rotation *rot, const paro_half_t *X, int64_t ldx, int32_t T,
+                                             uint32_t *codes, uint8_t *scales, void *stream)
+{
+    paro_status st = check_rotation(rot);
+    if (st != PARO_OK) return st;
+    if (!X || !codes || !scales) return PARO_ERR_NULL;
+    if (T <= 0 || ldx < rot->c_in) return PARO_ERR_SHAPE;
+    if (ldx % 2 || !aligned(X, 4) || !aligned(codes, 4)) return PARO_ERR_ALIGN;
+    if (!rot->plan) return PARO_ERR_UNSUPPORTED;
+    return from_hip(paro::launch_quantize_act_mxfp4(*rot, X, ldx, T, codes, scales, (hipStream_t)stream));
+}
+
 // Tuning knob (process-wide, not thread-safe): target number of wavefronts of a decode launch.
 void paro_tune_decode_waves(int waves) { paro::set_decode_target_waves(waves); }
 

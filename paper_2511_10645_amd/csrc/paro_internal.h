@@ -122,6 +122,10 @@ hipError_t launch_quantize(const paro_rotation *rot, const paro_half_t *W, int64
 hipError_t launch_quantize_act(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
                                paro_half_t *scales, uint8_t *zeros, hipStream_t s);
 
+// The same with the MXFP4 quantiser: E2M1 codes, one E8M0 scale byte per 32 channels.
+hipError_t launch_quantize_act_mxfp4(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
+                                     uint8_t *scales, hipStream_t s);
+
 // Prefill-side linear (MFMA GEMM on the repacked weight), any T.
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T);
 double gemm_estimate_us(const paro_w4_weight &w, int T);

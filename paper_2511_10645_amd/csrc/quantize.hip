@@ -202,4 +202,84 @@ hipError_t launch_quantize_act(const paro_rotation &rot, const paro_half_t *X, i
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same activation side with a microscaling FP4 quantiser (MXFP4 of the OCP Microscaling
+// Formats specification, the 4-bit type the matrix cores of this chip take directly): 32
+// consecutive channels share a power-of-two scale 2^e, e = floor(log2(max|v|)) - 2 (>= -127),
+// stored as the byte e + 127; each value becomes the E2M1 code of v / 2^e, rounded to nearest
+// with ties to the even code and saturated at 6.  Everything after the rotation is exact.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t e2m1_code(float r)
+{
+    const float a = fabsf(r);
+    uint32_t c = a <= 0.25f ? 0u : a < 0.75f ? 1u : a <= 1.25f ? 2u : a < 1.75f ? 3u
+               : a <= 2.5f ? 4u : a < 3.5f ? 5u : a <= 5.0f ? 6u : 7u;
+    return c | ((__float_as_uint(r) >> 28) & 8u);
+}
+
+template <int K>
+__global__ __launch_bounds__(kActWaves * 64) void quantize_act_mxfp4_kernel(const uint32_t *__restrict__ plan,
+                                                                             const _Float16 *__restrict__ X, int64_t ldx,
+                                                                             int T, int C, uint32_t *__restrict__ codes,
+                                                                             uint8_t *__restrict__ scales)
+{
+    __shared__ _Float16 s_stage[kActWaves][kGroup];
+    __shared__ float s_val[kActWaves][kGroup];
+    __shared__ __attribute__((aligned(4))) uint8_t s_codes[kActWaves][kLanes];
+    const int g = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.y * kActWaves + wave;
+    if (t >= T) return;
+
+    LanePlan<K> P;
+    load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
+    *(uint32_t *)&s_stage[wave][2 * lane] = *((const uint32_t *)(X + (size_t)t * ldx + (size_t)g * kGroup) + lane);
+    __builtin_amdgcn_wave_barrier();
+    float a[1] = {(float)s_stage[wave][P.in_a] * P.sia};
+    float b[1] = {(float)s_stage[wave][P.in_b] * P.sib};
+    rotate_layers<K, 1>(P, a, b);
+    s_val[wave][P.out_a] = a[0] * P.soa;
+    s_val[wave][P.out_b] = b[0] * P.sob;
+    __builtin_amdgcn_wave_barrier();
+
+    // channel order from here: lane l holds channels 2l, 2l+1; 16 lanes = one 32-channel block
+    const float2 v = *(const float2 *)&s_val[wave][2 * lane];
+    float amax = fmaxf(fabsf(v.x), fabsf(v.y));
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    int e = (int)(__float_as_uint(amax) >> 23) - 127 - 2;
+    if (e < -127) e = -127;
+    const uint32_t byte = e2m1_code(ldexpf(v.x, -e)) | (e2m1_code(ldexpf(v.y, -e)) << 4);
+    s_codes[wave][lane] = (uint8_t)byte;
+    __builtin_amdgcn_wave_barrier();
+    if (lane < kGroup / 8) codes[(size_t)t * (C / 8) + (size_t)g * (kGroup / 8) + lane] = *(const uint32_t *)&s_codes[wave][4 * lane];
+    if ((lane & 15) == 0) scales[(size_t)t * (C / 32) + (size_t)g * (kGroup / 32) + (lane >> 4)] = (uint8_t)(e + 127);
+}
+
+template <int K>
+static hipError_t launch_quantize_act_mxfp4_k(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T,
+                                              uint32_t *codes, uint8_t *scales, hipStream_t s)
+{
+    hipLaunchKernelGGL(quantize_act_mxfp4_kernel<K>, dim3(rot.c_in / kGroup, (T + kActWaves - 1) / kActWaves),
+                       dim3(kActWaves * 64), 0, s, (const uint32_t *)rot.plan, (const _Float16 *)X, ldx, T, rot.c_in, codes,
+                       scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_act_mxfp4(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
+                                     uint8_t *scales, hipStream_t s)
+{
+    switch (rot.n_layers) {
+    case 0: return launch_quantize_act_mxfp4_k<0>(rot, X, ldx, T, codes, scales, s);
+    case 1: return launch_quantize_act_mxfp4_k<1>(rot, X, ldx, T, codes, scales, s);
+    case 2: return launch_quantize_act_mxfp4_k<2>(rot, X, ldx, T, codes, scales, s);
+    case 3: return launch_quantize_act_mxfp4_k<3>(rot, X, ldx, T, codes, scales, s);
+    case 4: return launch_quantize_act_mxfp4_k<4>(rot, X, ldx, T, codes, scales, s);
+    case 5: return launch_quantize_act_mxfp4_k<5>(rot, X, ldx, T, codes, scales, s);
+    case 6: return launch_quantize_act_mxfp4_k<6>(rot, X, ldx, T, codes, scales, s);
+    case 7: return launch_quantize_act_mxfp4_k<7>(rot, X, ldx, T, codes, scales, s);
+    default: return launch_quantize_act_mxfp4_k<8>(rot, X, ldx, T, codes, scales, s);
+    }
+}
+
 }  // namespace paro

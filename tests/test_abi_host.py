@@ -174,3 +174,16 @@ def test_activation_quantize_argument_errors():
     assert q(_rot(), ldx=513) == E_ALIGN
     assert q(_rot()) == E_UNSUP                       # no plan
     assert q(_rot(n_layers=9, plan=FAKE)) == E_UNSUP
+
+
+def test_activation_mxfp4_argument_errors():
+    L = paro.lib()
+    q = lambda r, X=FAKE, ldx=512, T=1, c=FAKE, s=FAKE: L.paro_rotate_scale_quantize_mxfp4(
+        ctypes.byref(r), X, ldx, T, c, s, None)
+    assert L.paro_rotate_scale_quantize_mxfp4(None, FAKE, 512, 1, FAKE, FAKE, None) == E_NULL
+    assert q(_rot(), X=None) == E_NULL
+    assert q(_rot(), s=None) == E_NULL
+    assert q(_rot(), T=0) == E_SHAPE
+    assert q(_rot(), ldx=256) == E_SHAPE
+    assert q(_rot(), ldx=513) == E_ALIGN
+    assert q(_rot()) == E_UNSUP                       # no plan

@@ -186,3 +186,51 @@ def test_activation_int4_after_rotation(P, case):
     if case["n_layers"] == 0 and case["order"] == 0:
         # no rotation: products of two fp16 values are exact in fp32, every decision is unique
         assert np.array_equal(codes, rc) and np.array_equal(zeros, rz.T)
+
+
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=601, T=1, c_in=512, n_layers=8, ppl=64, order=0),
+    dict(seed=602, T=7, c_in=1536, n_layers=8, ppl=64, order=1),
+    dict(seed=603, T=33, c_in=256, n_layers=3, ppl=17, order=0),
+    dict(seed=604, T=5, c_in=512, n_layers=0, ppl=1, order=0),
+    dict(seed=605, T=16, c_in=4096, n_layers=8, ppl=64, order=0),
+])
+def test_activation_mxfp4_after_rotation(P, case):
+    """Transformed activations in MXFP4: block exponent and E2M1 codes against the oracle's conversion of the
+    oracle's fp64 transform; a decision may differ only where the fp32 rotation error crosses a threshold."""
+    import torch
+    say(f"activation mxfp4 {case}")
+    li = pin.make_custom(case["seed"], case["T"], case["c_in"], 8, n_layers=case["n_layers"], pairs_per_layer=case["ppl"],
+                         n_outlier=3)
+    rot = P.Rotation(li.pairs, li.theta, li.ch_scale, scale_order=case["order"])
+    P.paro_rotation_plan_build(rot)
+    codes_t, scales_t = P.paro_rotate_scale_quantize_mxfp4(rot, torch.as_tensor(li.x).cuda())
+    torch.cuda.synchronize()
+    codes = oracle.unpack_codes(codes_t.cpu().numpy().view(np.uint32))                  # [T][C] nibbles
+    scales = scales_t.cpu().numpy()                                                      # [T][C/32]
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale, scale_order=case["order"])
+    rc, rs = oracle.mxfp4_quantize(u)
+    T, C = u.shape
+    de = scales.astype(np.int32) - rs.astype(np.int32)
+    assert np.abs(de).max() <= 1 and (de != 0).mean() < 1e-3, (np.abs(de).max(), (de != 0).mean())
+    # with the kernel's own exponent, every code is a nearest representable value up to the rotation's error
+    e = np.repeat(scales.astype(np.int32) - 127, 32, axis=1)
+    r = np.clip(u / 2.0 ** e, -6, 6)
+    allv = np.concatenate([-E2M1[:0:-1], E2M1])
+    best = np.abs(r[..., None] - allv).min(axis=-1)
+    got = E2M1[codes & 7] * np.where(codes & 8, -1.0, 1.0)
+    gnorm = np.repeat(np.linalg.norm(u.reshape(T, C // 128, 128), axis=2), 128, axis=1)
+    tol = 2.0 ** -18 * gnorm / 2.0 ** e + 1e-6
+    assert np.all(np.abs(got - r) <= best + tol)
+    same = np.repeat(de == 0, 32, axis=1)
+    mag_agree = ((codes & 7) == (rc & 7))[same]
+    assert mag_agree.mean() > 0.999, mag_agree.mean()
+    nz = same & ((codes & 7) != 0) & ((rc & 7) != 0)
+    assert np.array_equal((codes & 8)[nz], (rc & 8)[nz])
+    if case["n_layers"] == 0 and case["order"] == 0:
+        # no rotation: products of two fp16 values are exact in fp32, every decision is unique
+        assert np.array_equal(scales, rs)
+        assert np.array_equal(got, E2M1[rc & 7] * np.where(rc & 8, -1.0, 1.0))
