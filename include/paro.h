@@ -125,6 +125,10 @@ paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stre
 
 /* Hot path ------------------------------------------------------------------------------- */
 
+/* Row strides of activations and outputs (ldx, ldy, ldxr: in elements) must be below 2^22
+ * (PARO_ERR_UNSUPPORTED otherwise): the kernels address runs of rows with 32-bit byte offsets.
+ * T itself is not limited by that. */
+
 /* Bytes of workspace the two linear calls need for T tokens (rot may be NULL for the bare
  * linear).  The workspace must be zero-filled ONCE after allocation; every call leaves it
  * zero-filled again.  Two calls that share a workspace must not overlap in time. */

@@ -16,6 +16,7 @@ constexpr int kFuseMaxTokens = 4;     // rotation runs inside the decode kernel 
 #ifndef PARO_DECODE_MAX_TOKENS
 #define PARO_DECODE_MAX_TOKENS 16
 #endif
+constexpr int64_t kMaxRowStride = 1 << 22;   // elements; the kernels address a run of up to 256 rows with 31-bit byte offsets
 constexpr int kDecodeMaxTokens = PARO_DECODE_MAX_TOKENS;  // above this the MFMA GEMM takes over from the streaming decode kernel
 
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -55,6 +56,7 @@ paro_status check_io(const void *X, int64_t ldx, int width_x, const void *Y, int
 {
     if (!X || !Y) return PARO_ERR_NULL;
     if (T <= 0 || ldx < width_x || ldy < width_y) return PARO_ERR_SHAPE;
+    if (ldx >= kMaxRowStride || ldy >= kMaxRowStride) return PARO_ERR_UNSUPPORTED;   // 32-bit offsets inside a run of rows
     if (ldx % ld_mult || ldy % ld_mult || !aligned(X, 2 * ld_mult) || !aligned(Y, 2 * ld_mult)) return PARO_ERR_ALIGN;
     return PARO_OK;
 }
@@ -88,6 +90,18 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
     if (!fast_weight(w)) {
         if (!(w->qweight && w->scales && w->qzeros)) return PARO_ERR_UNSUPPORTED;
         return from_hip(launch_linear_generic(*w, X, ldx, Y, ldy, T, s));
+    }
+    if (T >= 512 && !gemm_supported(*w, ldx, ldy, T) && gemm_supported(*w, ldx, ldy, 256)) {
+        // The GEMM addresses X and Y through 31-bit byte offsets: walk longer inputs in runs of
+        // whole 256-token tiles that fit.
+        const int64_t ld = ldx > ldy ? ldx : ldy;
+        const int64_t chunk = (((int64_t)1 << 30) - 1) / ld / 256 * 256;
+        for (int64_t t0 = 0; t0 < T; t0 += chunk) {
+            const int tc = (int)(T - t0 < chunk ? T - t0 : chunk);
+            paro_status st = run_linear(w, X + t0 * ldx, ldx, Y + t0 * ldy, ldy, tc, ws, s);
+            if (st != PARO_OK) return st;
+        }
+        return PARO_OK;
     }
     if (T > kDecodeMaxTokens && gemm_supported(*w, ldx, ldy, T)) {
         // Moderate token counts leave most of the chip idle in the GEMM (few token tiles), while the
@@ -392,6 +406,7 @@ paro_status paro_rotate_scale_quantize_int4(const paro_rotation *rot, const paro
     if (st != PARO_OK) return st;
     if (!X || !codes || !scales || !zeros) return PARO_ERR_NULL;
     if (T <= 0 || ldx < rot->c_in) return PARO_ERR_SHAPE;
+    if (ldx >= kMaxRowStride) return PARO_ERR_UNSUPPORTED;
     if (ldx % 2 || !aligned(X, 4) || !aligned(codes, 4) || !aligned(scales, 2)) return PARO_ERR_ALIGN;
     if (!rot->plan) return PARO_ERR_UNSUPPORTED;
     return from_hip(paro::launch_quantize_act(*rot, X, ldx, T, codes, scales, zeros, (hipStream_t)stream));
@@ -404,6 +419,7 @@ paro_status paro_rotate_scale_quantize_mxfp4(const paro_rotation *rot, const par
     if (st != PARO_OK) return st;
     if (!X || !codes || !scales) return PARO_ERR_NULL;
     if (T <= 0 || ldx < rot->c_in) return PARO_ERR_SHAPE;
+    if (ldx >= kMaxRowStride) return PARO_ERR_UNSUPPORTED;
     if (ldx % 2 || !aligned(X, 4) || !aligned(codes, 4)) return PARO_ERR_ALIGN;
     if (!rot->plan) return PARO_ERR_UNSUPPORTED;
     return from_hip(paro::launch_quantize_act_mxfp4(*rot, X, ldx, T, codes, scales, (hipStream_t)stream));

@@ -187,3 +187,14 @@ def test_activation_mxfp4_argument_errors():
     assert q(_rot(), ldx=256) == E_SHAPE
     assert q(_rot(), ldx=513) == E_ALIGN
     assert q(_rot()) == E_UNSUP                       # no plan
+
+
+def test_row_stride_limit():
+    """Strides of 2^22 elements and more are refused before any launch (32-bit offsets inside a run of rows)."""
+    L = paro.lib()
+    big = 1 << 22
+    assert L.paro_rotate_scale(ctypes.byref(_rot()), FAKE, big, FAKE, 512, 1, None) == E_UNSUP
+    assert L.paro_rotate_scale(ctypes.byref(_rot()), FAKE, 512, FAKE, big, 1, None) == E_UNSUP
+    w = _w(packed=FAKE)
+    assert L.paro_w4a16_linear(ctypes.byref(w), FAKE, big, FAKE, 8192, 1, None, 0, None) == E_UNSUP
+    assert L.paro_rotate_scale_quantize_mxfp4(ctypes.byref(_rot(plan=FAKE)), FAKE, big, 1, FAKE, FAKE, None) == E_UNSUP

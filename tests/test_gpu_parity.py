@@ -225,6 +225,23 @@ def test_rotated_linear(P, case):
         assert int(ws.buf.sum().item()) == 0                             # fused path leaves the workspace zero-filled
 
 
+def test_long_strided_input_walked_in_runs(P):
+    """Rows 4 MiB apart: 600 of them span more than the 31-bit offsets one GEMM launch addresses, so the
+    call walks the tokens in runs of whole tiles (256 + 256 + 88 here); results as for any other input."""
+    import torch
+    T, c_in, c_out, ld = 600, 512, 16 * 21, 1 << 21
+    say(f"long strided input T={T} ld={ld}")
+    li = pin.make_custom(4242, T, c_in, c_out, n_outlier=3)
+    y, allowed = _linear_ref(li, li.x.astype(np.float64))
+    w = make_w(P, li)
+    ws = P.Workspace(P.paro_workspace_bytes(None, w, T))
+    big = torch.empty((T, ld), dtype=torch.float16, device="cuda")
+    big[:, :c_in] = dev(li.x)
+    got = P.paro_w4a16_linear(w, big[:, :c_in], ws).cpu().numpy()
+    del big
+    _assert_linear(got, y, allowed, "bare, long strided input")
+
+
 def test_identity_transform_equals_bare_linear(P):
     """theta = 0 and scale = 1: the fused call must give the bare linear's bits."""
     li = pin.make_custom(31, 2, 1024, 256)
