@@ -712,8 +712,8 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
     a.KS = a.G / kSliceGroups;
     a.tiles_per_block = g.tiles_per_block;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
         const void *fns[4] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
                               (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>};
         for (const void *f : fns) {
@@ -721,7 +721,7 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
                                                (int)(((size_t)kMaxIter * kWideWaves * 256 + kReduceWords) * sizeof(float)));
             if (e != hipSuccess) return e;
         }
-        attr_set = true;
+        once_done(attr_done, dev);
     }
     const dim3 grid(g.kb, g.nb), block(g.waves * 64);
     if (T == 1) {

@@ -339,12 +339,12 @@ static hipError_t launch_gemm_cfg(GemmArgs &a, int n_tile0, int n_count, hipStre
     const int rounds = (patches + 7) / 8;                 // patches per XCD
     const int blocks = rounds * 8 * pb;
     const size_t lds = (size_t)2 * (BM + kBN) * kLdsRow * sizeof(_Float16);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel<MI, NI, WM, WN>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        once_done(attr_done, dev);
     }
     hipLaunchKernelGGL((gemm_w4a16_kernel<MI, NI, WM, WN>), dim3(blocks), dim3(WM * WN * 64), lds, s, a);
     return hipGetLastError();

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 
 #include "paro.h"
 
@@ -73,6 +74,20 @@ __host__ __device__ inline PackedView packed_view(const void *blob, int c_in, in
 
 // nibble position of logical element e (0..7) inside a repacked dword
 __host__ __device__ inline int packed_nibble_pos(int e) { return (e >> 1) + 4 * (e & 1); }
+
+// Kernel attributes (dynamic LDS limit) are per device: a launcher sets them the first time it
+// runs on each device.  once_pending() returns the current device if the caller still has to do
+// that there (two threads may both do it: the call is idempotent), -1 if it is done.
+inline int once_pending(std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 64;      // not tracked: set every time
+    return ((done.load(std::memory_order_acquire) >> dev) & 1) ? -1 : dev;
+}
+inline void once_done(std::atomic<uint64_t> &done, int dev)
+{
+    if (dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
+}
 
 // ---------------------------------------------------------------------------------------
 // Launchers (defined next to their kernels).  All return the hipError_t of the launch.
