@@ -186,14 +186,21 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
             ptr[u] = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
             bits[u] = on ? __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
         }
+        // words still empty are requested again, all of a thread's in one round trip
+        for (int spin = 0; spin < kSpinLimit; ++spin) {
+            bool empty = false;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) empty |= bits[u] == 0u;
+            if (!empty) break;
+#pragma unroll
+            for (int u = 0; u < PER; ++u)
+                if (bits[u] == 0u)
+                    bits[u] = __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int j = threadIdx.x + u * THREADS;
-            if (j < n_out * parts) {
-                for (int spin = 0; bits[u] == 0u && spin < kSpinLimit; ++spin)
-                    bits[u] = __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
-            }
+            if (j < n_out * parts) s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
         }
         __syncthreads();
         for (int i = threadIdx.x; i < n_out; i += THREADS) {
