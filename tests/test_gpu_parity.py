@@ -225,6 +225,34 @@ def test_rotated_linear(P, case):
         assert int(ws.buf.sum().item()) == 0                             # fused path leaves the workspace zero-filled
 
 
+@pytest.mark.parametrize("T", [1, 3, 16, 40, 300])
+@pytest.mark.parametrize("fused", [False, True])
+def test_linear_with_padded_rows(P, T, fused):
+    """X and Y as column slices of wider buffers (ld > width): every kernel of the dispatch (narrow, wide,
+    rotation pass, GEMM) must honour both strides and leave Y's padding columns alone."""
+    import torch
+    c_in, c_out = 1024, 16 * 21
+    say(f"padded rows T={T} fused={fused}")
+    li = pin.make_custom(5100 + T, T, c_in, c_out, n_outlier=3)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale) if fused else li.x.astype(np.float64)
+    y, allowed = _linear_ref(li, u)
+    w = make_w(P, li)
+    rot = make_rot(P, li) if fused else None
+    ws = P.Workspace(P.paro_workspace_bytes(rot, w, T))
+    xbuf = torch.full((T, c_in + 64), 3.0, dtype=torch.float16, device="cuda")
+    xbuf[:, 8:8 + c_in] = dev(li.x)
+    ybuf = torch.full((T, c_out + 24), 7.0, dtype=torch.float16, device="cuda")
+    xv, yv = xbuf[:, 8:8 + c_in], ybuf[:, 16:16 + c_out]
+    if fused:
+        P.paro_rotated_linear(rot, w, xv, ws, Y=yv)
+    else:
+        P.paro_w4a16_linear(w, xv, ws, Y=yv)
+    got = ybuf.cpu().numpy()
+    _assert_linear(got[:, 16:16 + c_out], y, allowed, f"padded rows T={T} fused={fused}")
+    assert (got[:, :16] == 7.0).all() and (got[:, 16 + c_out:] == 7.0).all()
+    assert (xbuf[:, :8] == 3.0).all() and (xbuf[:, 8:8 + c_in].cpu().numpy() == li.x).all()          # input untouched
+
+
 def test_long_strided_input_walked_in_runs(P):
     """Rows 4 MiB apart: 600 of them span more than the 31-bit offsets one GEMM launch addresses, so the
     call walks the tokens in runs of whole tiles (256 + 256 + 88 here); results as for any other input."""
