@@ -129,10 +129,19 @@ paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stre
  * (PARO_ERR_UNSUPPORTED otherwise): the kernels address runs of rows with 32-bit byte offsets.
  * T itself is not limited by that. */
 
-/* Bytes of workspace the two linear calls need for T tokens (rot may be NULL for the bare
- * linear).  The workspace must be zero-filled ONCE after allocation; every call leaves it
- * zero-filled again.  Two calls that share a workspace must not overlap in time. */
+/* Workspace of the linear calls (rot may be NULL for the bare linear), in two parts:
+ *   - the exchange part, the first paro_workspace_exchange_bytes() bytes of the buffer: partial
+ *     sums that blocks hand to each other.  It must be zero-filled ONCE after allocation; every
+ *     call leaves it zero-filled again;
+ *   - the scratch part, the LAST paro_workspace_bytes() - paro_workspace_exchange_bytes() bytes
+ *     of the buffer as given by ws_bytes (rounded down to 256): transformed activations when the
+ *     rotation runs as a pass of its own.  No requirement before a call, any contents after it.
+ * paro_workspace_bytes() is the sum: enough for a buffer that only serves calls of that one shape.
+ * A buffer shared by calls of several shapes must hold the largest exchange part plus the largest
+ * scratch part of all of them, so that no call's scratch reaches into another's exchange part;
+ * pass its full size as ws_bytes.  Calls that share a workspace must not overlap in time. */
 size_t paro_workspace_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T);
+size_t paro_workspace_exchange_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T);
 
 /* Xr[t, :] = R_K ... R_1 . S . X[t, :] for t < T, fp32 arithmetic, one fp16 rounding at the
  * store (Eq. 5, Eq. 8).  X, Xr: fp16 [T][ld*], ld >= c_in, rows 4-byte aligned (ld even).
@@ -161,7 +170,10 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
  * repacked and equal layer counts the parts run as ONE launch (results are bit-identical to the
  * separate calls); otherwise the call is the sequence of separate calls.  rots, weights, Y and
  * ldy are HOST arrays of n_parts entries (device pointers inside, as in the single call).
- * ws: device, zero-filled once, >= paro_workspace_bytes_multi(...) bytes, 256-byte aligned. */
+ * ws: device, >= paro_workspace_bytes_multi(...) bytes, 256-byte aligned, in the two parts
+ * described at paro_workspace_bytes() (exchange part: paro_workspace_exchange_bytes_multi()). */
+size_t paro_workspace_exchange_bytes_multi(int32_t n_parts, const paro_rotation *const *rots,
+                                           const paro_w4_weight *const *weights, int32_t T);
 size_t paro_workspace_bytes_multi(int32_t n_parts, const paro_rotation *const *rots,
                                   const paro_w4_weight *const *weights, int32_t T);
 paro_status paro_rotated_linear_multi(int32_t n_parts, const paro_rotation *const *rots,

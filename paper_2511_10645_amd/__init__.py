@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     paro_w4_unpack_zeros,
     paro_w4a16_linear,
     paro_workspace_bytes,
+    paro_workspace_exchange_bytes,
+    paro_workspace_exchange_bytes_multi,
     paro_workspace_bytes_multi,
     Workspace,
 )

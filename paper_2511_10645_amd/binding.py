@@ -64,6 +64,8 @@ def lib():
         L.paro_w4_repack.argtypes = [wp, vp, vp]
         L.paro_workspace_bytes.restype = sz
         L.paro_workspace_bytes.argtypes = [rp, wp, i32]
+        L.paro_workspace_exchange_bytes.restype = sz
+        L.paro_workspace_exchange_bytes.argtypes = [rp, wp, i32]
         L.paro_rotate_scale.argtypes = [rp, vp, i64, vp, i64, i32, vp]
         L.paro_w4a16_linear.argtypes = [wp, vp, i64, vp, i64, i32, vp, sz, vp]
         L.paro_rotated_linear.argtypes = [rp, wp, vp, i64, vp, i64, i32, vp, sz, vp]
@@ -75,6 +77,8 @@ def lib():
         L.paro_rotate_scale_quantize_mxfp4.argtypes = [rp, vp, i64, i32, vp, vp, vp]
         L.paro_workspace_bytes_multi.restype = sz
         L.paro_workspace_bytes_multi.argtypes = [i32, vp, vp, i32]
+        L.paro_workspace_exchange_bytes_multi.restype = sz
+        L.paro_workspace_exchange_bytes_multi.argtypes = [i32, vp, vp, i32]
         L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
         L.paro_tune_decode_waves.argtypes = [ctypes.c_int]
         L.paro_tune_decode_waves.restype = None
@@ -193,11 +197,23 @@ class W4Weight:
 
 
 class Workspace:
-    """Zero-filled device scratch for the linear calls (see paro_workspace_bytes)."""
+    """Zero-filled device workspace for the linear calls (see paro_workspace_bytes)."""
 
     def __init__(self, nbytes: int, device="cuda"):
         self.nbytes = int(nbytes)
         self.buf = torch.zeros(max(self.nbytes, 256), dtype=torch.uint8, device=device)
+
+    @classmethod
+    def shared(cls, calls, device="cuda"):
+        """One workspace for calls of several shapes: calls = [(rot or None, weight, T), ...].  Sized as the
+        largest exchange part plus the largest scratch part, so no call's scratch touches another's exchange part."""
+        ex = sc = 0
+        for rot, w, T in calls:
+            total, e = paro_workspace_bytes(rot, w, T), paro_workspace_exchange_bytes(rot, w, T)
+            ex, sc = max(ex, e), max(sc, total - e)
+        ws = cls(ex + sc, device)
+        ws.exchange_bytes = ex
+        return ws
 
 
 def paro_rotation_plan_build(rot: Rotation) -> None:
@@ -235,6 +251,10 @@ def paro_w4_quantize(rot: Rotation | None, W: torch.Tensor, group: int = 128) ->
 
 def paro_workspace_bytes(rot: Rotation | None, w: W4Weight, T: int) -> int:
     return lib().paro_workspace_bytes(rot.ref() if rot is not None else None, w.ref(), T)
+
+
+def paro_workspace_exchange_bytes(rot: Rotation | None, w: W4Weight, T: int) -> int:
+    return lib().paro_workspace_exchange_bytes(rot.ref() if rot is not None else None, w.ref(), T)
 
 
 def _rows(x: torch.Tensor):
@@ -298,6 +318,11 @@ def _ptr_array(objs):
 def paro_workspace_bytes_multi(rots, weights, T: int) -> int:
     assert len(rots) == len(weights)
     return lib().paro_workspace_bytes_multi(len(rots), _ptr_array(rots), _ptr_array(weights), T)
+
+
+def paro_workspace_exchange_bytes_multi(rots, weights, T: int) -> int:
+    assert len(rots) == len(weights)
+    return lib().paro_workspace_exchange_bytes_multi(len(rots), _ptr_array(rots), _ptr_array(weights), T)
 
 
 def paro_rotated_linear_multi(rots, weights, x: torch.Tensor, ws: Workspace, ys=None):

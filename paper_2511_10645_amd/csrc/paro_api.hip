@@ -61,9 +61,14 @@ paro_status check_io(const void *X, int64_t ldx, int width_x, const void *Y, int
     return PARO_OK;
 }
 
+// The exchange part (split-K partial sums; zero-filled between calls, every kernel that uses it
+// leaves it zero-filled) sits at the start of the caller's buffer, the scratch part (rotated
+// activations when the rotation is a separate pass; left in any state) at its END: a buffer that
+// holds the largest exchange part plus the largest scratch part of all calls that share it keeps
+// every call's scratch out of every other call's exchange part.
 struct WsLayout {
-    size_t decode_bytes;   // counters + split-K partial sums
-    size_t xr_offset;      // rotated activations (fp16 [T][c_in]) when the rotation is a separate pass
+    size_t exchange_bytes;
+    size_t scratch_bytes;
     size_t total;
 };
 
@@ -74,11 +79,17 @@ WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
         DecodeGeometry d = decode_geometry(w->c_in, w->c_out, T);
         size_t wide = decode_wide_partial_bytes(w->c_in, w->c_out, T);
         size_t part = d.partial_bytes > wide ? d.partial_bytes : wide;
-        L.decode_bytes = round_up(part, 256);
+        L.exchange_bytes = round_up(part, 256);
     }
-    L.xr_offset = L.decode_bytes;
-    L.total = L.decode_bytes + (rot ? round_up((size_t)T * w->c_in * 2, 256) : 0);
+    const bool fused = rot && fast_weight(w) && rot->plan && T <= kFuseMaxTokens;
+    L.scratch_bytes = (rot && !fused) ? round_up((size_t)T * w->c_in * 2, 256) : 0;
+    L.total = L.exchange_bytes + L.scratch_bytes;
     return L;
+}
+
+inline void *ws_scratch(void *ws, size_t ws_bytes, const WsLayout &L)
+{
+    return (char *)ws + (ws_bytes - L.scratch_bytes) / 256 * 256;
 }
 
 paro_status from_hip(hipError_t e) { return e == hipSuccess ? PARO_OK : PARO_ERR_HIP; }
@@ -240,6 +251,13 @@ size_t paro_workspace_bytes(const paro_rotation *rot, const paro_w4_weight *w, i
     return ws_layout(rot, w, T).total;
 }
 
+size_t paro_workspace_exchange_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T)
+{
+    if (check_weight(w, false) != PARO_OK || T <= 0) return 0;
+    if (rot && (check_rotation(rot) != PARO_OK || rot->c_in != w->c_in)) return 0;
+    return ws_layout(rot, w, T).exchange_bytes;
+}
+
 paro_status paro_rotate_scale(const paro_rotation *rot, const paro_half_t *X, int64_t ldx, paro_half_t *Xr,
                               int64_t ldxr, int32_t T, void *stream)
 {
@@ -285,7 +303,7 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
         return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
 
     // two passes: transform into the workspace, then the bare linear
-    paro_half_t *xr = (paro_half_t *)((char *)ws + L.xr_offset);
+    paro_half_t *xr = (paro_half_t *)ws_scratch(ws, ws_bytes, L);
     hipError_t e = rot->plan ? launch_rotate_planned(*rot, X, ldx, xr, w->c_in, T, s)
                              : launch_rotate_generic(*rot, X, ldx, xr, w->c_in, T, s);
     if (e != hipSuccess) return PARO_ERR_HIP;
@@ -343,20 +361,36 @@ static paro_status check_multi(int32_t n, const paro_rotation *const *rots, cons
     return PARO_OK;
 }
 
+static WsLayout ws_layout_multi(int32_t n_parts, const paro_rotation *const *rots, const paro_w4_weight *const *weights,
+                                int32_t T)
+{
+    WsLayout M{0, 0, 0};
+    for (int p = 0; p < n_parts; ++p) {
+        WsLayout one = ws_layout(rots[p], weights[p], T);
+        if (one.exchange_bytes > M.exchange_bytes) M.exchange_bytes = one.exchange_bytes;
+        if (one.scratch_bytes > M.scratch_bytes) M.scratch_bytes = one.scratch_bytes;
+    }
+    if (multi_one_launch(n_parts, rots, weights, T)) {
+        size_t m = round_up(paro::decode_multi_bytes(n_parts, weights, T), 256);
+        if (m > M.exchange_bytes) M.exchange_bytes = m;
+        M.scratch_bytes = 0;
+    }
+    M.total = M.exchange_bytes + M.scratch_bytes;
+    return M;
+}
+
 size_t paro_workspace_bytes_multi(int32_t n_parts, const paro_rotation *const *rots,
                                   const paro_w4_weight *const *weights, int32_t T)
 {
     if (check_multi(n_parts, rots, weights) != PARO_OK || T <= 0) return 0;
-    size_t need = 0;
-    for (int p = 0; p < n_parts; ++p) {
-        size_t one = ws_layout(rots[p], weights[p], T).total;
-        if (one > need) need = one;
-    }
-    if (multi_one_launch(n_parts, rots, weights, T)) {
-        size_t m = paro::decode_multi_bytes(n_parts, weights, T);
-        if (m > need) need = m;
-    }
-    return need;
+    return ws_layout_multi(n_parts, rots, weights, T).total;
+}
+
+size_t paro_workspace_exchange_bytes_multi(int32_t n_parts, const paro_rotation *const *rots,
+                                           const paro_w4_weight *const *weights, int32_t T)
+{
+    if (check_multi(n_parts, rots, weights) != PARO_OK || T <= 0) return 0;
+    return ws_layout_multi(n_parts, rots, weights, T).exchange_bytes;
 }
 
 paro_status paro_rotated_linear_multi(int32_t n_parts, const paro_rotation *const *rots,

@@ -198,3 +198,21 @@ def test_row_stride_limit():
     w = _w(packed=FAKE)
     assert L.paro_w4a16_linear(ctypes.byref(w), FAKE, big, FAKE, 8192, 1, None, 0, None) == E_UNSUP
     assert L.paro_rotate_scale_quantize_mxfp4(ctypes.byref(_rot(plan=FAKE)), FAKE, big, 1, FAKE, FAKE, None) == E_UNSUP
+
+
+def test_workspace_parts():
+    """Exchange part <= total; a fused call (T <= 4, planned, repacked) needs no scratch, a separate rotation pass
+    adds T * c_in * 2 bytes of it (rounded to 256)."""
+    L = paro.lib()
+    w = _w(c_in=2048, c_out=512, packed=FAKE)
+    r = _rot(c_in=2048, plan=FAKE)
+    for T in (1, 4, 5, 16, 300):
+        tot, ex = L.paro_workspace_bytes(ctypes.byref(r), ctypes.byref(w), T), L.paro_workspace_exchange_bytes(
+            ctypes.byref(r), ctypes.byref(w), T)
+        assert ex <= tot and ex % 256 == 0
+        assert tot - ex == (0 if T <= 4 else (T * 2048 * 2 + 255) // 256 * 256), (T, tot, ex)
+        assert L.paro_workspace_bytes(None, ctypes.byref(w), T) == L.paro_workspace_exchange_bytes(None, ctypes.byref(w), T)
+    r2 = _rot(c_in=2048)                                              # no plan: always a separate pass
+    assert L.paro_workspace_bytes(ctypes.byref(r2), ctypes.byref(w), 1) - L.paro_workspace_exchange_bytes(
+        ctypes.byref(r2), ctypes.byref(w), 1) == 4096
+    assert L.paro_workspace_exchange_bytes(ctypes.byref(_rot(c_in=512)), ctypes.byref(w), 1) == 0     # mismatch: 0

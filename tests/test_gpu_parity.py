@@ -253,6 +253,48 @@ def test_linear_with_padded_rows(P, T, fused):
     assert (xbuf[:, :8] == 3.0).all() and (xbuf[:, 8:8 + c_in].cpu().numpy() == li.x).all()          # input untouched
 
 
+def test_graph_replays_match_eager(P):
+    """The calls only enqueue kernels (no memset nodes, no allocation), so a captured sequence can be replayed:
+    every replay, with eager work in between, must reproduce the eager bits and leave the workspace zero-filled."""
+    import torch
+    say("graph replays")
+    li = pin.make_custom(77, 4, 2048, 16 * 37, n_outlier=3)
+    lp = pin.make_custom(78, 40, 2048, 16 * 37, n_outlier=3)
+    rot, w = make_rot(P, li), make_w(P, li)
+    ws = P.Workspace.shared([(rot, w, 1), (rot, w, 4), (None, w, 4), (rot, w, 40)])
+    x1, x4, x40 = dev(li.x[:1]), dev(li.x), dev(lp.x)
+    outs = [torch.zeros((t, w.c_out), dtype=torch.float16, device="cuda") for t in (1, 4, 4, 40)]
+
+    def sequence():
+        P.paro_rotated_linear(rot, w, x1, ws, Y=outs[0])         # narrow kernel, split-K exchange
+        P.paro_rotated_linear(rot, w, x4, ws, Y=outs[1])
+        P.paro_w4a16_linear(w, x4, ws, Y=outs[2])                # wide kernel
+        P.paro_rotated_linear(rot, w, x40, ws, Y=outs[3])        # rotation pass + GEMM or streamed passes
+
+    sequence()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            sequence()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), rep
+        assert int(ws.buf[:ws.exchange_bytes].sum().item()) == 0
+        sequence()                                               # eager work between replays
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), rep
+
+
 def test_long_strided_input_walked_in_runs(P):
     """Rows 4 MiB apart: 600 of them span more than the 31-bit offsets one GEMM launch addresses, so the
     call walks the tokens in runs of whole tiles (256 + 256 + 88 here); results as for any other input."""
@@ -382,8 +424,8 @@ def test_one_workspace_shared_by_many_calls(P):
         y_bare, allowed_bare = _linear_ref(li, li.x.astype(np.float64))
         cases.append(dict(T=T, li=li, rot=make_rot(P, li), w=make_w(P, li), x=dev(li.x),
                           y_rot=y_rot, a_rot=allowed_rot, y_bare=y_bare, a_bare=allowed_bare))
-    need = max(P.paro_workspace_bytes(c["rot"], c["w"], c["T"]) for c in cases)
-    ws = P.Workspace(need)
+    ws = P.Workspace.shared([(c["rot"], c["w"], c["T"]) for c in cases] + [(None, c["w"], c["T"]) for c in cases])
+    assert ws.exchange_bytes > 0 and ws.nbytes > ws.exchange_bytes
     rs = np.random.default_rng(77)
     for it in range(60):
         c = cases[int(rs.integers(len(cases)))]
@@ -393,6 +435,9 @@ def test_one_workspace_shared_by_many_calls(P):
         else:
             got = P.paro_w4a16_linear(c["w"], c["x"], ws).cpu().numpy()
             _assert_linear(got, c["y_bare"], c["a_bare"], f"seq {it} bare T={c['T']} C={c['li'].c_in}")
+        # the part every later call may use for its exchange is zero again, whatever ran (a separate
+        # rotation pass leaves its output in the scratch part at the end of the buffer only)
+        assert int(ws.buf[:ws.exchange_bytes].sum().item()) == 0, it
     torch.cuda.synchronize()
 
 
