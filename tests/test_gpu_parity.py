@@ -478,3 +478,33 @@ def test_selected_pairs_through_the_gpu_path(P):
     w = make_w(P, li)
     ws = P.Workspace(P.paro_workspace_bytes(rot, w, T))
     _assert_linear(P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy(), y, allowed, "selected pairs")
+
+
+def test_seeded_sweep_of_shapes(P):
+    """48 seeded draws of (T, c_in, c_out, layers, pairs per layer, scale order, bias, plan, repack): whatever
+    kernel the dispatch picks (narrow, wide with 1..n blocks per column, rotation pass, GEMM with ragged tiles,
+    interchange-layout fallback), the fused call and the bare call meet the linear gate."""
+    rs = np.random.default_rng(20251127)
+    for it in range(48):
+        T = int(rs.choice([1, 2, 3, 4, 5, 9, 16, 17, 31, 64, 130, 257]))
+        c_in = int(rs.choice([128, 384, 512, 1024, 1536, 2560, 4608, 7168]))
+        c_out = 16 * int(rs.integers(1, 70))
+        K = int(rs.choice([0, 1, 5, 8]))
+        ppl = int(rs.choice([1, 23, 64]))
+        order = int(rs.integers(2))
+        plan, packed, with_bias = bool(rs.integers(4)), bool(rs.integers(4)), bool(rs.integers(2))
+        packed = packed and c_in % 512 == 0                  # the repacked layout tiles K in slices of 4 groups
+        case = dict(it=it, T=T, c_in=c_in, c_out=c_out, K=K, ppl=ppl, order=order, plan=plan, packed=packed, bias=with_bias)
+        say(f"sweep {case}")
+        li = pin.make_custom(7000 + it, T, c_in, c_out, n_layers=K, pairs_per_layer=ppl, n_outlier=2)
+        bias = pin.make_bias(7000 + it, 3, c_out) if with_bias else None
+        u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale, scale_order=order)
+        y, allowed = _linear_ref(li, u, bias)
+        yb, allowed_b = _linear_ref(li, li.x.astype(np.float64), bias)
+        rot = make_rot(P, li, plan=plan, scale_order=order)
+        w = make_w(P, li, packed=packed, bias=bias)
+        ws = P.Workspace.shared([(rot, w, T), (None, w, T)])
+        x = dev(li.x)
+        _assert_linear(P.paro_rotated_linear(rot, w, x, ws).cpu().numpy(), y, allowed, f"sweep fused {case}")
+        _assert_linear(P.paro_w4a16_linear(w, x, ws).cpu().numpy(), yb, allowed_b, f"sweep bare {case}")
+        assert int(ws.buf[:ws.exchange_bytes].sum().item()) == 0, case
