@@ -12,7 +12,10 @@ void set_decode_target_waves(int blocks);
 
 namespace {
 
-constexpr int kFuseMaxTokens = 4;     // rotation runs inside the decode kernel up to this many tokens
+#ifndef PARO_FUSE_MAX_TOKENS
+#define PARO_FUSE_MAX_TOKENS 4
+#endif
+constexpr int kFuseMaxTokens = PARO_FUSE_MAX_TOKENS;     // rotation runs inside the decode kernel up to this many tokens
 #ifndef PARO_DECODE_MAX_TOKENS
 #define PARO_DECODE_MAX_TOKENS 16
 #endif
