@@ -135,7 +135,8 @@ paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stre
  *     call leaves it zero-filled again;
  *   - the scratch part, the LAST paro_workspace_bytes() - paro_workspace_exchange_bytes() bytes
  *     of the buffer as given by ws_bytes (rounded down to 256): transformed activations when the
- *     rotation runs as a pass of its own.  No requirement before a call, any contents after it.
+ *     rotation runs as a pass of its own, and fp32 partial tiles where the GEMM splits K (some
+ *     tens to hundreds of tokens).  No requirement before a call, any contents after it.
  * paro_workspace_bytes() is the sum: enough for a buffer that only serves calls of that one shape.
  * A buffer shared by calls of several shapes must hold the largest exchange part plus the largest
  * scratch part of all of them, so that no call's scratch reaches into another's exchange part;

@@ -30,6 +30,11 @@
 // weight panels through that XCD's L2.  With fewer than 8 token tiles the patch is narrower
 // in tokens and wider in outputs, so that no block id of a patch is left without work, and
 // with fewer than 256 tiles the patches shrink so that all 8 XCDs still get one.
+//
+// Split K.  Some tens to hundreds of tokens give only a handful of tiles, each walking all of K on
+// one compute unit.  Then K is cut into slices (blockIdx.y), as many as fit one round of blocks;
+// every slice stores its fp32 tile to scratch memory and a second kernel sums the slices in index
+// order, adds the bias and rounds once (deterministic; no atomics).
 #include "paro_internal.h"
 #include <type_traits>
 
@@ -69,6 +74,8 @@ struct GemmArgs {
     int T, C, N, G, S;          // S = G / 4 K-slices of the scales/zeros tiling
     int m_tiles, n_tiles;       // tiles of this launch
     int n_tile0;                // first 256-output tile of this launch
+    int k_split, k_steps;       // blockIdx.y walks K-steps [y k_steps, (y+1) k_steps); k_split > 1: fp32 partial tiles
+    float *partial;             //   [k_split][T][N] instead of Y, summed by gemm_splitk_reduce_kernel
     int patch_m, patch_n;       // token tiles x output tiles of the patch of blocks one XCD works on
     uint32_t m_lo, m_hi, k_lo, k_hi;   // 0x000F000F, 0x00F000F0, 0x64006400, 0x54005400: passed as arguments and
                                        // moved to VGPRs so that (u & mask) | magic becomes one v_and_or_b32
@@ -97,7 +104,8 @@ __host__ __device__ constexpr int staging_item(int k)
 
 // MI x NI: 32x32 MFMA tiles per wave (tokens x outputs); WM x WN: waves per block.
 // Block tile = (WM MI 32) tokens x (WN NI 32 = 256) outputs.
-template <int MI, int NI, int WM, int WN>
+// SPLITK: blockIdx.y selects a slice of K and the block stores fp32 partial tiles.
+template <int MI, int NI, int WM, int WN, bool SPLITK = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 {
     constexpr int THREADS = WM * WN * 64;
@@ -166,16 +174,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
     u32x4 areg[AL];
     u32x4 bw[PB];
     uint16_t bsc[PB], bzq[PB];      // widened where they are used: no ALU op (hence no wait) at the load
-    const int n_ks = a.C / kBK;
+    const int k_begin = SPLITK ? blockIdx.y * a.k_steps : 0;             // this block's K-steps (split K: a slice)
+    const int k_end = SPLITK ? min(a.C / kBK, k_begin + a.k_steps) : a.C / kBK;
     auto load_a = [&](int r, int ks) {
         areg[r] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)a_voff[r], ks * (kBK * 2), 0);
     };
-    auto load_b = [&](int p, int ks) {
+    auto load_b_into = [&](u32x4 &wv, uint16_t &sv, uint16_t &zv, int p, int ks) {
         const int g = ks >> 1, half = ks & 1;
-        bw[p] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)bw_voff[p], g * 1024 + half * 512, 0);
-        bsc[p] = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8) + (g & 3) * 2, 0);
-        bzq[p] = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
+        wv = __builtin_amdgcn_raw_buffer_load_b128(br, (int)bw_voff[p], g * 1024 + half * 512, 0);
+        sv = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8) + (g & 3) * 2, 0);
+        zv = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
     };
+    auto load_b = [&](int p, int ks) { load_b_into(bw[p], bsc[p], bzq[p], p, ks); };
     half2v nlo[PB], nhi[PB], s2[PB];
     auto deq_consts = [&](int p, int ks) {
         const int g = ks >> 1;
@@ -209,20 +219,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 
     // ---- prologue: K-step 0 into LDS buffer 0, K-step 1 into the registers -------------------
 #pragma unroll
-    for (int r = 0; r < AL; ++r) load_a(r, 0);
+    for (int r = 0; r < AL; ++r) load_a(r, k_begin);
 #pragma unroll
-    for (int p = 0; p < PB; ++p) load_b(p, 0);
+    for (int p = 0; p < PB; ++p) load_b(p, k_begin);
 #pragma unroll
     for (int r = 0; r < AL; ++r) *(u32x4 *)&As[a_lds + kARows * r * kLdsRow] = areg[r];
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
-        deq_consts(p, 0);
+        deq_consts(p, k_begin);
 #pragma unroll
         for (int w4 = 0; w4 < 4; ++w4) { deq_half(Bs, p, w4, 0); deq_half(Bs, p, w4, 1); }
     }
     {
         // same order as in the steady state, so that the loop's load counting is exact from the start
-        const int k1 = n_ks > 1 ? 1 : 0;
+        const int k1 = k_begin + 1 < k_end ? k_begin + 1 : k_begin;
         static_for<kItems>([&](auto KI) {
             constexpr int code = staging_item<ALP, PB>(KI);
             if constexpr (code >= 16 && code < 24) load_a(code - 16, k1);
@@ -243,12 +253,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 #pragma unroll
     for (int f = 0; f < MI + NI; ++f) read_frag(As, Bs, f, 0, 0);
 
-    for (int ks = 0; ks < n_ks; ++ks) {
-        const int buf = ks & 1;
+    for (int ks = k_begin; ks < k_end; ++ks) {
+        const int buf = (ks - k_begin) & 1;
         const _Float16 *Ac = As + buf * BM * kLdsRow, *Bc = Bs + buf * kBN * kLdsRow;
         _Float16 *An = As + (buf ^ 1) * BM * kLdsRow, *Bn = Bs + (buf ^ 1) * kBN * kLdsRow;
         const int ks_store = ks + 1;                                      // K-step held in the registers
-        const int ks_load = ks + 2 < n_ks ? ks + 2 : n_ks - 1;            // clamped: the surplus data is never used
+        const int ks_load = ks + 2 < k_end ? ks + 2 : k_end - 1;          // clamped: the surplus data is never used
         static_for<4>([&](auto PH) {
             constexpr int ph = PH;
             static_for<kSlots>([&](auto SL) {
@@ -282,8 +292,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
         });
     }
 
-    // ---- epilogue: + bias, fp16 store.  Lane (column fr, half fh) holds rows 8b + 4 fh + r. ------
-    const __amdgpu_buffer_rsrc_t yr = make_rsrc_g(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
+    // ---- epilogue.  Lane (column fr, half fh) holds rows 8b + 4 fh + r. --------------------------
+    if constexpr (SPLITK) {
+        // split K: this slice's fp32 sums; bias and rounding happen once, in the reduction
+        const __amdgpu_buffer_rsrc_t pr =
+            make_rsrc_g(a.partial + (size_t)blockIdx.y * a.T * a.N, (uint32_t)((size_t)a.T * a.N * 4));
+#pragma unroll
+        for (int jn = 0; jn < NI; ++jn) {
+            const int n = n0 + wn * NI * 32 + jn * 32 + fr;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * MI * 32 + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
+                    const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.N + n) * 4) : kOobG;
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][jn][v]), pr, (int)off, 0, 0);
+                }
+        }
+        return;
+    }
+    // + bias, fp16 store
+    const __amdgpu_buffer_rsrc_t yr = make_rsrc_g(a.Y, SPLITK ? 0u : (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
 #pragma unroll
     for (int jn = 0; jn < NI; ++jn) {
         const int n = n0 + wn * NI * 32 + jn * 32 + fr;
@@ -298,6 +327,73 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
                 __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
             }
     }
+}
+
+// Split K, second step: Y[t][n] = fp16( sum_k partial[k][t][n] + bias[n] ), slices added in index
+// order (deterministic).  One thread per 4 consecutive outputs of a token.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float *__restrict__ partial, int k_split, int T,
+                                                                 int N, const _Float16 *__restrict__ bias,
+                                                                 _Float16 *__restrict__ Y, int64_t ldy)
+{
+    const int n4 = N / 4;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)T * n4) return;
+    const int t = (int)(idx / n4), n = (int)(idx % n4) * 4;
+    const size_t slice = (size_t)T * N;
+    const float *p = partial + (size_t)t * N + n;
+    float4 sum = *(const float4 *)p;
+    for (int k = 1; k < k_split; ++k) {
+        const float4 v = *(const float4 *)(p + k * slice);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    if (bias) { sum.x += (float)bias[n]; sum.y += (float)bias[n + 1]; sum.z += (float)bias[n + 2]; sum.w += (float)bias[n + 3]; }
+    union { _Float16 h[4]; uint2 u; } o;
+    o.h[0] = (_Float16)sum.x; o.h[1] = (_Float16)sum.y; o.h[2] = (_Float16)sum.z; o.h[3] = (_Float16)sum.w;
+    *(uint2 *)(Y + (size_t)t * ldy + n) = o.u;
+}
+
+// Few token tiles and few output tiles leave most compute units without a block, each of the few
+// walking all of K.  Then K is cut into slices (grid.y), enough to fill the chip once with blocks
+// of at least 4 K-steps; the slices' fp32 tiles go to scratch memory and are summed afterwards.
+// Block slots of a launch over m_tiles x n_tiles tiles: the XCD patches are rounded up to whole
+// rounds of 8 (see the kernel's block numbering); slots without a tile exit at once.
+static void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, int &blocks)
+{
+    int pb = kPatchBlocks;
+    while (pb > 1 && (long)m_tiles * n_tiles < 8L * pb) pb >>= 1;
+    patch_m = 1;
+    while (patch_m * 2 <= pb && patch_m * 2 <= 8 && patch_m * 2 <= m_tiles) patch_m <<= 1;
+    patch_n = pb / patch_m;
+    const int m_patches = (m_tiles + patch_m - 1) / patch_m, n_patches = (n_tiles + patch_n - 1) / patch_n;
+    blocks = (m_patches * n_patches + 7) / 8 * 8 * pb;
+}
+
+struct GemmSplit { int k_split, k_steps; double est_us; };
+static GemmSplit choose_split(const paro_w4_weight &w, int T)
+{
+    const int n_ks = w.c_in / kBK;
+    const long tiles = (long)((T + 127) / 128) * ((w.c_out + kBN - 1) / kBN);     // 128-token tiles
+    GemmSplit best{1, n_ks, (double)n_ks * 0.95 * (double)((tiles + 255) / 256)};
+    if (T > 512 || tiles > 128 || n_ks < 8 || (size_t)T * w.c_out * 4 >= (1ull << 31)) return best;
+    // One round of blocks only (more than 256 slots was measured slower than fewer, longer blocks).
+    // Measured: ~5 us of launch, pipeline fill and partial-tile stores, ~1.2 us per K-step of these
+    // short blocks; the partial tiles are written and read once at ~4.5 TB/s; the reduction is one
+    // more launch (~2 us).
+    int pm, pn, slots;
+    gemm_patches((T + 127) / 128, (w.c_out + kBN - 1) / kBN, pm, pn, slots);
+    for (int ks = 2; ks <= n_ks / 4 && (long)slots * ks <= 256; ++ks) {
+        const int steps = (n_ks + ks - 1) / ks, split = (n_ks + steps - 1) / steps;
+        if (split != ks) continue;
+        const double us = 5.0 + steps * 1.2 + 2.0 + (double)ks * T * w.c_out * 8.0 / 4.5e6;
+        if (us < best.est_us) best = GemmSplit{ks, steps, us};
+    }
+    return best;
+}
+
+size_t gemm_scratch_bytes(const paro_w4_weight &w, int T)
+{
+    const GemmSplit g = choose_split(w, T);
+    return g.k_split > 1 ? (size_t)g.k_split * T * w.c_out * sizeof(float) : 0;
 }
 
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T)
@@ -318,40 +414,35 @@ double gemm_estimate_us(const paro_w4_weight &w, int T)
     const bool big = big_tiles >= 256;
     const long blocks = big ? big_tiles : (long)((T + 127) / 128) * n_tiles;
     const long rounds = (blocks + 255) / 256;
-    return (double)(w.c_in / kBK) * (double)rounds * (big ? 1.9 : 0.95);
+    if (!big) return choose_split(w, T).est_us;
+    return (double)(w.c_in / kBK) * (double)rounds * 1.9;
 }
 
 // output tiles [n_tile0, n_tile0 + n_count) x all token tiles
-template <int MI, int NI, int WM, int WN>
+template <int MI, int NI, int WM, int WN, bool SPLITK = false>
 static hipError_t launch_gemm_cfg(GemmArgs &a, int n_tile0, int n_count, hipStream_t s)
 {
     constexpr int BM = WM * MI * 32;
     a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = n_count; a.n_tile0 = n_tile0;
     // 32 blocks per patch when there is work for all 8 XCDs at that size; smaller patches
     // otherwise, so that a small grid is still spread over every XCD's L2 and memory channels
-    int pb = kPatchBlocks;
-    while (pb > 1 && (long)a.m_tiles * a.n_tiles < 8L * pb) pb >>= 1;
-    a.patch_m = 1;
-    while (a.patch_m * 2 <= pb && a.patch_m * 2 <= 8 && a.patch_m * 2 <= a.m_tiles) a.patch_m <<= 1;
-    a.patch_n = pb / a.patch_m;
-    const int m_patches = (a.m_tiles + a.patch_m - 1) / a.patch_m, n_patches = (a.n_tiles + a.patch_n - 1) / a.patch_n;
-    const int patches = m_patches * n_patches;
-    const int rounds = (patches + 7) / 8;                 // patches per XCD
-    const int blocks = rounds * 8 * pb;
+    int blocks;
+    gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
     const size_t lds = (size_t)2 * (BM + kBN) * kLdsRow * sizeof(_Float16);
     static std::atomic<uint64_t> attr_done{0};
     if (const int dev = once_pending(attr_done); dev >= 0) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel<MI, NI, WM, WN>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_w4a16_kernel<MI, NI, WM, WN, SPLITK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         once_done(attr_done, dev);
     }
-    hipLaunchKernelGGL((gemm_w4a16_kernel<MI, NI, WM, WN>), dim3(blocks), dim3(WM * WN * 64), lds, s, a);
+    hipLaunchKernelGGL((gemm_w4a16_kernel<MI, NI, WM, WN, SPLITK>), dim3(blocks, SPLITK ? a.k_split : 1),
+                       dim3(WM * WN * 64), lds, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T,
-                       hipStream_t s)
+                       void *scratch, size_t scratch_bytes, hipStream_t s)
 {
     GemmArgs a;
     a.blob = w.packed;
@@ -362,6 +453,7 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
+    a.k_split = 1; a.k_steps = w.c_in / kBK; a.partial = nullptr;
     // 256-token tiles unless they leave compute units idle.  Fewer than one full round of 256
     // blocks: 128-token tiles throughout.  Otherwise, when the last round would be at most half
     // full, that remainder (a range of output tiles) is launched separately with 128-token tiles:
@@ -375,7 +467,24 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 2, 2, 4>(a, n0, n, s); };
     auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 2, 2, 4>(a, n0, n, s); };
 #endif
-    if (big_tiles < 256) return small(0, n_all);
+    if (big_tiles < 256) {
+        const GemmSplit g = choose_split(w, T);
+        const size_t need = g.k_split > 1 ? (size_t)g.k_split * T * w.c_out * sizeof(float) : 0;
+        if (g.k_split > 1 && scratch && scratch_bytes >= need && ((uintptr_t)scratch % 16) == 0 && ldy % 4 == 0) {
+            a.k_split = g.k_split; a.k_steps = g.k_steps; a.partial = (float *)scratch;
+#ifdef PARO_GEMM_4WAVES
+            hipError_t e = launch_gemm_cfg<2, 4, 2, 2, true>(a, 0, n_all, s);
+#else
+            hipError_t e = launch_gemm_cfg<2, 2, 2, 4, true>(a, 0, n_all, s);
+#endif
+            if (e != hipSuccess) return e;
+            const long quads = (long)T * (w.c_out / 4);
+            hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                               (const float *)scratch, g.k_split, T, w.c_out, (const _Float16 *)w.bias, (_Float16 *)Y, ldy);
+            return hipGetLastError();
+        }
+        return small(0, n_all);
+    }
     const long full = big_tiles / 256, rem = big_tiles - full * 256;
 #ifndef PARO_GEMM_NO_TAIL_SPLIT
     if (rem > 0 && rem <= 128) {

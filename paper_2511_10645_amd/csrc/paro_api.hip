@@ -71,26 +71,30 @@ paro_status check_io(const void *X, int64_t ldx, int width_x, const void *Y, int
 // every call's scratch out of every other call's exchange part.
 struct WsLayout {
     size_t exchange_bytes;
+    size_t xr_bytes;        // scratch, first piece: rotated activations of a separate rotation pass
+    size_t gemm_bytes;      // scratch, second piece: split-K partial tiles of the GEMM at moderate token counts
     size_t scratch_bytes;
     size_t total;
 };
 
 WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
 {
-    WsLayout L{0, 0, 0};
+    WsLayout L{0, 0, 0, 0, 0};
     if (fast_weight(w)) {
         DecodeGeometry d = decode_geometry(w->c_in, w->c_out, T);
         size_t wide = decode_wide_partial_bytes(w->c_in, w->c_out, T);
         size_t part = d.partial_bytes > wide ? d.partial_bytes : wide;
         L.exchange_bytes = round_up(part, 256);
+        if (T > kDecodeMaxTokens) L.gemm_bytes = round_up(gemm_scratch_bytes(*w, T), 256);
     }
     const bool fused = rot && fast_weight(w) && rot->plan && T <= kFuseMaxTokens;
-    L.scratch_bytes = (rot && !fused) ? round_up((size_t)T * w->c_in * 2, 256) : 0;
+    L.xr_bytes = (rot && !fused) ? round_up((size_t)T * w->c_in * 2, 256) : 0;
+    L.scratch_bytes = L.xr_bytes + L.gemm_bytes;
     L.total = L.exchange_bytes + L.scratch_bytes;
     return L;
 }
 
-inline void *ws_scratch(void *ws, size_t ws_bytes, const WsLayout &L)
+inline char *ws_scratch(void *ws, size_t ws_bytes, const WsLayout &L)
 {
     return (char *)ws + (ws_bytes - L.scratch_bytes) / 256 * 256;
 }
@@ -99,7 +103,7 @@ paro_status from_hip(hipError_t e) { return e == hipSuccess ? PARO_OK : PARO_ERR
 
 // bare linear on (already transformed) activations, any T
 paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T,
-                       void *ws, hipStream_t s)
+                       void *ws, void *gemm_scratch, size_t gemm_bytes, hipStream_t s)
 {
     if (!fast_weight(w)) {
         if (!(w->qweight && w->scales && w->qzeros)) return PARO_ERR_UNSUPPORTED;
@@ -112,7 +116,7 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
         const int64_t chunk = (((int64_t)1 << 30) - 1) / ld / 256 * 256;
         for (int64_t t0 = 0; t0 < T; t0 += chunk) {
             const int tc = (int)(T - t0 < chunk ? T - t0 : chunk);
-            paro_status st = run_linear(w, X + t0 * ldx, ldx, Y + t0 * ldy, ldy, tc, ws, s);
+            paro_status st = run_linear(w, X + t0 * ldx, ldx, Y + t0 * ldy, ldy, tc, ws, gemm_scratch, gemm_bytes, s);
             if (st != PARO_OK) return st;
         }
         return PARO_OK;
@@ -123,7 +127,8 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
         // Measured per 16-token pass: ~5 us plus the tile bytes at ~6 TB/s.
         const double passes = (double)((T + kDecodeMaxTokens - 1) / kDecodeMaxTokens);
         const double stream_us = passes * (5.0 + (double)packed_tiles_bytes(w->c_in, w->c_out) / 6.0e6);
-        if (T >= 512 || gemm_estimate_us(*w, T) <= stream_us) return from_hip(launch_gemm(*w, X, ldx, Y, ldy, T, s));
+        if (T >= 512 || gemm_estimate_us(*w, T) <= stream_us)
+            return from_hip(launch_gemm(*w, X, ldx, Y, ldy, T, gemm_scratch, gemm_bytes, s));
     }
     for (int t0 = 0; t0 < T; t0 += 16) {
         int tc = T - t0 < 16 ? T - t0 : 16;
@@ -284,7 +289,8 @@ paro_status paro_w4a16_linear(const paro_w4_weight *w, const paro_half_t *X, int
     WsLayout L = ws_layout(nullptr, w, T);
     if (L.total && (!ws || ws_bytes < L.total)) return PARO_ERR_WORKSPACE;
     if (L.total && !aligned(ws, 256)) return PARO_ERR_ALIGN;
-    return run_linear(w, X, ldx, Y, ldy, T, ws, (hipStream_t)stream);
+    return run_linear(w, X, ldx, Y, ldy, T, ws, L.gemm_bytes ? ws_scratch(ws, ws_bytes, L) + L.xr_bytes : nullptr,
+                      L.gemm_bytes, (hipStream_t)stream);
 }
 
 paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X, int64_t ldx,
@@ -310,7 +316,8 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
     hipError_t e = rot->plan ? launch_rotate_planned(*rot, X, ldx, xr, w->c_in, T, s)
                              : launch_rotate_generic(*rot, X, ldx, xr, w->c_in, T, s);
     if (e != hipSuccess) return PARO_ERR_HIP;
-    return run_linear(w, xr, w->c_in, Y, ldy, T, ws, s);
+    return run_linear(w, xr, w->c_in, Y, ldy, T, ws, L.gemm_bytes ? ws_scratch(ws, ws_bytes, L) + L.xr_bytes : nullptr,
+                      L.gemm_bytes, s);
 }
 
 paro_status paro_w4_unpack_codes(const paro_w4_weight *w, uint8_t *codes, void *stream)

@@ -144,7 +144,10 @@ hipError_t launch_quantize_act_mxfp4(const paro_rotation &rot, const paro_half_t
 // Prefill-side linear (MFMA GEMM on the repacked weight), any T.
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T);
 double gemm_estimate_us(const paro_w4_weight &w, int T);
+// scratch: room for split-K partial tiles (gemm_scratch_bytes; any contents before and after);
+// without it the call runs unsplit.
+size_t gemm_scratch_bytes(const paro_w4_weight &w, int T);
 hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
-                       int T, hipStream_t s);
+                       int T, void *scratch, size_t scratch_bytes, hipStream_t s);
 
 }  // namespace paro

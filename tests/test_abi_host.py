@@ -210,8 +210,11 @@ def test_workspace_parts():
         tot, ex = L.paro_workspace_bytes(ctypes.byref(r), ctypes.byref(w), T), L.paro_workspace_exchange_bytes(
             ctypes.byref(r), ctypes.byref(w), T)
         assert ex <= tot and ex % 256 == 0
-        assert tot - ex == (0 if T <= 4 else (T * 2048 * 2 + 255) // 256 * 256), (T, tot, ex)
-        assert L.paro_workspace_bytes(None, ctypes.byref(w), T) == L.paro_workspace_exchange_bytes(None, ctypes.byref(w), T)
+        xr = 0 if T <= 4 else (T * 2048 * 2 + 255) // 256 * 256
+        bare = L.paro_workspace_bytes(None, ctypes.byref(w), T) - L.paro_workspace_exchange_bytes(None, ctypes.byref(w), T)
+        assert tot - ex == xr + bare, (T, tot, ex)
+        # the bare linear needs scratch only where the GEMM splits K (moderate token counts, few output tiles)
+        assert (bare == 0) if T <= 16 else (bare % 256 == 0 and bare >= 2 * T * 512 * 4), (T, bare)
     r2 = _rot(c_in=2048)                                              # no plan: always a separate pass
     assert L.paro_workspace_bytes(ctypes.byref(r2), ctypes.byref(w), 1) - L.paro_workspace_exchange_bytes(
         ctypes.byref(r2), ctypes.byref(w), 1) == 4096
