@@ -411,11 +411,8 @@ double gemm_estimate_us(const paro_w4_weight &w, int T)
 {
     const long n_tiles = (w.c_out + kBN - 1) / kBN;
     const long big_tiles = (long)((T + 255) / 256) * n_tiles;
-    const bool big = big_tiles >= 256;
-    const long blocks = big ? big_tiles : (long)((T + 127) / 128) * n_tiles;
-    const long rounds = (blocks + 255) / 256;
-    if (!big) return choose_split(w, T).est_us;
-    return (double)(w.c_in / kBK) * (double)rounds * 1.9;
+    if (big_tiles <= 128) return choose_split(w, T).est_us;          // 128-token tiles, K possibly split
+    return (double)(w.c_in / kBK) * (double)((big_tiles + 255) / 256) * 1.9;
 }
 
 // output tiles [n_tile0, n_tile0 + n_count) x all token tiles
@@ -454,8 +451,11 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
     a.k_split = 1; a.k_steps = w.c_in / kBK; a.partial = nullptr;
-    // 256-token tiles unless they leave compute units idle.  Fewer than one full round of 256
-    // blocks: 128-token tiles throughout.  Otherwise, when the last round would be at most half
+    // 256-token tiles unless they leave compute units idle.  Up to half a round of 256 blocks:
+    // 128-token tiles throughout (twice the blocks, still one round).  More than half a round but
+    // less than a full one: 256-token tiles all the same - two rounds of half-size tiles take as
+    // long on paper and longer in practice (measured 2048 x 4096 -> 6144, 192 tiles: 120 us against
+    // 136 us).  Otherwise, when the last round would be at most half
     // full, that remainder (a range of output tiles) is launched separately with 128-token tiles:
     // e.g. 896 tiles = 3 rounds of 256-token tiles + one round of 256 half-size tiles instead of 4.
     const int n_all = (w.c_out + kBN - 1) / kBN, m_big = (T + 255) / 256;
@@ -467,7 +467,7 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 2, 2, 4>(a, n0, n, s); };
     auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 2, 2, 4>(a, n0, n, s); };
 #endif
-    if (big_tiles < 256) {
+    if (big_tiles <= 128) {
         const GemmSplit g = choose_split(w, T);
         const size_t need = g.k_split > 1 ? (size_t)g.k_split * T * w.c_out * sizeof(float) : 0;
         if (g.k_split > 1 && scratch && scratch_bytes >= need && ((uintptr_t)scratch % 16) == 0 && ldy % 4 == 0) {
