@@ -162,7 +162,6 @@ __device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGrou
 // anything before writing.  The poll is bounded; a word that never fills is reported as NaN.
 __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, int tile_lo, int tile_hi, float *s_red)
 {
-#ifndef PARO_EXP_NO_FINALIZE
     const int THREADS = blockDim.x;                 // >= 256: kReducePerThread requests per thread cover a round
     const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
     const int outputs = a.T * width;
@@ -212,7 +211,6 @@ __device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, i
             a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
         }
     }
-#endif
 }
 
 // K: rotation layers fused in front.  SPLIT: more than one K-slice.  T1: exactly one token.

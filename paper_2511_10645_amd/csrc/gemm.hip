@@ -460,23 +460,14 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     // e.g. 896 tiles = 3 rounds of 256-token tiles + one round of 256 half-size tiles instead of 4.
     const int n_all = (w.c_out + kBN - 1) / kBN, m_big = (T + 255) / 256;
     const long big_tiles = (long)m_big * n_all;
-#ifdef PARO_GEMM_4WAVES
-    auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 4, 2, 2>(a, n0, n, s); };
-    auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 4, 2, 2>(a, n0, n, s); };
-#else
     auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 2, 2, 4>(a, n0, n, s); };
     auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 2, 2, 4>(a, n0, n, s); };
-#endif
     if (big_tiles <= 128) {
         const GemmSplit g = choose_split(w, T);
         const size_t need = g.k_split > 1 ? (size_t)g.k_split * T * w.c_out * sizeof(float) : 0;
         if (g.k_split > 1 && scratch && scratch_bytes >= need && ((uintptr_t)scratch % 16) == 0 && ldy % 4 == 0) {
             a.k_split = g.k_split; a.k_steps = g.k_steps; a.partial = (float *)scratch;
-#ifdef PARO_GEMM_4WAVES
-            hipError_t e = launch_gemm_cfg<2, 4, 2, 2, true>(a, 0, n_all, s);
-#else
             hipError_t e = launch_gemm_cfg<2, 2, 2, 4, true>(a, 0, n_all, s);
-#endif
             if (e != hipSuccess) return e;
             const long quads = (long)T * (w.c_out / 4);
             hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
@@ -486,7 +477,6 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
         return small(0, n_all);
     }
     const long full = big_tiles / 256, rem = big_tiles - full * 256;
-#ifndef PARO_GEMM_NO_TAIL_SPLIT
     if (rem > 0 && rem <= 128) {
         const int n_main = (int)(full * 256 / m_big);
         if (n_main > 0 && n_main < n_all) {
@@ -495,7 +485,6 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
             return small(n_main, n_all - n_main);
         }
     }
-#endif
     return big(0, n_all);
 }
 
