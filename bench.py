@@ -182,8 +182,9 @@ def main() -> int:
     achieved = dom["bytes"] / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.config),
-                "kernel": f"decode_kernel (fused, split-K, T={T}) on {dom['shape'].name} "
-                          f"{dom['shape'].c_in}->{dom['shape'].c_out}",
+                "kernel": (f"decode_kernel (fused, split-K, T={T})" if T <= 4 else
+                           f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})")
+                          + f" on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
                 "algorithmic_bytes_per_launch": dom["bytes"], "avg_launch_us": dom_us}
 
     # ---- prefill side (config 3: 2048 tokens): rotation pass + MFMA GEMM per linear ----------------
