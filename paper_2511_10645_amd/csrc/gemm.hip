@@ -75,7 +75,8 @@ struct GemmArgs {
     int m_tiles, n_tiles;       // tiles of this launch
     int n_tile0;                // first 256-output tile of this launch
     int k_split, k_steps;       // blockIdx.y walks K-steps [y k_steps, (y+1) k_steps); k_split > 1: fp32 partial tiles
-    float *partial;             //   [k_split][T][N] instead of Y, summed by gemm_splitk_reduce_kernel
+    float *partial;             //   [k_split][T][part_w] instead of Y (outputs part_n0 .. part_n0 + part_w), summed
+    int part_n0, part_w;        //   by gemm_splitk_reduce_kernel
     int patch_m, patch_n;       // token tiles x output tiles of the patch of blocks one XCD works on
     uint32_t m_lo, m_hi, k_lo, k_hi;   // 0x000F000F, 0x00F000F0, 0x64006400, 0x54005400: passed as arguments and
                                        // moved to VGPRs so that (u & mask) | magic becomes one v_and_or_b32
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
     if constexpr (SPLITK) {
         // split K: this slice's fp32 sums; bias and rounding happen once, in the reduction
         const __amdgpu_buffer_rsrc_t pr =
-            make_rsrc_g(a.partial + (size_t)blockIdx.y * a.T * a.N, (uint32_t)((size_t)a.T * a.N * 4));
+            make_rsrc_g(a.partial + (size_t)blockIdx.y * a.T * a.part_w, (uint32_t)((size_t)a.T * a.part_w * 4));
 #pragma unroll
         for (int jn = 0; jn < NI; ++jn) {
             const int n = n0 + wn * NI * 32 + jn * 32 + fr;
@@ -305,7 +306,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + wm * MI * 32 + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
-                    const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.N + n) * 4) : kOobG;
+                    const uint32_t off =
+                        (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.part_w + (n - a.part_n0)) * 4) : kOobG;
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][jn][v]), pr, (int)off, 0, 0);
                 }
         }
@@ -329,32 +331,32 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
     }
 }
 
-// Split K, second step: Y[t][n] = fp16( sum_k partial[k][t][n] + bias[n] ), slices added in index
-// order (deterministic).  One thread per 4 consecutive outputs of a token.
+// Split K, second step: Y[t][n0 + n] = fp16( sum_k partial[k][t][n] + bias[n0 + n] ) for n < width,
+// slices added in index order (deterministic).  One thread per 4 consecutive outputs of a token.
 __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float *__restrict__ partial, int k_split, int T,
-                                                                 int N, const _Float16 *__restrict__ bias,
+                                                                 int n0, int width, const _Float16 *__restrict__ bias,
                                                                  _Float16 *__restrict__ Y, int64_t ldy)
 {
-    const int n4 = N / 4;
+    const int n4 = width / 4;
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long)T * n4) return;
     const int t = (int)(idx / n4), n = (int)(idx % n4) * 4;
-    const size_t slice = (size_t)T * N;
-    const float *p = partial + (size_t)t * N + n;
+    const size_t slice = (size_t)T * width;
+    const float *p = partial + (size_t)t * width + n;
     float4 sum = *(const float4 *)p;
     for (int k = 1; k < k_split; ++k) {
         const float4 v = *(const float4 *)(p + k * slice);
         sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
     }
-    if (bias) { sum.x += (float)bias[n]; sum.y += (float)bias[n + 1]; sum.z += (float)bias[n + 2]; sum.w += (float)bias[n + 3]; }
+    if (bias) {
+        const _Float16 *b = bias + n0 + n;
+        sum.x += (float)b[0]; sum.y += (float)b[1]; sum.z += (float)b[2]; sum.w += (float)b[3];
+    }
     union { _Float16 h[4]; uint2 u; } o;
     o.h[0] = (_Float16)sum.x; o.h[1] = (_Float16)sum.y; o.h[2] = (_Float16)sum.z; o.h[3] = (_Float16)sum.w;
-    *(uint2 *)(Y + (size_t)t * ldy + n) = o.u;
+    *(uint2 *)(Y + (size_t)t * ldy + n0 + n) = o.u;
 }
 
-// Few token tiles and few output tiles leave most compute units without a block, each of the few
-// walking all of K.  Then K is cut into slices (grid.y), enough to fill the chip once with blocks
-// of at least 4 K-steps; the slices' fp32 tiles go to scratch memory and are summed afterwards.
 // Block slots of a launch over m_tiles x n_tiles tiles: the XCD patches are rounded up to whole
 // rounds of 8 (see the kernel's block numbering); slots without a tile exit at once.
 static void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, int &blocks)
@@ -368,33 +370,78 @@ static void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, i
     blocks = (m_patches * n_patches + 7) / 8 * 8 * pb;
 }
 
-struct GemmSplit { int k_split, k_steps; double est_us; };
-static GemmSplit choose_split(const paro_w4_weight &w, int T)
+// How a (weight, T) pair is launched.
+//   Tiles: 256 tokens x 256 outputs unless they leave compute units idle.  Up to half a round of
+//   256 blocks: 128-token tiles throughout (twice the blocks, still one round).  More than half a
+//   round but less than a full one: 256-token tiles all the same - two rounds of half-size tiles
+//   take as long on paper and longer in practice (2048 x 4096 -> 6144, 192 tiles: 120 us against
+//   136 us).  Otherwise, when the last round would be at most half full, that remainder (a range
+//   of output tiles, the "tail") is launched separately with 128-token tiles: e.g. 896 tiles =
+//   3 rounds of 256-token tiles + one round of 256 half-size tiles instead of 4.
+//   Split K: a launch of 128-token tiles that fills at most half of the block slots (the whole
+//   call at some tens to hundreds of tokens, or the tail) cuts K into slices over blockIdx.y, as
+//   many as fit one round of slots with at least 4 K-steps each; the slices' fp32 tiles go to
+//   scratch memory and are summed by a second kernel.  The number of slices minimises a measured
+//   cost model: ~0.95 us per K-step of a block in a long launch, ~5 us + 1.2 us per K-step for the
+//   short blocks of a whole-call split, partial tiles written and read at ~4.5 TB/s, ~2 us for the
+//   reduction launch.  (More than one round of slots was measured slower.)
+struct GemmPlan {
+    int n_all, m_big;
+    int n_main;              // output tiles [0, n_main) with 256-token tiles (0: none)
+    int n_small;             // output tiles [n_main, n_main + n_small) with 128-token tiles (0: none)
+    int k_split, k_steps;    // of the 128-token-tile launch
+    size_t scratch;          // bytes of partial tiles
+    double est_us;
+};
+
+static void plan_split(GemmPlan &p, int T, int n_ks, int width, double base_us, double fixed_us, double step_us)
 {
-    const int n_ks = w.c_in / kBK;
-    const long tiles = (long)((T + 127) / 128) * ((w.c_out + kBN - 1) / kBN);     // 128-token tiles
-    GemmSplit best{1, n_ks, (double)n_ks * 0.95 * (double)((tiles + 255) / 256)};
-    if (T > 512 || tiles > 128 || n_ks < 8 || (size_t)T * w.c_out * 4 >= (1ull << 31)) return best;
-    // One round of blocks only (more than 256 slots was measured slower than fewer, longer blocks).
-    // Measured: ~5 us of launch, pipeline fill and partial-tile stores, ~1.2 us per K-step of these
-    // short blocks; the partial tiles are written and read once at ~4.5 TB/s; the reduction is one
-    // more launch (~2 us).
+    p.k_split = 1; p.k_steps = n_ks; p.scratch = 0;
+    const int m_tiles = (T + 127) / 128;
+    if ((long)m_tiles * p.n_small > 128 || n_ks < 8 || (size_t)T * width * 4 >= (1ull << 31)) return;
     int pm, pn, slots;
-    gemm_patches((T + 127) / 128, (w.c_out + kBN - 1) / kBN, pm, pn, slots);
+    gemm_patches(m_tiles, p.n_small, pm, pn, slots);
+    double best = base_us;
     for (int ks = 2; ks <= n_ks / 4 && (long)slots * ks <= 256; ++ks) {
         const int steps = (n_ks + ks - 1) / ks, split = (n_ks + steps - 1) / steps;
         if (split != ks) continue;
-        const double us = 5.0 + steps * 1.2 + 2.0 + (double)ks * T * w.c_out * 8.0 / 4.5e6;
-        if (us < best.est_us) best = GemmSplit{ks, steps, us};
+        const double us = fixed_us + steps * step_us + 2.0 + (double)ks * T * width * 8.0 / 4.5e6;
+        if (us < best) { best = us; p.k_split = ks; p.k_steps = steps; }
     }
-    return best;
+    if (p.k_split > 1) { p.scratch = (size_t)p.k_split * T * width * sizeof(float); p.est_us += best - base_us; }
 }
 
-size_t gemm_scratch_bytes(const paro_w4_weight &w, int T)
+static GemmPlan plan_gemm(const paro_w4_weight &w, int T)
 {
-    const GemmSplit g = choose_split(w, T);
-    return g.k_split > 1 ? (size_t)g.k_split * T * w.c_out * sizeof(float) : 0;
+    GemmPlan p{};
+    const int n_ks = w.c_in / kBK;
+    p.n_all = (w.c_out + kBN - 1) / kBN; p.m_big = (T + 255) / 256;
+    const long big_tiles = (long)p.m_big * p.n_all;
+    if (big_tiles <= 128) {                                  // 128-token tiles throughout
+        p.n_main = 0; p.n_small = p.n_all;
+        const long tiles = (long)((T + 127) / 128) * p.n_all;
+        p.est_us = (double)n_ks * 0.95 * (double)((tiles + 255) / 256);
+        if (T <= 512) plan_split(p, T, n_ks, w.c_out, p.est_us, 5.0, 1.2);
+        else { p.k_split = 1; p.k_steps = n_ks; }
+        return p;
+    }
+    const long full = big_tiles / 256, rem = big_tiles - full * 256;
+    p.n_main = p.n_all; p.n_small = 0; p.k_split = 1; p.k_steps = n_ks;
+    p.est_us = (double)n_ks * 1.9 * (double)((big_tiles + 255) / 256);
+    if (rem > 0 && rem <= 128) {
+        const int n_main = (int)(full * 256 / p.m_big);
+        if (n_main > 0 && n_main < p.n_all) {
+            p.n_main = n_main; p.n_small = p.n_all - n_main;
+            const double tail_us = (double)n_ks * 0.95;      // one (partly filled) round of 128-token tiles
+            p.est_us = (double)n_ks * 1.9 * (double)full + tail_us;
+            const int width = w.c_out - n_main * kBN;
+            plan_split(p, T, n_ks, width, tail_us, 0.0, 0.95);
+        }
+    }
+    return p;
 }
+
+size_t gemm_scratch_bytes(const paro_w4_weight &w, int T) { return plan_gemm(w, T).scratch; }
 
 bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T)
 {
@@ -405,15 +452,8 @@ bool gemm_supported(const paro_w4_weight &w, int64_t ldx, int64_t ldy, int T)
 }
 
 // Rough duration of the GEMM in microseconds, for the choice between it and repeated passes of the
-// streaming decode kernel at moderate token counts.  A block walks c_in / 64 K-steps; measured
-// per K-step and round of blocks: ~0.95 us with 128-token tiles, ~1.9 us with 256-token tiles.
-double gemm_estimate_us(const paro_w4_weight &w, int T)
-{
-    const long n_tiles = (w.c_out + kBN - 1) / kBN;
-    const long big_tiles = (long)((T + 255) / 256) * n_tiles;
-    if (big_tiles <= 128) return choose_split(w, T).est_us;          // 128-token tiles, K possibly split
-    return (double)(w.c_in / kBK) * (double)((big_tiles + 255) / 256) * 1.9;
-}
+// streaming decode kernel at moderate token counts (see plan_gemm for the model).
+double gemm_estimate_us(const paro_w4_weight &w, int T) { return plan_gemm(w, T).est_us; }
 
 // output tiles [n_tile0, n_tile0 + n_count) x all token tiles
 template <int MI, int NI, int WM, int WN, bool SPLITK = false>
@@ -450,42 +490,22 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.S = a.G / kSliceGroups;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
-    a.k_split = 1; a.k_steps = w.c_in / kBK; a.partial = nullptr;
-    // 256-token tiles unless they leave compute units idle.  Up to half a round of 256 blocks:
-    // 128-token tiles throughout (twice the blocks, still one round).  More than half a round but
-    // less than a full one: 256-token tiles all the same - two rounds of half-size tiles take as
-    // long on paper and longer in practice (measured 2048 x 4096 -> 6144, 192 tiles: 120 us against
-    // 136 us).  Otherwise, when the last round would be at most half
-    // full, that remainder (a range of output tiles) is launched separately with 128-token tiles:
-    // e.g. 896 tiles = 3 rounds of 256-token tiles + one round of 256 half-size tiles instead of 4.
-    const int n_all = (w.c_out + kBN - 1) / kBN, m_big = (T + 255) / 256;
-    const long big_tiles = (long)m_big * n_all;
-    auto big = [&](int n0, int n) { return launch_gemm_cfg<4, 2, 2, 4>(a, n0, n, s); };
-    auto small = [&](int n0, int n) { return launch_gemm_cfg<2, 2, 2, 4>(a, n0, n, s); };
-    if (big_tiles <= 128) {
-        const GemmSplit g = choose_split(w, T);
-        const size_t need = g.k_split > 1 ? (size_t)g.k_split * T * w.c_out * sizeof(float) : 0;
-        if (g.k_split > 1 && scratch && scratch_bytes >= need && ((uintptr_t)scratch % 16) == 0 && ldy % 4 == 0) {
-            a.k_split = g.k_split; a.k_steps = g.k_steps; a.partial = (float *)scratch;
-            hipError_t e = launch_gemm_cfg<2, 2, 2, 4, true>(a, 0, n_all, s);
-            if (e != hipSuccess) return e;
-            const long quads = (long)T * (w.c_out / 4);
-            hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
-                               (const float *)scratch, g.k_split, T, w.c_out, (const _Float16 *)w.bias, (_Float16 *)Y, ldy);
-            return hipGetLastError();
-        }
-        return small(0, n_all);
+    a.k_split = 1; a.k_steps = w.c_in / kBK; a.partial = nullptr; a.part_n0 = 0; a.part_w = 0;
+    const GemmPlan p = plan_gemm(w, T);
+    if (p.n_main > 0) {
+        hipError_t e = launch_gemm_cfg<4, 2, 2, 4>(a, 0, p.n_main, s);
+        if (e != hipSuccess || p.n_small == 0) return e;
     }
-    const long full = big_tiles / 256, rem = big_tiles - full * 256;
-    if (rem > 0 && rem <= 128) {
-        const int n_main = (int)(full * 256 / m_big);
-        if (n_main > 0 && n_main < n_all) {
-            hipError_t e = big(0, n_main);
-            if (e != hipSuccess) return e;
-            return small(n_main, n_all - n_main);
-        }
-    }
-    return big(0, n_all);
+    const bool split = p.k_split > 1 && scratch && scratch_bytes >= p.scratch && ((uintptr_t)scratch % 16) == 0;
+    if (!split) return launch_gemm_cfg<2, 2, 2, 4>(a, p.n_main, p.n_small, s);
+    a.k_split = p.k_split; a.k_steps = p.k_steps; a.partial = (float *)scratch;
+    a.part_n0 = p.n_main * kBN; a.part_w = w.c_out - a.part_n0;
+    hipError_t e = launch_gemm_cfg<2, 2, 2, 4, true>(a, p.n_main, p.n_small, s);
+    if (e != hipSuccess) return e;
+    const long quads = (long)T * (a.part_w / 4);
+    hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                       (const float *)scratch, p.k_split, T, a.part_n0, a.part_w, (const _Float16 *)w.bias, (_Float16 *)Y, ldy);
+    return hipGetLastError();
 }
 
 }  // namespace paro
