@@ -3,7 +3,7 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input: the fused
 transform + INT4 linear (paro_rotated_linear) of each of the four linears of one 8B-class
-decoder layer (config 1 of the benchmark spec: batch-1 decode, hidden 4096, group 128, K = 8).
+decoder layer (config 1 of paro_inputs.CONFIGS: batch-1 decode, hidden 4096, group 128, K = 8).
 Inputs are resident in HBM before the timed region.  Decode streams every weight once per
 token, so consecutive steps use different copies of the layer's weights from a pool larger
 than the 256 MB Infinity Cache - as successive layers of a real model would.
