@@ -104,14 +104,15 @@ __host__ __device__ constexpr int staging_item(int k)
 }
 
 // MI x NI: 32x32 MFMA tiles per wave (tokens x outputs); WM x WN: waves per block.
-// Block tile = (WM MI 32) tokens x (WN NI 32 = 256) outputs.
+// Block tile = (WM MI 32) tokens x (WN NI 32 = 256 or 192) outputs.
 // SPLITK: blockIdx.y selects a slice of K and the block stores fp32 partial tiles.
 template <int MI, int NI, int WM, int WN, bool SPLITK = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 {
     constexpr int THREADS = WM * WN * 64;
     constexpr int BM = WM * MI * 32;
-    static_assert(WN * NI * 32 == kBN, "256 outputs per block");
+    constexpr int BN = WN * NI * 32;                       // outputs per block: 256, or 192 (the B tile is still staged as 256 rows)
+    static_assert(BN <= kBN && BN % 32 == 0, "at most 256 outputs per block");
     constexpr int AL = BM * 8 / THREADS;                   // 16-byte activation loads per thread and K-step
     constexpr int PB = 512 / THREADS;                      // 16-byte code loads per thread and K-step
     constexpr int ALP = AL / PB;
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
     const int pm = gp % m_patches, pn = gp / m_patches;
     const int mt = pm * a.patch_m + q % a.patch_m, ntile = pn * a.patch_n + q / a.patch_m;
     if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
-    const int m0 = mt * BM, n0 = (a.n_tile0 + ntile) * kBN;
+    const int m0 = mt * BM, n0 = (a.n_tile0 + ntile) * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         const int nt = n0 / kTileN + b_rt + kBTiles * p;
-        const bool ok = nt * kTileN < a.N;
+        const bool ok = nt * kTileN < a.N && (b_rt + kBTiles * p) * kTileN < BN;    // rows beyond a 192-wide tile: not fetched
         bw_voff[p] = ok ? ((uint32_t)nt * a.G * 64u + b_kq * 16 + b_n) * 16u : kOobG;
         const uint32_t sidx = (uint32_t)nt * a.S * kTileN + b_n;
         bs_voff[p] = ok ? a.scales_off + sidx * 8u : kOobG;
@@ -387,6 +388,7 @@ static void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, i
 //   reduction launch.  (More than one round of slots was measured slower.)
 struct GemmPlan {
     int n_all, m_big;
+    int n_192;               // > 0: the whole call as 256-token x 192-output tiles, this many across (see plan_gemm)
     int n_main;              // output tiles [0, n_main) with 256-token tiles (0: none)
     int n_small;             // output tiles [n_main, n_main + n_small) with 128-token tiles (0: none)
     int k_split, k_steps;    // of the 128-token-tile launch
@@ -428,6 +430,13 @@ static GemmPlan plan_gemm(const paro_w4_weight &w, int T)
     const long full = big_tiles / 256, rem = big_tiles - full * 256;
     p.n_main = p.n_all; p.n_small = 0; p.k_split = 1; p.k_steps = n_ks;
     p.est_us = (double)n_ks * 1.9 * (double)((big_tiles + 255) / 256);
+    // Less than one round of 256 x 256 tiles, but one round of 256 x 192 tiles: narrower tiles, every
+    // compute unit busy (2048 x 4096 -> 6144: 192 tiles become 256; measured 125 -> 100 us).
+    const int n_192 = (w.c_out + 191) / 192;
+    if (full == 0 && (long)p.m_big * n_192 <= 256 && (long)p.m_big * n_192 > big_tiles) {
+        p.n_192 = n_192; p.est_us = (double)n_ks * 1.9 * 0.8;
+        return p;
+    }
     if (rem > 0 && rem <= 128) {
         const int n_main = (int)(full * 256 / p.m_big);
         if (n_main > 0 && n_main < p.n_all) {
@@ -492,6 +501,7 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
     a.k_split = 1; a.k_steps = w.c_in / kBK; a.partial = nullptr; a.part_n0 = 0; a.part_w = 0;
     const GemmPlan p = plan_gemm(w, T);
+    if (p.n_192 > 0) return launch_gemm_cfg<2, 3, 4, 2>(a, 0, p.n_192, s);
     if (p.n_main > 0) {
         hipError_t e = launch_gemm_cfg<4, 2, 2, 4>(a, 0, p.n_main, s);
         if (e != hipSuccess || p.n_small == 0) return e;

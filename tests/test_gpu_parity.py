@@ -181,6 +181,7 @@ def _assert_linear(got16, y, allowed, note):
     dict(T=1, c_in=6144, c_out=16 * 37),        # 12 K-slices: the widest single-block reduction
     dict(T=5, c_in=6656, c_out=16 * 11),        # 13 K-slices: spread over two blocks of 7 waves, partials exchanged
     dict(T=16, c_in=5120, c_out=16 * 19),       # 10 K-slices, a full 16-token pass
+    dict(T=300, c_in=512, c_out=16 * 1037),     # GEMM with 256 x 192 tiles (130 tiles of 256 x 256 would leave half the chip idle), ragged both ways
 ])
 def test_bare_linear(P, packed, case):
     li = pin.make_custom(700 + case["T"], case["T"], case["c_in"], case["c_out"], n_outlier=3)
