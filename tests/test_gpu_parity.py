@@ -402,6 +402,13 @@ def test_config4_32b(P, linear, T):
     _full_config_case(P, 4, linear, T)
 
 
+@pytest.mark.parametrize("linear,T", [(0, 40), (1, 128), (2, 96), (3, 256), (3, 512)])
+def test_config1_shapes_between_decode_and_prefill(P, linear, T):
+    """Tens to hundreds of tokens on the 8B-class shapes: repeated streaming passes, or the GEMM with K split
+    over blockIdx.y and the separate reduction, whichever the call picks."""
+    _full_config_case(P, 1, linear, T)
+
+
 def test_config0_tiny_full(P):
     li = pin.make_linear(0, 0)
     u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
