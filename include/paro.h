@@ -82,6 +82,7 @@ typedef struct {
                                  kernels that read the interchange layout                      */
 } paro_w4_weight;
 
+/* major * 100 + minor; 110: two-part workspace (exchange part + scratch at the end of the buffer). */
 int paro_version(void);
 const char *paro_status_string(paro_status s);
 

@@ -142,7 +142,7 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
 
 extern "C" {
 
-int paro_version(void) { return 100; }
+int paro_version(void) { return 110; }
 
 const char *paro_status_string(paro_status s)
 {
