@@ -392,6 +392,7 @@ struct GemmPlan {
     int n_main;              // output tiles [0, n_main) with 256-token tiles (0: none)
     int n_small;             // output tiles [n_main, n_main + n_small) with 128-token tiles (0: none)
     int k_split, k_steps;    // of the 128-token-tile launch
+    int big_split, big_steps;// of the 256-token-tile launch (only without a 128-token-tile launch; 1: not split)
     size_t scratch;          // bytes of partial tiles
     double est_us;
 };
@@ -416,6 +417,7 @@ static void plan_split(GemmPlan &p, int T, int n_ks, int width, double base_us, 
 static GemmPlan plan_gemm(const paro_w4_weight &w, int T)
 {
     GemmPlan p{};
+    p.big_split = 1;
     const int n_ks = w.c_in / kBK;
     p.n_all = (w.c_out + kBN - 1) / kBN; p.m_big = (T + 255) / 256;
     const long big_tiles = (long)p.m_big * p.n_all;
@@ -425,6 +427,26 @@ static GemmPlan plan_gemm(const paro_w4_weight &w, int T)
         p.est_us = (double)n_ks * 0.95 * (double)((tiles + 255) / 256);
         if (T <= 512) plan_split(p, T, n_ks, w.c_out, p.est_us, 5.0, 1.2);
         else { p.k_split = 1; p.k_steps = n_ks; }
+        // Long K on few tiles (2048 x 14336 -> 4096): 256-token tiles with K cut so that they fill the
+        // round do more MFMA work per staged byte than one round of 128-token tiles.  Measured per
+        // K-step: ~1.1 us for the half-size tile in such launches, ~1.95 us for the full one; the
+        // partial tiles cost about their bytes at 9 TB/s (they overlap the tail of the main kernel).
+        // 254 -> 236 us on that shape; not worth it for K = 4096.
+        if (p.k_split == 1 && T > 512 && (size_t)T * w.c_out * 4 < (1ull << 31)) {
+            int pm, pn, slots;
+            gemm_patches(p.m_big, p.n_all, pm, pn, slots);
+            double best = (double)n_ks * 1.1 * (double)((tiles + 255) / 256);
+            for (int ks = 2; ks <= 4 && (long)slots * ks <= 256 && n_ks / ks >= 32; ++ks) {
+                const int steps = (n_ks + ks - 1) / ks;
+                if ((n_ks + steps - 1) / steps != ks) continue;
+                const double us = steps * 1.95 + 2.0 + (double)ks * T * w.c_out * 8.0 / 9.0e6;
+                if (us < best) { best = us; p.big_split = ks; p.big_steps = steps; }
+            }
+            if (p.big_split > 1) {
+                p.n_main = p.n_all; p.n_small = 0; p.est_us = best;
+                p.scratch = (size_t)p.big_split * T * w.c_out * sizeof(float);
+            }
+        }
         return p;
     }
     const long full = big_tiles / 256, rem = big_tiles - full * 256;
@@ -502,20 +524,30 @@ hipError_t launch_gemm(const paro_w4_weight &w, const paro_half_t *X, int64_t ld
     a.k_split = 1; a.k_steps = w.c_in / kBK; a.partial = nullptr; a.part_n0 = 0; a.part_w = 0;
     const GemmPlan p = plan_gemm(w, T);
     if (p.n_192 > 0) return launch_gemm_cfg<2, 3, 4, 2>(a, 0, p.n_192, s);
+    auto reduce = [&](int k_split) {
+        const long quads = (long)T * (a.part_w / 4);
+        hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                           (const float *)scratch, k_split, T, a.part_n0, a.part_w, (const _Float16 *)w.bias, (_Float16 *)Y, ldy);
+        return hipGetLastError();
+    };
+    const bool have_scratch = scratch && scratch_bytes >= p.scratch && ((uintptr_t)scratch % 16) == 0;
+    if (p.big_split > 1) {
+        if (have_scratch) {
+            a.k_split = p.big_split; a.k_steps = p.big_steps; a.partial = (float *)scratch; a.part_n0 = 0; a.part_w = w.c_out;
+            hipError_t e = launch_gemm_cfg<4, 2, 2, 4, true>(a, 0, p.n_all, s);
+            return e != hipSuccess ? e : reduce(p.big_split);
+        }
+        return launch_gemm_cfg<2, 2, 2, 4>(a, 0, p.n_all, s);      // no room for partial tiles: the unsplit choice
+    }
     if (p.n_main > 0) {
         hipError_t e = launch_gemm_cfg<4, 2, 2, 4>(a, 0, p.n_main, s);
         if (e != hipSuccess || p.n_small == 0) return e;
     }
-    const bool split = p.k_split > 1 && scratch && scratch_bytes >= p.scratch && ((uintptr_t)scratch % 16) == 0;
-    if (!split) return launch_gemm_cfg<2, 2, 2, 4>(a, p.n_main, p.n_small, s);
+    if (!(p.k_split > 1 && have_scratch)) return launch_gemm_cfg<2, 2, 2, 4>(a, p.n_main, p.n_small, s);
     a.k_split = p.k_split; a.k_steps = p.k_steps; a.partial = (float *)scratch;
     a.part_n0 = p.n_main * kBN; a.part_w = w.c_out - a.part_n0;
     hipError_t e = launch_gemm_cfg<2, 2, 2, 4, true>(a, p.n_main, p.n_small, s);
-    if (e != hipSuccess) return e;
-    const long quads = (long)T * (a.part_w / 4);
-    hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
-                       (const float *)scratch, p.k_split, T, a.part_n0, a.part_w, (const _Float16 *)w.bias, (_Float16 *)Y, ldy);
-    return hipGetLastError();
+    return e != hipSuccess ? e : reduce(p.k_split);
 }
 
 }  // namespace paro
