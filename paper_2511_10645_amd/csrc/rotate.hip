@@ -161,7 +161,7 @@ constexpr int kRotTU = 4;      // tokens in flight per wave
 
 // A wave owns one group and a run of tokens.  Global traffic is one coalesced 4-byte access per
 // lane, token and direction (a group row is 256 contiguous bytes); the permutation between
-// channel order and the plan's lane order goes through a wave-private LDS row (no block
+// channel order and the plan's lane order goes through a wave-private LDS buffer (no block
 // barrier: LDS operations of one wave execute in issue order).  The loads of the next batch of
 // tokens are issued before the current batch is rotated.  Rows are read completely before any of
 // them is written, so X and Xr may be the same buffer.
@@ -196,31 +196,48 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
 
     LanePlan<K> P;
     load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
-    _Float16(*st)[kGroup] = s_stage[wave];
+    // Staging layout: [channel][token of the batch], 4 fp16 = 8 bytes per channel, so that the
+    // gather of a lane's two channels and the scatter of its two results take one 8-byte LDS access
+    // each for all 4 tokens (the LDS pipe, shared by the CU's four SIMDs, is as loaded as the vector
+    // pipes in this kernel).  A lane's loads hold channels 2 lane and 2 lane + 1 of each token:
+    // transposed in registers to (4 tokens of channel 2 lane, 4 tokens of channel 2 lane + 1) =
+    // 16 contiguous bytes, and back on the way out.
+    static_assert(kRotTU == 4, "8 bytes per channel");
+    typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+    char *sp = (char *)s_stage[wave];                      // 128 channels x 8 bytes
+    auto lo_pair = [](uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); };
+    auto hi_pair = [](uint32_t x, uint32_t y) { return (x >> 16) | (y & 0xffff0000u); };
 
     for (int t = 0; t < n_tok; t += kRotTU) {
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) nxt[u] = __builtin_amdgcn_raw_buffer_load_b32(xr, v4 + (t + kRotTU + u) * row_x, 0, 0);
-#pragma unroll
-        for (int u = 0; u < kRotTU; ++u) *(uint32_t *)&st[u][2 * lane] = cur[u];
+        const u32x4v in = {lo_pair(cur[0], cur[1]), lo_pair(cur[2], cur[3]), hi_pair(cur[0], cur[1]), hi_pair(cur[2], cur[3])};
+        *(u32x4v *)(sp + lane * 16) = in;
         __builtin_amdgcn_wave_barrier();
+        const half4v ha = *(const half4v *)(sp + P.in_a * 8), hb = *(const half4v *)(sp + P.in_b * 8);
         float a[kRotTU], b[kRotTU];
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) {
-            a[u] = (float)st[u][P.in_a] * P.sia;
-            b[u] = (float)st[u][P.in_b] * P.sib;
+            a[u] = (float)ha[u] * P.sia;
+            b[u] = (float)hb[u] * P.sib;
         }
         rotate_layers<K, kRotTU>(P, a, b);
         __builtin_amdgcn_wave_barrier();
+        half4v oa, ob;
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) {
-            st[u][P.out_a] = (_Float16)(a[u] * P.soa);
-            st[u][P.out_b] = (_Float16)(b[u] * P.sob);
+            oa[u] = (_Float16)(a[u] * P.soa);
+            ob[u] = (_Float16)(b[u] * P.sob);
         }
+        *(half4v *)(sp + P.out_a * 8) = oa;
+        *(half4v *)(sp + P.out_b * 8) = ob;
         __builtin_amdgcn_wave_barrier();
+        const u32x4v out = *(const u32x4v *)(sp + lane * 16);
+        const uint32_t o[kRotTU] = {lo_pair(out[0], out[2]), hi_pair(out[0], out[2]), lo_pair(out[1], out[3]), hi_pair(out[1], out[3])};
 #pragma unroll
-        for (int u = 0; u < kRotTU; ++u)
-            __builtin_amdgcn_raw_buffer_store_b32(*(const uint32_t *)&st[u][2 * lane], yr, v4 + (t + u) * row_y, 0, 0);
+        for (int u = 0; u < kRotTU; ++u) __builtin_amdgcn_raw_buffer_store_b32(o[u], yr, v4 + (t + u) * row_y, 0, 0);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) cur[u] = nxt[u];
