@@ -175,26 +175,34 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 
     u32x4 areg[AL];
     u32x4 bw[PB];
-    uint16_t bsc[PB], bzq[PB];      // widened where they are used: no ALU op (hence no wait) at the load
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 bsc[PB];                  // the 4 fp16 group scales of the thread's row in the current 512-channel slice
+    uint16_t bzq[PB];               // its 4 zero points; widened where it is used: no ALU op (hence no wait) at the load
     const int k_begin = SPLITK ? blockIdx.y * a.k_steps : 0;             // this block's K-steps (split K: a slice)
     const int k_end = SPLITK ? min(a.C / kBK, k_begin + a.k_steps) : a.C / kBK;
     auto load_a = [&](int r, int ks) {
         areg[r] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)a_voff[r], ks * (kBK * 2), 0);
     };
-    auto load_b_into = [&](u32x4 &wv, uint16_t &sv, uint16_t &zv, int p, int ks) {
+    // Codes of K-step ks; scales and zero points only where a new 512-channel slice (8 K-steps)
+    // begins - they are laid out 4 groups together, and a thread keeps its row for the whole loop.
+    // The branch is uniform; the registers of the old slice are free by then (the refill of a load
+    // comes after the last dequantisation that uses it).
+    auto load_b = [&](int p, int ks, bool first = false) {
         const int g = ks >> 1, half = ks & 1;
-        wv = __builtin_amdgcn_raw_buffer_load_b128(br, (int)bw_voff[p], g * 1024 + half * 512, 0);
-        sv = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8) + (g & 3) * 2, 0);
-        zv = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
+        bw[p] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)bw_voff[p], g * 1024 + half * 512, 0);
+        if (first || (ks & 7) == 0) {
+            bsc[p] = __builtin_amdgcn_raw_buffer_load_b64(br, (int)bs_voff[p], (g >> 2) * (kTileN * 8), 0);
+            bzq[p] = __builtin_amdgcn_raw_buffer_load_b16(br, (int)bz_voff[p], (g >> 2) * (kTileN * 2), 0);
+        }
     };
-    auto load_b = [&](int p, int ks) { load_b_into(bw[p], bsc[p], bzq[p], p, ks); };
     half2v nlo[PB], nhi[PB], s2[PB];
     auto deq_consts = [&](int p, int ks) {
         const int g = ks >> 1;
         const uint32_t z = ((uint32_t)bzq[p] >> (4 * (g & 3))) & 15u;
         nlo[p] = g_as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
         nhi[p] = g_as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
-        s2[p] = g_as_h2((uint32_t)bsc[p] * 0x00010001u);
+        const uint32_t sc = ((g & 2) ? bsc[p][1] : bsc[p][0]) >> (16 * (g & 1));
+        s2[p] = g_as_h2((sc & 0xffffu) * 0x00010001u);
     };
     // half h of word w4 of load p -> 4 fp16 weights; the second half stores the word's 8 weights
     auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4a16_kernel(GemmArgs a)
 #pragma unroll
     for (int r = 0; r < AL; ++r) load_a(r, k_begin);
 #pragma unroll
-    for (int p = 0; p < PB; ++p) load_b(p, k_begin);
+    for (int p = 0; p < PB; ++p) load_b(p, k_begin, true);
 #pragma unroll
     for (int r = 0; r < AL; ++r) *(u32x4 *)&As[a_lds + kARows * r * kLdsRow] = areg[r];
 #pragma unroll
