@@ -402,7 +402,10 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
     d.ks = G / kSliceGroups;
     // measured: with many K-slices (few tiles per slice and block) one 8-wave block per CU beats
     // two 4-wave blocks (14336 -> 4096, one token: 10.4 against 11.2 us); single launches only
-    d.waves = (T == 1 && d.ks >= 16 && target_blocks == 0 && g_decode_target_blocks == 0) ? 2 * kDecWaves : kDecWaves;
+    // ... and so does, by a little, a long stream whose 8-wave blocks still fit one round
+    // (4096 -> 28672: 14.65 against 14.9 us); the small linears are faster with 4 waves
+    const bool many_slices = d.ks >= 16, big = packed_tiles_bytes(c_in, c_out) >= (24u << 20);
+    d.waves = (T == 1 && (many_slices || big) && target_blocks == 0 && g_decode_target_blocks == 0) ? 2 * kDecWaves : kDecWaves;
     // measured on MI355X: one 4-wave block per CU for the small linears (the prologue is repeated
     // less often), two per CU once the weight stream exceeds ~24 MB
     int target = target_blocks > 0 ? target_blocks : g_decode_target_blocks;
