@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # `bench.py --pmc-probe`, scaled by the same counters on a 256 MiB copy (profiles/ has the runs)
-TRAFFIC_BYTES_PER_LAUNCH = {1: 66_170_000}
+TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000}
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
 
 
