@@ -50,11 +50,11 @@ def main() -> int:
     ap.add_argument("--pool-mb", type=int, default=1200, help="minimum total size of the weight-copy pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
-    ap.add_argument("--decode-waves", type=int, default=0, help="tuning knob (0 = library default)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (config 3) side measurement")
     ap.add_argument("--pmc-probe", action="store_true",
-                    help="for rocprofv3 --pmc runs: 3 plain 256 MiB device copies, then 3 launches of the dominant "
-                         "fused kernel on distinct weight copies; prints nothing else")
+                    help="for rocprofv3 --pmc runs: 3 plain 256 MiB device copies, then on the dominant linear 3 fused "
+                         "launches, 3 bare launches and 3 pure-read launches over the same bytes, each on distinct "
+                         "weight copies; prints nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it", file=sys.stderr)
@@ -69,8 +69,6 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     paro.lib()
-    if args.decode_waves:
-        paro.paro_tune_decode_waves(args.decode_waves)
     cfg = pin.CONFIGS[args.config]
     T = cfg.tokens[0]
     dev = "cuda"
@@ -156,6 +154,11 @@ def main() -> int:
         k = lin.index(dom)
         for i in range(3):
             step(i, which=k)
+        for i in range(3, 6):
+            step(i, which=k, bare=True)
+        for i in range(6, 9):
+            c = dom["copies"][i % dom["n_copies"]]
+            paro.paro_diag_read_stream(c.packed, c.packed.numel() // 16 * 16)
         torch.cuda.synchronize()
         return 0
 

@@ -131,17 +131,32 @@ paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stre
  * T itself is not limited by that. */
 
 /* Workspace of the linear calls (rot may be NULL for the bare linear), in two parts:
- *   - the exchange part, the first paro_workspace_exchange_bytes() bytes of the buffer: partial
- *     sums that blocks hand to each other.  It must be zero-filled ONCE after allocation; every
- *     call leaves it zero-filled again;
+ *   - the exchange part, the first paro_workspace_exchange_bytes() bytes of the buffer: what blocks
+ *     of one launch hand to each other.  It must be zero-filled ONCE after allocation and is then
+ *     kept consistent by the calls themselves.  Its layout is the same for every call, so calls
+ *     of any shapes may share it:
+ *        bytes [0, 256)   header.  Bytes 8..11 (paro_workspace_error_offset()) hold an error
+ *                         word: it stays 0 unless a bounded wait between blocks of a launch ran
+ *                         out (the outputs that depended on it are then NaN);
+ *        from paro_workspace_partials_offset() on: fp32 partial sums of split-K launches; every
+ *                         word is reset by its reader, so this range is all zero again after
+ *                         every call.
+ *     The blocks that exchange data must be resident at the same time: do not run other long
+ *     kernels concurrently with these calls.  After a non-zero error word (or after a call that
+ *     was cancelled or faulted) zero-fill the exchange part again before the next call.
  *   - the scratch part, the LAST paro_workspace_bytes() - paro_workspace_exchange_bytes() bytes
  *     of the buffer as given by ws_bytes (rounded down to 256): transformed activations when the
- *     rotation runs as a pass of its own, and fp32 partial tiles where the GEMM splits K (some
- *     tens to hundreds of tokens).  No requirement before a call, any contents after it.
+ *     rotation runs as a pass of its own (T > 4, or no plan / no repacked weight), and fp32
+ *     partial tiles where the GEMM splits K (some tens to hundreds of tokens).  No requirement
+ *     before a call, any contents after it.
  * paro_workspace_bytes() is the sum: enough for a buffer that only serves calls of that one shape.
  * A buffer shared by calls of several shapes must hold the largest exchange part plus the largest
  * scratch part of all of them, so that no call's scratch reaches into another's exchange part;
- * pass its full size as ws_bytes.  Calls that share a workspace must not overlap in time. */
+ * pass its full size as ws_bytes.  Calls that share a workspace must not overlap in time.
+ * The bare linear needs no workspace (0 bytes, ws may be NULL) where it neither splits K between
+ * blocks nor runs the GEMM's split. */
+size_t paro_workspace_error_offset(void);
+size_t paro_workspace_partials_offset(void);
 size_t paro_workspace_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T);
 size_t paro_workspace_exchange_bytes(const paro_rotation *rot, const paro_w4_weight *w, int32_t T);
 
@@ -234,11 +249,21 @@ paro_status paro_w4_unpack_zeros(const paro_w4_weight *w, uint8_t *zeros, void *
 /* W[n][c] = fp16( (q - z) * s ), exact product rounded once to nearest-even. */
 paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *stream);
 
-/* Diagnostics ---------------------------------------------------------------------------- */
+/* Diagnostics: measured ceilings of the machine (benchmark only; not part of the method) ------
+ * A roofline fraction against the nominal peaks (8 TB/s, 2.5 PFLOP/s) says little unless one
+ * knows what a kernel that does nothing else reaches on the same chip at the same size. */
 
-/* Tuning knob for experiments: target number of wavefronts of a decode launch (<= 0 restores
- * the default).  Process-wide and not thread-safe; results do not depend on it. */
-void paro_tune_decode_waves(int waves);
+/* Pure read: every lane reads 16 bytes per step (non-temporal, four loads in flight), nothing is
+ * written.  src: device, 16-byte aligned, `bytes` readable; sink: device uint32 or NULL (written
+ * only if the xor of all words equals one magic value); blocks of 256 threads. */
+paro_status paro_diag_read_stream(const void *src, size_t bytes, void *sink, int32_t blocks, void *stream);
+
+/* Pure fp16 MFMA issue: every wave runs iters x 16 independent 32x32x16 MFMAs on register
+ * operands (constant, or pseudo-random per lane when random_operands != 0).  out: device floats,
+ * blocks * 256 of them.  paro_diag_mfma_f16_flops() = floating-point operations of such a launch. */
+paro_status paro_diag_mfma_f16(void *out, size_t out_bytes, int32_t blocks, int32_t iters,
+                               int32_t random_operands, void *stream);
+double paro_diag_mfma_f16_flops(int32_t blocks, int32_t iters);
 
 #ifdef __cplusplus
 }

@@ -205,13 +205,13 @@ int oracle_weight_transform(const uint16_t *w16, int64_t ldw, int32_t N, int32_t
 
 /*
  * Eq. 1 with b = 4, one (s, z) per `group` consecutive input channels of one output row:
- *      s = (max - min) / 15,   z = -round(min / s),   q = clamp(round(w / s) + z, 0, 15).
+ *      s = (max - min) / 15,   z = -round(min / s),   q = clamp(round(w / s) + z, 0, 15),
+ * written out in fp64 exactly as printed.  The one step that is not fp64 is marked below: the
+ * scale is STORED as fp16 (the weight format of Section 2.1 as used here keeps one fp16 scale
+ * per group), and z and q are computed with the stored value, so that (q - z) * s reproduces w
+ * to within s/2 wherever nothing was clamped.
  * Readings (the paper gives the formula only):
- *   - the decisions that produce integers are taken in fp32 on the fp32-rounded input (the
- *     paper names no precision; this is the precision of the GPU quantiser), division and
- *     round-half-to-even (rintf) as written;
- *   - the scale is stored as fp16, and z and q are computed with the STORED value, so that
- *     (q - z) * s reproduces w to within s/2 wherever nothing was clamped;
+ *   - round() is round-half-to-even (rint);
  *   - s has the floor 2^-14 (smallest normal fp16), which also covers constant groups;
  *   - z is an INT4 value: clamped to 0..15.
  * codes: [N][C] bytes; scales16: [G][N] fp16 bits; zeros: [G][N] bytes.
@@ -224,25 +224,24 @@ void oracle_rtn_quantize(const double *wt, int64_t ldwt, int32_t N, int32_t C, i
     for (int32_t n = 0; n < N; ++n)
         for (int32_t g = 0; g < G; ++g) {
             const double *wg = wt + (int64_t)n * ldwt + (int64_t)g * group;
-            float mn = (float)wg[0], mx = (float)wg[0];
+            double mn = wg[0], mx = wg[0];
             for (int32_t c = 1; c < group; ++c) {
-                float v = (float)wg[c];
-                if (v < mn) mn = v;
-                if (v > mx) mx = v;
+                if (wg[c] < mn) mn = wg[c];
+                if (wg[c] > mx) mx = wg[c];
             }
-            float s32 = (mx - mn) / 15.0f;
-            if (!(s32 >= 6.103515625e-05f)) s32 = 6.103515625e-05f;
-            uint16_t sb = oracle_f64_to_fp16((double)s32);
-            float s = (float)oracle_fp16_to_f64(sb);
-            float zf = -rintf(mn / s);
-            if (zf < 0.0f) zf = 0.0f;
-            if (zf > 15.0f) zf = 15.0f;
+            double s_exact = (mx - mn) / 15.0;
+            if (!(s_exact >= 6.103515625e-05)) s_exact = 6.103515625e-05;
+            uint16_t sb = oracle_f64_to_fp16(s_exact);      /* <- the single rounding: the stored fp16 scale */
+            double s = oracle_fp16_to_f64(sb);
+            double z = -rint(mn / s);
+            if (z < 0.0) z = 0.0;
+            if (z > 15.0) z = 15.0;
             scales16[(int64_t)g * N + n] = sb;
-            zeros[(int64_t)g * N + n] = (uint8_t)zf;
+            zeros[(int64_t)g * N + n] = (uint8_t)z;
             for (int32_t c = 0; c < group; ++c) {
-                float q = rintf((float)wg[c] / s) + zf;
-                if (q < 0.0f) q = 0.0f;
-                if (q > 15.0f) q = 15.0f;
+                double q = rint(wg[c] / s) + z;
+                if (q < 0.0) q = 0.0;
+                if (q > 15.0) q = 15.0;
                 codes[(int64_t)n * C + (int64_t)g * group + c] = (uint8_t)q;
             }
         }
@@ -255,8 +254,9 @@ void oracle_rtn_quantize(const double *wt, int64_t ldwt, int32_t N, int32_t C, i
  *      shared_exp = floor(log2(max |V_i|)) - 2          (2 = largest E2M1 exponent), >= -127
  *      code_i     = E2M1( V_i / 2^shared_exp ), round to nearest, ties to even, saturating at 6
  * E2M1 magnitudes by code 0..7: 0, 0.5, 1, 1.5, 2, 3, 4, 6; bit 3 is the sign.  An all-zero
- * block gets the smallest scale (byte 0) and zero codes.  Input rows are fp64 and are rounded to
- * fp32 first (the precision the GPU holds them in); everything after that is exact.
+ * block gets the smallest scale (byte 0) and zero codes.  Input rows are fp64; scaling by a power of
+ * two and the comparisons against the eight magnitudes are exact in fp64, so nothing is rounded
+ * before the code is chosen.
  * codes: [T][C] bytes (0..15); scales: [T][C/32] bytes (shared_exp + 127).
  */
 void oracle_mxfp4_quantize(const double *u, int64_t ldu, int32_t T, int32_t C, uint8_t *codes, uint8_t *scales)
@@ -268,7 +268,7 @@ void oracle_mxfp4_quantize(const double *u, int64_t ldu, int32_t T, int32_t C, u
             const double *v = u + (int64_t)t * ldu + (int64_t)b * 32;
             double amax = 0.0;
             for (int i = 0; i < 32; ++i) {
-                double a = fabs((double)(float)v[i]);
+                double a = fabs(v[i]);
                 if (a > amax) amax = a;
             }
             int shared = -127;
@@ -280,7 +280,7 @@ void oracle_mxfp4_quantize(const double *u, int64_t ldu, int32_t T, int32_t C, u
             }
             scales[(int64_t)t * (C / 32) + b] = (uint8_t)(shared + 127);
             for (int i = 0; i < 32; ++i) {
-                double r = ldexp((double)(float)v[i], -shared);
+                double r = ldexp(v[i], -shared);
                 double a = fabs(r);
                 int code = 7;                        /* saturate */
                 if (a <= 6.0) {

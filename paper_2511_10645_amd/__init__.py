@@ -6,6 +6,8 @@ for device memory and streams.  There is no CPU fallback: a missing library is a
 """
 from .binding import (  # noqa: F401
     ParoError,
+    paro_diag_mfma_f16,
+    paro_diag_read_stream,
     Rotation,
     W4Weight,
     lib,
@@ -18,7 +20,6 @@ from .binding import (  # noqa: F401
     paro_rotation_plan_build,
     paro_select_pairs_host,
     paro_status_string,
-    paro_tune_decode_waves,
     paro_validate_pairs_host,
     paro_version,
     paro_w4_dequant,

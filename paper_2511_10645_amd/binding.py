@@ -65,6 +65,8 @@ def lib():
         L.paro_workspace_bytes.restype = sz
         L.paro_workspace_bytes.argtypes = [rp, wp, i32]
         L.paro_workspace_exchange_bytes.restype = sz
+        L.paro_workspace_error_offset.restype = sz
+        L.paro_workspace_partials_offset.restype = sz
         L.paro_workspace_exchange_bytes.argtypes = [rp, wp, i32]
         L.paro_rotate_scale.argtypes = [rp, vp, i64, vp, i64, i32, vp]
         L.paro_w4a16_linear.argtypes = [wp, vp, i64, vp, i64, i32, vp, sz, vp]
@@ -80,12 +82,15 @@ def lib():
         L.paro_workspace_exchange_bytes_multi.restype = sz
         L.paro_workspace_exchange_bytes_multi.argtypes = [i32, vp, vp, i32]
         L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
-        L.paro_tune_decode_waves.argtypes = [ctypes.c_int]
-        L.paro_tune_decode_waves.restype = None
+        L.paro_diag_read_stream.argtypes = [vp, sz, vp, i32, vp]
+        L.paro_diag_mfma_f16.argtypes = [vp, sz, i32, i32, i32, vp]
+        L.paro_diag_mfma_f16_flops.argtypes = [i32, i32]
+        L.paro_diag_mfma_f16_flops.restype = ctypes.c_double
         for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
-                     "paro_rotate_scale_quantize_int4", "paro_rotate_scale_quantize_mxfp4"):
+                     "paro_rotate_scale_quantize_int4", "paro_rotate_scale_quantize_mxfp4",
+                     "paro_diag_read_stream", "paro_diag_mfma_f16"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -120,8 +125,18 @@ def paro_validate_pairs_host(pairs: np.ndarray, group: int = 128) -> int:
     return lib().paro_validate_pairs_host(p.ctypes.data, G, K, P, group)
 
 
-def paro_tune_decode_waves(blocks: int) -> None:
-    lib().paro_tune_decode_waves(int(blocks))
+def paro_diag_read_stream(src: torch.Tensor, nbytes: int, blocks: int = 2048) -> None:
+    """Pure-read ceiling probe over the first nbytes of src (a uint8 device tensor)."""
+    assert src.dtype == torch.uint8 and src.numel() >= nbytes
+    _check(lib().paro_diag_read_stream(src.data_ptr(), nbytes, None, blocks, _stream()), "paro_diag_read_stream")
+
+
+def paro_diag_mfma_f16(out: torch.Tensor, blocks: int, iters: int, random_operands: bool) -> float:
+    """Pure fp16 MFMA probe; returns the floating-point operations of the launch."""
+    assert out.dtype == torch.float32 and out.numel() >= blocks * 256
+    _check(lib().paro_diag_mfma_f16(out.data_ptr(), out.numel() * 4, blocks, iters, int(random_operands), _stream()),
+           "paro_diag_mfma_f16")
+    return lib().paro_diag_mfma_f16_flops(blocks, iters)
 
 
 def paro_select_pairs_host(order: np.ndarray, group: int, n_rotations: int, pairs_per_rotation: int):
@@ -201,7 +216,21 @@ class Workspace:
 
     def __init__(self, nbytes: int, device="cuda"):
         self.nbytes = int(nbytes)
+        self.exchange_bytes = None          # set by shared(); None: unknown, taken to be present
         self.buf = torch.zeros(max(self.nbytes, 256), dtype=torch.uint8, device=device)
+
+    def error_word(self) -> int:
+        """The header's error word (synchronises): non-zero after an exchange between blocks timed out."""
+        off = lib().paro_workspace_error_offset()
+        if self.exchange_bytes is not None and self.exchange_bytes < off + 4:
+            return 0                        # no exchange part: the buffer is scratch only
+        return int(self.buf[off:off + 4].view(torch.int32).item()) if self.nbytes >= off + 4 else 0
+
+    def partials_clean(self, exchange_bytes=None) -> bool:
+        """True if the split-K partial sums of the exchange part are all zero again (synchronises)."""
+        lo = lib().paro_workspace_partials_offset()
+        hi = self.nbytes if exchange_bytes is None else exchange_bytes
+        return hi <= lo or int(self.buf[lo:hi].max().item()) == 0
 
     @classmethod
     def shared(cls, calls, device="cuda"):

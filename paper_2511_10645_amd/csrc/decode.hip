@@ -25,193 +25,9 @@
 // rounds to fp16.  Agent-scope release/acquire fences would cost an L2 write-back and
 // invalidate per wave on this multi-XCD part (measured: +40..85 us per launch), so none are
 // used: each partial word is its own full/empty flag (see splitk_reduce).
-#include "paro_internal.h"
+#include "decode_common.h"
 
 namespace paro {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kDecWaves = 4;
-constexpr int kDecThreads = kDecWaves * 64;
-constexpr int kSliceCh = kSliceGroups * kGroup;      // 512
-constexpr int kXPad = 8;                             // halfs of padding per LDS row
-constexpr int kReducePerThread = 4;                   // partial words requested per thread and round
-constexpr int kReduceWords = kReducePerThread * 256;  // partial words gathered per reduction round (LDS floats)
-constexpr int kMaxIter = 9;                          // tiles per wave (unrolled stream), multiple of 3
-constexpr int kSpinLimit = 1 << 22;                  // bounded wait for a partial word to fill
-
-static int g_decode_target_blocks = 0;      // 0: choose by size (see decode_geometry)
-
-struct DecodeArgs {
-    const void *blob;            // repacked weight: tiles | scales | zeros
-    uint32_t blob_bytes, scales_off, zeros_off;
-    const _Float16 *X; int64_t ldx;
-    _Float16 *Y; int64_t ldy;
-    const _Float16 *bias;
-    const uint32_t *plan;
-    float *partial;
-    int T, C, N, G, NT, KS, tiles_per_block;
-    uint32_t m_lo, m_hi, k_lo, k_hi;     // dequant constants, see DequantConsts
-};
-
-// Raw buffer resources (stride 0): an access whose byte offset lies beyond num_records returns 0
-// (loads) or is dropped (stores).  Predication by offset keeps every memory instruction of the
-// stream loop unconditional, so the outstanding-load count is static and the compiler can wait
-// for exactly the stage it needs while later stages stay in flight.
-constexpr uint32_t kOob = 0x80000000u;
-constexpr int kRsrcFlags = 0x00020000;        // 32-bit data format field of a gfx9-family raw buffer
-#ifndef PARO_TILE_AUX
-#define PARO_TILE_AUX 2
-#endif
-constexpr int kTileAux = PARO_TILE_AUX;       // weight tiles are read once: non-temporal (bit 1); measured 6 % faster than default
-constexpr int kAuxSc1 = 16;                   // agent-scope (write-through / cache-bypassing) access
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, kRsrcFlags);
-}
-
-struct Stage {
-    u32x4 w[kSliceGroups];
-    uint2 sc;
-    uint32_t zq;
-};
-
-// tile < 0 loads nothing (all zeros)
-__device__ inline void load_stage(__amdgpu_buffer_rsrc_t blob, const DecodeArgs &a, int tile, int ks, int lane,
-                                  Stage &st)
-{
-    const bool ok = tile >= 0;
-    const uint32_t toff = ok ? (((uint32_t)tile * a.G + (uint32_t)ks * kSliceGroups) * 64u + lane) * 16u : kOob;
-#pragma unroll
-    for (int gi = 0; gi < kSliceGroups; ++gi)
-        st.w[gi] = __builtin_amdgcn_raw_buffer_load_b128(blob, (int)(toff + gi * 1024u), 0, kTileAux);
-    const uint32_t sidx = ((uint32_t)tile * a.KS + ks) * kTileN + (lane & 15);
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    u32x2 sc = __builtin_amdgcn_raw_buffer_load_b64(blob, ok ? (int)(a.scales_off + sidx * 8u) : (int)kOob, 0, 0);
-    st.sc = make_uint2(sc[0], sc[1]);
-    st.zq = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(blob, ok ? (int)(a.zeros_off + sidx * 2u) : (int)kOob, 0, 0);
-}
-
-__device__ inline half2v as_h2(uint32_t u) { union { uint32_t u; half2v h; } c; c.u = u; return c.h; }
-__device__ inline uint32_t as_u32(half2v h) { union { uint32_t u; half2v h; } c; c.h = h; return c.u; }
-
-// (a & mask) | magic is one VALU op (v_and_or_b32) when mask and magic sit in registers.  GFX9-family
-// VOP3 encodings take no literals, so with compile-time constants the compiler emits two VOP2
-// ops with literals instead; the four constants therefore travel as kernel arguments and are
-// moved into VGPRs once per wave.  (Inline
-// asm is not an option: instructions hidden from the compiler's hazard handling next to MFMAs
-// produced wrong results.)
-__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) { return (a & mask) | magic; }
-
-struct DequantConsts {
-    uint32_t m_lo, m_hi, k_lo, k_hi;     // 0x000F000F, 0x00F000F0, 0x64006400 (1024.0 x2), 0x54005400 (64.0 x2)
-};
-
-// Sum over the slice's 4 groups of s_g * sum_k (q - z_g) x' for one 16-row tile.
-//
-// The codes are turned into fp16 by or-ing them into the mantissa of 1024.0 (low nibble of a
-// byte) or 64.0 (high nibble): B holds b_k + q with b_k in {1024, 64}.  Instead of subtracting
-// b_k + z from every weight, the MFMA accumulator starts at
-//      -(sum_k b_k x'_k) - z * (sum_k x'_k)  =  nb1 + z * nb2
-// (two per-token, per-group sums computed once per block), so that after the four MFMAs it
-// holds sum_k (q - z) x'.  fp32 accumulation: the bias inflates partial sums by <= 1039x, which
-// costs ~2^-24 * 1039 relative to the group's |x'| mass - far inside the output tolerance.
-// T1: one token, only accumulator row 0 is live.
-template <bool T1>
-__device__ inline float4v tile_dot(const Stage &st, const half8 (&xf)[kSliceGroups][4],
-                                   const float4v (&nb1)[kSliceGroups], const float4v (&nb2)[kSliceGroups],
-                                   const DequantConsts &k)
-{
-    float4v tot = {0.f, 0.f, 0.f, 0.f};
-    union { uint2 v; _Float16 h[4]; } sc; sc.v = st.sc;
-#pragma unroll
-    for (int gi = 0; gi < kSliceGroups; ++gi) {
-        const float zf = (float)((st.zq >> (4 * gi)) & 15u);
-        float4v acc;
-        if constexpr (T1) { acc[0] = zf * nb2[gi][0] + nb1[gi][0]; acc[1] = acc[2] = acc[3] = 0.f; }
-        else acc = zf * nb2[gi] + nb1[gi];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t u = st.w[gi][j], t = u >> 8;
-            union { uint32_t d[4]; half8 h; } b;
-            b.d[0] = and_or(u, k.m_lo, k.k_lo);
-            b.d[1] = and_or(u, k.m_hi, k.k_hi);
-            b.d[2] = and_or(t, k.m_lo, k.k_lo);
-            b.d[3] = and_or(t, k.m_hi, k.k_hi);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[gi][j], b.h, acc, 0, 0, 0);
-        }
-        const float s = (float)sc.h[gi];
-        if constexpr (T1) tot[0] += s * acc[0];
-        else tot += s * acc;
-    }
-    return tot;
-}
-
-// Split-K reduction, spread over the `parts` blocks of one output range.  The T*width outputs of
-// the range are cut into `parts` contiguous shares; block `part` sums the partials of its share
-// in a fixed order (deterministic), adds the bias and stores fp16.  No fences and no counters:
-// every partial word is its own full/empty flag (0 = empty; a value is never stored as +0),
-// written with agent-scope stores and taken by its reader with an agent-scope atomic exchange
-// against 0, which reads the word and leaves it empty in one operation (an exchange that finds
-// 0 changes nothing and is repeated).  Measured: the returning atomic comes back faster than an
-// agent-scope load (the fused launches lose 0.3-0.7 us), while atomics on the writer side would
-// serialise.  The writers are the blocks dispatched next to the reader, which never wait on
-// anything before writing.  The poll is bounded; a word that never fills is reported as NaN.
-__device__ inline void splitk_reduce(const DecodeArgs &a, int parts, int part, int tile_lo, int tile_hi, float *s_red)
-{
-    const int THREADS = blockDim.x;                 // >= 256: kReducePerThread requests per thread cover a round
-    const int n_lo = tile_lo * kTileN, width = (tile_hi - tile_lo) * kTileN;
-    const int outputs = a.T * width;
-    const int share = (outputs + parts - 1) / parts;
-    const int o_lo = part * share, o_hi = min(outputs, o_lo + share);
-    const int round_outputs = kReduceWords / parts;
-    for (int base = o_lo; base < o_hi; base += round_outputs) {
-        const int n_out = min(round_outputs, o_hi - base);
-        __syncthreads();
-        // all of a thread's words are requested before any is examined: one round trip
-        constexpr int PER = kReducePerThread;
-        uint32_t bits[PER];
-        uint32_t *ptr[PER];
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int j = threadIdx.x + u * THREADS;
-            const bool on = j < n_out * parts;
-            // consecutive threads take consecutive outputs of one K-part: coalesced requests
-            const int o = base + (on ? j % n_out : 0), k2 = on ? j / n_out : 0;
-            const int t = o / width, n = n_lo + o % width;
-            ptr[u] = (uint32_t *)(a.partial + ((size_t)k2 * a.T + t) * a.N + n);
-            bits[u] = on ? __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0x80000000u;
-        }
-        // words still empty are requested again, all of a thread's in one round trip
-        for (int spin = 0; spin < kSpinLimit; ++spin) {
-            bool empty = false;
-#pragma unroll
-            for (int u = 0; u < PER; ++u) empty |= bits[u] == 0u;
-            if (!empty) break;
-#pragma unroll
-            for (int u = 0; u < PER; ++u)
-                if (bits[u] == 0u)
-                    bits[u] = __hip_atomic_exchange(ptr[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int j = threadIdx.x + u * THREADS;
-            if (j < n_out * parts) s_red[j] = bits[u] == 0u ? __builtin_nanf("") : __uint_as_float(bits[u]);
-        }
-        __syncthreads();
-        for (int i = threadIdx.x; i < n_out; i += THREADS) {
-            const int o = base + i;
-            const int t = o / width, n = n_lo + o % width;
-            float sum = 0.f;
-            for (int k2 = 0; k2 < parts; ++k2) sum += s_red[k2 * n_out + i];
-            if (a.bias) sum += (float)a.bias[n];
-            a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
-        }
-    }
-}
 
 // K: rotation layers fused in front.  SPLIT: more than one K-slice.  T1: exactly one token.
 template <int K, bool SPLIT, bool T1, int W = kDecWaves>
@@ -405,10 +221,11 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
     // ... and so does, by a little, a long stream whose 8-wave blocks still fit one round
     // (4096 -> 28672: 14.65 against 14.9 us); the small linears are faster with 4 waves
     const bool many_slices = d.ks >= 16, big = packed_tiles_bytes(c_in, c_out) >= (24u << 20);
-    d.waves = (T == 1 && (many_slices || big) && target_blocks == 0 && g_decode_target_blocks == 0) ? 2 * kDecWaves : kDecWaves;
+    // (the 8-wave kernel exists in its split-K form only: never with a single K-slice)
+    d.waves = (T == 1 && d.ks > 1 && (many_slices || big) && target_blocks == 0) ? 2 * kDecWaves : kDecWaves;
     // measured on MI355X: one 4-wave block per CU for the small linears (the prologue is repeated
     // less often), two per CU once the weight stream exceeds ~24 MB
-    int target = target_blocks > 0 ? target_blocks : g_decode_target_blocks;
+    int target = target_blocks;
     if (target <= 0) target = packed_tiles_bytes(c_in, c_out) >= (24u << 20) ? 512 : 256;
     if (d.waves > kDecWaves) target = 256;
     int nb = target / d.ks;
@@ -438,7 +255,7 @@ template <int K>
 static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, hipStream_t s)
 {
     const dim3 grid(d.ks, d.nb), block(d.waves * 64);
-    if (d.waves == 2 * kDecWaves) {      // only chosen for one token and many K-slices
+    if (d.waves == 2 * kDecWaves) {      // only chosen for one token and more than one K-slice (decode_geometry)
         hipLaunchKernelGGL((decode_kernel<K, true, true, 2 * kDecWaves>), grid, block, 0, s, a);
         return hipGetLastError();
     }
@@ -453,14 +270,13 @@ static hipError_t launch_decode_k(const DecodeArgs &a, const DecodeGeometry &d, 
 }
 
 static hipError_t fill_decode_args(DecodeArgs &a, DecodeGeometry &d, const paro_rotation *rot, const paro_w4_weight &w,
-                                   const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T, void *partial,
-                                   int target_blocks = 0)
+                                   const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T, void *ws,
+                                   size_t partial_off, int target_blocks = 0)
 {
     if (!rot || !rot->plan) return hipErrorInvalidValue;
     d = decode_geometry(w.c_in, w.c_out, T, target_blocks);
     if (d.ks > kReduceWords) return hipErrorInvalidValue;
-    if (packed_tiles_bytes(w.c_in, w.c_out) + packed_scales_bytes(w.c_in, w.c_out) + packed_zeros_bytes(w.c_in, w.c_out) >= (1ull << 31))
-        return hipErrorInvalidValue;   // 32-bit buffer offsets
+    if (packed_blob_bytes(w.c_in, w.c_out) >= (1ull << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets (checked by the caller)
     a.blob = w.packed;
     a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);
     a.zeros_off = a.scales_off + (uint32_t)packed_scales_bytes(w.c_in, w.c_out);
@@ -468,7 +284,8 @@ static hipError_t fill_decode_args(DecodeArgs &a, DecodeGeometry &d, const paro_
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
     a.plan = (const uint32_t *)rot->plan;
-    a.partial = (float *)partial;
+    a.partial = (float *)((char *)ws + kWsPartialOff + partial_off);
+    a.err = (uint32_t *)ws + kWsErrorWord;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN; a.KS = d.ks;
     a.tiles_per_block = d.tiles_per_block;
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
@@ -480,7 +297,7 @@ hipError_t launch_decode(const paro_rotation *rot, const paro_w4_weight &w, cons
 {
     DecodeArgs a;
     DecodeGeometry d;
-    hipError_t e = fill_decode_args(a, d, rot, w, X, ldx, Y, ldy, T, ws);
+    hipError_t e = fill_decode_args(a, d, rot, w, X, ldx, Y, ldy, T, ws, 0);
     if (e != hipSuccess) return e;
     switch (rot->n_layers) {
     case 0: return launch_decode_k<0>(a, d, s);
@@ -515,8 +332,7 @@ static int multi_part_target(int n_parts, const paro_w4_weight *const *w, int p)
 {
     size_t n_all = 0;
     for (int q = 0; q < n_parts; ++q) n_all += (size_t)w[q]->c_out;
-    int target = g_decode_target_blocks;
-    if (target <= 0) target = packed_tiles_bytes(w[0]->c_in, (int)n_all) >= (24u << 20) ? 512 : 256;
+    const int target = packed_tiles_bytes(w[0]->c_in, (int)n_all) >= (24u << 20) ? 512 : 256;
     const int ks = w[p]->c_in / kGroup / kSliceGroups;
     int mine = (int)(((size_t)target * w[p]->c_out + n_all / 2) / n_all);
     return mine < ks ? ks : mine;
@@ -543,7 +359,7 @@ hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, con
     size_t off = 0;
     for (int p = 0; p < n_parts; ++p) {
         DecodeGeometry d;
-        hipError_t e = fill_decode_args(m.part[p], d, rot[p], *w[p], X, ldx, Y[p], ldy[p], T, (char *)ws + off,
+        hipError_t e = fill_decode_args(m.part[p], d, rot[p], *w[p], X, ldx, Y[p], ldy[p], T, ws, off,
                                         multi_part_target(n_parts, w, p));
         if (e != hipSuccess) return e;
         if (p && (d.ks != ks || rot[p]->n_layers != rot[0]->n_layers)) return hipErrorInvalidValue;
@@ -564,182 +380,6 @@ hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, con
     case 7: return launch_multi_k<7>(m, ks, nb_total, T, s);
     default: return launch_multi_k<8>(m, ks, nb_total, T, s);
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// Wide variant: the waves of a block cover different K-slices (one each, up to 12 = 6144
-// channels) of the SAME tiles; their partial tiles are summed through LDS, so such layers need no
-// exchange between blocks at all, and wider ones (slices spread evenly over blocks of at most 8
-// waves) exchange correspondingly fewer partial sums.  Used for the bare linear and for 5..16
-// tokens, where partial sums (T x N fp32 per K-part) would otherwise rival the weight stream.
-// The transform, if any, has run as a separate pass.
-// ------------------------------------------------------------------------------------------
-#ifndef PARO_WIDE_WAVES
-#define PARO_WIDE_WAVES 12
-#endif
-constexpr int kWideWaves = PARO_WIDE_WAVES;     // most K-slices (waves) of one block
-constexpr int kWideThreads = kWideWaves * 64;
-
-template <bool SPLIT, bool T1>
-__global__ __launch_bounds__(kWideThreads) void decode_wide_kernel(DecodeArgs a)
-{
-    extern __shared__ __attribute__((aligned(16))) float s_wide[];      // [n_iter][8 waves][256] + reduce scratch
-    const int kb = blockIdx.x, nb = blockIdx.y;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nw = blockDim.x >> 6;                                        // K-slices (waves) per block, <= 8
-    const int ks = kb * nw + wave;
-    const bool slice_ok = ks < a.KS;
-    const int tile_lo = nb * a.tiles_per_block;
-    const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
-    const int n_iter = tile_hi - tile_lo;                                  // <= kMaxIter
-    auto tile_of = [&](int i) { return (i < n_iter && slice_ok) ? tile_lo + i : -1; };
-    const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
-
-    Stage st0, st1, st2;
-    half8 xf[kSliceGroups][4];
-    const int ft = lane & 15, fkb = lane >> 4;
-    {
-        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
-        const uint32_t xoff = (ft < a.T && slice_ok) ? (uint32_t)(((size_t)ft * a.ldx + (size_t)ks * kSliceCh + fkb * 32) * 2) : kOob;
-#pragma unroll
-        for (int g2 = 0; g2 < kSliceGroups; ++g2)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                union { u32x4 u; half8 h; } v;
-                v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
-                xf[g2][j] = v.h;
-            }
-        load_stage(blob, a, tile_of(0), ks, lane, st0);
-        load_stage(blob, a, tile_of(1), ks, lane, st1);
-    }
-    float4v nb1[kSliceGroups], nb2[kSliceGroups];
-    {
-        const half8 cb1 = {-1024, -1024, -64, -64, -1024, -1024, -64, -64};
-        const half8 cb2 = {-1, -1, -1, -1, -1, -1, -1, -1};
-#pragma unroll
-        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
-            float4v s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb1, s1, 0, 0, 0);
-                s2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb2, s2, 0, 0, 0);
-            }
-            nb1[g2] = s1; nb2[g2] = s2;
-        }
-    }
-    auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
-    const DequantConsts dq = {to_vgpr(a.m_lo), to_vgpr(a.m_hi), to_vgpr(a.k_lo), to_vgpr(a.k_hi)};
-
-    // partial tile of (iteration i, this wave): element lane*4 + r <-> token 4*(lane/16)+r, row lane%16
-    auto emit = [&](const Stage &stg, int i) {
-        float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
-        float *dst = s_wide + ((size_t)i * nw + wave) * 256 + lane * 4;
-        if constexpr (T1) { if (lane < 16) dst[0] = tot[0]; }
-        else *(float4v *)dst = tot;
-    };
-#pragma unroll
-    for (int i = 0; i < kMaxIter; i += 3) {
-        load_stage(blob, a, tile_of(i + 2), ks, lane, st2);
-        emit(st0, i);
-        if (i + 1 >= n_iter) break;
-        load_stage(blob, a, tile_of(i + 3), ks, lane, st0);
-        emit(st1, i + 1);
-        if (i + 2 >= n_iter) break;
-        load_stage(blob, a, tile_of(i + 4), ks, lane, st1);
-        emit(st2, i + 2);
-        if (i + 3 >= n_iter) break;
-    }
-    __syncthreads();
-
-    // ---- sum the 8 K-slices; outputs indexed (i, t, n) with n fastest for coalesced stores -----
-    const int per_tile = a.T * kTileN;
-    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += blockDim.x) {
-        const int i = idx / per_tile, rem = idx % per_tile;
-        const int t = rem / kTileN, nn = rem % kTileN;
-        const int e = ((t >> 2) * 16 + nn) * 4 + (t & 3);
-        float sum = 0.f;
-        for (int w = 0; w < nw; ++w) sum += s_wide[((size_t)i * nw + w) * 256 + e];
-        const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
-        if constexpr (!SPLIT) {
-            if (a.bias) sum += (float)a.bias[n];
-            a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
-        } else {
-            uint32_t bits = __float_as_uint(sum);
-            if ((bits << 1) == 0u) bits = 0x80000000u;
-            __hip_atomic_store((uint32_t *)(a.partial + ((size_t)kb * a.T + t) * a.N + n), bits, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    if constexpr (SPLIT)
-        splitk_reduce(a, gridDim.x, kb, tile_lo, tile_hi, s_wide + (size_t)kMaxIter * nw * 256);
-}
-
-struct WideGeometry { int kb, nb, waves, tiles_per_block; size_t lds; };
-static WideGeometry wide_geometry(int c_in, int c_out)
-{
-    WideGeometry g;
-    const int KS = c_in / kGroup / kSliceGroups, NT = c_out / kTileN;
-    // up to 12 slices fit one block (3 waves per SIMD): no exchange between blocks at all.  Beyond
-    // that the slices are spread evenly over blocks of at most 8 waves.
-    g.kb = KS <= kWideWaves ? 1 : (KS + 7) / 8;
-    g.waves = (KS + g.kb - 1) / g.kb;
-    int nb = (g.waves > 8 ? 256 : 2048 / g.waves) / g.kb;   // about 8 waves per CU; one block per CU beyond 8 waves
-    if (nb < 1) nb = 1;
-    int tpb = (NT + nb - 1) / nb;
-    if (tpb > kMaxIter) tpb = kMaxIter;
-    g.tiles_per_block = tpb;
-    g.nb = (NT + tpb - 1) / tpb;
-    g.lds = ((size_t)kMaxIter * g.waves * 256 + kReduceWords) * sizeof(float);
-    return g;
-}
-
-size_t decode_wide_partial_bytes(int c_in, int c_out, int T)
-{
-    WideGeometry g = wide_geometry(c_in, c_out);
-    int t16 = T < 16 ? T : 16;
-    return g.kb > 1 ? (size_t)g.kb * t16 * c_out * sizeof(float) : 0;
-}
-
-hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
-                              int T, void *ws, hipStream_t s)
-{
-    if (packed_tiles_bytes(w.c_in, w.c_out) + packed_scales_bytes(w.c_in, w.c_out) + packed_zeros_bytes(w.c_in, w.c_out) >= (1ull << 31))
-        return hipErrorInvalidValue;   // 32-bit buffer offsets
-    WideGeometry g = wide_geometry(w.c_in, w.c_out);
-    if (g.kb > 64) return hipErrorInvalidValue;
-    DecodeArgs a;
-    a.blob = w.packed;
-    a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);
-    a.zeros_off = a.scales_off + (uint32_t)packed_scales_bytes(w.c_in, w.c_out);
-    a.blob_bytes = a.zeros_off + (uint32_t)packed_zeros_bytes(w.c_in, w.c_out);
-    a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
-    a.bias = (const _Float16 *)w.bias;
-    a.plan = nullptr;
-    a.partial = (float *)ws;
-    a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN;
-    a.KS = a.G / kSliceGroups;
-    a.tiles_per_block = g.tiles_per_block;
-    a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
-    static std::atomic<uint64_t> attr_done{0};
-    if (const int dev = once_pending(attr_done); dev >= 0) {
-        const void *fns[4] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
-                              (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>};
-        for (const void *f : fns) {
-            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (int)(((size_t)kMaxIter * kWideWaves * 256 + kReduceWords) * sizeof(float)));
-            if (e != hipSuccess) return e;
-        }
-        once_done(attr_done, dev);
-    }
-    const dim3 grid(g.kb, g.nb), block(g.waves * 64);
-    if (T == 1) {
-        if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, true>), grid, block, g.lds, s, a);
-        else          hipLaunchKernelGGL((decode_wide_kernel<false, true>), grid, block, g.lds, s, a);
-    } else {
-        if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, false>), grid, block, g.lds, s, a);
-        else          hipLaunchKernelGGL((decode_wide_kernel<false, false>), grid, block, g.lds, s, a);
-    }
-    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -789,7 +429,5 @@ hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, 
                        (const _Float16 *)X, ldx, (_Float16 *)Y, ldy, T);
     return hipGetLastError();
 }
-
-void set_decode_target_waves(int waves) { g_decode_target_blocks = waves > 0 ? (waves + kDecWaves - 1) / kDecWaves : 0; }
 
 }  // namespace paro

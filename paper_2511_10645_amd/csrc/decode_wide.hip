@@ -1,0 +1,214 @@
+// Decode-side bare W4A16 linear, 1..16 tokens per pass: a block takes ALL K-slices of its tile
+// range, one 512-channel slice per wave (up to 12 waves = 6144 channels; beyond that the slices
+// are spread evenly over several blocks of at most 8 waves and only those few partial sums are
+// exchanged between blocks); the waves' partial tiles are summed through LDS, so layers up to
+// 6144 channels need no exchange between blocks at all.
+//
+// Stream.  Every wave keeps NS = 3 weight stages (one 16 x 512 tile slice each: 4 KB of codes plus
+// scales and zero points) in registers: two are in flight while the third is multiplied, and the
+// request for the next tile is issued before the multiplication of the current one starts.
+// Deeper staging was measured and is slower on this part (gate/up 4096 -> 28672, one token:
+// 12.6 us with 3 stages, 13.0 with 4, 14.4 with 6): what bounds the stream is not the number of
+// bytes a wave has requested.  One block per compute unit; for one token the partial sums of a
+// tile take 64 bytes of LDS per wave, so a block can run up to 16 tiles per wave and every shape
+// of the benchmark fits one round of blocks.
+//
+// The transform cannot be hosted here at a profit.  Measured: the rotation units dealt out to the
+// first waves of the grid, results published through agent-scope stores and fetched by every
+// wave with agent-scope loads (self-flagging words, no fences) costs +5 us per launch at one
+// token and +6..8 us at 16, more than a separate rotation launch (+3.2 us): vector memory
+// returns in order for the whole compute unit, so a poll waits behind every weight tile the
+// unit has requested, and throttling the requests until the activations have arrived delays the
+// stream by the same time.  Hence: up to 4 tokens the K-major kernel (decode.hip), whose blocks
+// rotate only their own slice; 5..16 tokens a rotation pass, then this kernel.
+#include "decode_common.h"
+#include <type_traits>
+
+namespace paro {
+
+// most tiles per wave (the stream loop is unrolled): one token keeps 64 B of partial sums per tile
+// and wave in LDS, several tokens 1 KB
+__host__ __device__ constexpr int wide_max_tiles(bool one_token) { return one_token ? 16 : 9; }
+constexpr int kWideStages = 3;
+constexpr int kWideWaves = 12;                  // most K-slices (waves) of one block
+
+// f(0), f(1), ... while f returns true, at most N times; nested, so that stopping is ONE forward jump
+// past all remaining steps (instruction fetch matters at these kernel durations)
+template <int N, class F, int I = 0>
+__device__ __forceinline__ void static_while(F &&f)
+{
+    if constexpr (I < N) {
+        if (f(std::integral_constant<int, I>{})) static_while<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
+
+template <bool SPLIT, bool T1>
+__global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs a)
+{
+    constexpr int NS = kWideStages;
+    // [tiles per block][waves] partial tiles | kReduceWords reduce scratch
+    extern __shared__ __attribute__((aligned(16))) float s_wide[];
+    const int kb = blockIdx.x, nb = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;                                        // K-slices (waves) per block
+    const int ks = kb * nw + wave;
+    const bool slice_ok = ks < a.KS;
+    const int tile_lo = nb * a.tiles_per_block;
+    const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
+    const int n_iter = tile_hi - tile_lo;
+    auto tile_of = [&](int i) { return (i < n_iter && slice_ok) ? tile_lo + i : -1; };
+    const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
+    constexpr int kTileWords = T1 ? kTileN : 256;
+    float *s_red = s_wide + (size_t)a.tiles_per_block * nw * kTileWords;
+
+    Stage st[NS];
+    half8 xf[kSliceGroups][4];
+    const int ft = lane & 15, fkb = lane >> 4;
+    {
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
+        const uint32_t xoff = (ft < a.T && slice_ok) ? (uint32_t)(((size_t)ft * a.ldx + (size_t)ks * kSliceCh + fkb * 32) * 2) : kOob;
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                union { u32x4 u; half8 h; } v;
+                v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
+                xf[g2][j] = v.h;
+            }
+#pragma unroll
+        for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
+    }
+    // per token and group: nb1 = -sum_k b_k x'_k, nb2 = -sum_k x'_k (see tile_dot)
+    float4v nb1[kSliceGroups], nb2[kSliceGroups];
+    {
+        const half8 cb1 = {-1024, -1024, -64, -64, -1024, -1024, -64, -64};
+        const half8 cb2 = {-1, -1, -1, -1, -1, -1, -1, -1};
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+            float4v s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb1, s1, 0, 0, 0);
+                s2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[g2][j], cb2, s2, 0, 0, 0);
+            }
+            nb1[g2] = s1; nb2[g2] = s2;
+        }
+    }
+    auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
+    const DequantConsts dq = {to_vgpr(a.m_lo), to_vgpr(a.m_hi), to_vgpr(a.k_lo), to_vgpr(a.k_hi)};
+
+    // partial tile of (tile i of the block, this wave).  More than one token: element lane*4 + r <-> token
+    // 4*(lane/16)+r, row lane%16 (1 KB per tile and wave); one token: the 16 rows only (64 B)
+    auto emit = [&](const Stage &stg, int i) {
+        float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
+        float *dst = s_wide + ((size_t)i * nw + wave) * kTileWords;
+        if constexpr (T1) { if (lane < 16) dst[lane] = tot[0]; }
+        else *(float4v *)(dst + lane * 4) = tot;
+    };
+    // Fully unrolled (n_iter <= MAXI, guaranteed by the launcher): straight-line code with one uniform
+    // early exit and no back edge, so every wait inserted by the compiler names exactly the stage it
+    // needs and the younger ones stay in flight.  (A rolled loop makes the compiler wait for all but
+    // the newest load at the back edge; skipping the unused steps one by one instead of with one jump
+    // costs 0.3-0.7 us per launch in instruction fetches.)
+    constexpr int MAXI = wide_max_tiles(T1);
+    static_while<MAXI>([&](auto I) {
+        constexpr int i = I;
+        if (i >= n_iter) return false;
+        // the request for tile i + NS - 1 goes out before tile i is multiplied: NS - 1 stages in flight
+        load_stage(blob, a, tile_of(i + NS - 1), ks, lane, st[(i + NS - 1) % NS]);
+        emit(st[i % NS], i);
+        return true;
+    });
+    __syncthreads();
+    // ---- sum the K-slices; outputs indexed (i, t, n) with n fastest for coalesced stores -----
+    const int per_tile = a.T * kTileN;
+    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += blockDim.x) {
+        const int i = idx / per_tile, rem = idx % per_tile;
+        const int t = rem / kTileN, nn = rem % kTileN;
+        const int e = T1 ? nn : ((t >> 2) * 16 + nn) * 4 + (t & 3);
+        float sum = 0.f;
+        for (int w = 0; w < nw; ++w) sum += s_wide[((size_t)i * nw + w) * kTileWords + e];
+        const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
+        if constexpr (!SPLIT) {
+            if (a.bias) sum += (float)a.bias[n];
+            a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
+        } else {
+            uint32_t bits = __float_as_uint(sum);
+            if ((bits << 1) == 0u) bits = 0x80000000u;
+            __hip_atomic_store((uint32_t *)(a.partial + ((size_t)kb * a.T + t) * a.N + n), bits, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if constexpr (SPLIT) splitk_reduce(a, gridDim.x, kb, tile_lo, tile_hi, s_red);
+}
+
+struct WideGeometry { int kb, nb, waves, tiles_per_block; size_t lds; };
+static WideGeometry wide_geometry(int c_in, int c_out, int T)
+{
+    WideGeometry g;
+    const int KS = c_in / kGroup / kSliceGroups, NT = c_out / kTileN;
+    // up to 12 slices fit one block (3 waves per SIMD): no exchange between blocks at all.  Beyond
+    // that the slices are spread evenly over blocks of at most 8 waves.
+    g.kb = KS <= kWideWaves ? 1 : (KS + 7) / 8;
+    g.waves = (KS + g.kb - 1) / g.kb;
+    int nb = 256 / g.kb;                                     // one block per compute unit
+    if (nb < 1) nb = 1;
+    int tpb = (NT + nb - 1) / nb;
+    if (tpb > wide_max_tiles(T == 1)) tpb = wide_max_tiles(T == 1);
+    g.tiles_per_block = tpb;
+    g.nb = (NT + tpb - 1) / tpb;
+    g.lds = ((size_t)tpb * g.waves * (T == 1 ? kTileN : 256) + kReduceWords) * sizeof(float);
+    return g;
+}
+
+size_t decode_wide_partial_bytes(int c_in, int c_out, int T)
+{
+    WideGeometry g = wide_geometry(c_in, c_out, T);
+    int t16 = T < 16 ? T : 16;
+    return g.kb > 1 ? (size_t)g.kb * t16 * c_out * sizeof(float) : 0;
+}
+
+// ws: the exchange part of the workspace (may be NULL where no partial sums are exchanged)
+hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                              int T, void *ws, hipStream_t s)
+{
+    if (packed_blob_bytes(w.c_in, w.c_out) >= (1ull << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets (checked by the caller)
+    const WideGeometry g = wide_geometry(w.c_in, w.c_out, T);
+    if (g.kb > 64 || g.lds > 160 * 1024 || (g.kb > 1 && !ws)) return hipErrorInvalidValue;
+    DecodeArgs a;
+    a.blob = w.packed;
+    a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);
+    a.zeros_off = a.scales_off + (uint32_t)packed_scales_bytes(w.c_in, w.c_out);
+    a.blob_bytes = a.zeros_off + (uint32_t)packed_zeros_bytes(w.c_in, w.c_out);
+    a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
+    a.bias = (const _Float16 *)w.bias;
+    a.plan = nullptr;
+    a.err = ws ? (uint32_t *)ws + kWsErrorWord : nullptr;
+    a.partial = ws ? (float *)((char *)ws + kWsPartialOff) : nullptr;
+    a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN;
+    a.KS = a.G / kSliceGroups;
+    a.tiles_per_block = g.tiles_per_block;
+    a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
+        const void *fns[4] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
+                              (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>};
+        for (const void *f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+        }
+        once_done(attr_done, dev);
+    }
+    const dim3 grid(g.kb, g.nb), block(g.waves * 64);
+    if (T == 1) {
+        if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, true>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((decode_wide_kernel<false, true>), grid, block, g.lds, s, a);
+    } else {
+        if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, false>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((decode_wide_kernel<false, false>), grid, block, g.lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace paro

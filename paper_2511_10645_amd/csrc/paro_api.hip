@@ -6,21 +6,11 @@
 
 using namespace paro;
 
-namespace paro {
-void set_decode_target_waves(int blocks);
-}
-
 namespace {
 
-#ifndef PARO_FUSE_MAX_TOKENS
-#define PARO_FUSE_MAX_TOKENS 4
-#endif
-constexpr int kFuseMaxTokens = PARO_FUSE_MAX_TOKENS;     // rotation runs inside the decode kernel up to this many tokens
-#ifndef PARO_DECODE_MAX_TOKENS
-#define PARO_DECODE_MAX_TOKENS 16
-#endif
+constexpr int kFuseMaxTokens = 4;            // the K-major decode kernel hosts the rotation up to this many tokens
 constexpr int64_t kMaxRowStride = 1 << 22;   // elements; the kernels address a run of up to 256 rows with 31-bit byte offsets
-constexpr int kDecodeMaxTokens = PARO_DECODE_MAX_TOKENS;  // above this the MFMA GEMM takes over from the streaming decode kernel
+constexpr int kDecodeMaxTokens = 16;         // above this the MFMA GEMM takes over from the streaming decode kernels
 
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -52,7 +42,17 @@ paro_status check_weight(const paro_w4_weight *w, bool need_interchange)
     return PARO_OK;
 }
 
-inline bool fast_weight(const paro_w4_weight *w) { return w->packed && (w->c_in / kGroup) % kSliceGroups == 0; }
+// the tiled kernels address the repacked blob with 32-bit byte offsets
+inline bool fast_weight(const paro_w4_weight *w)
+{
+    return w->packed && (w->c_in / kGroup) % kSliceGroups == 0 && packed_blob_bytes(w->c_in, w->c_out) < (1ull << 31);
+}
+
+// the K-major decode kernel hosts the rotation: planned rotation, repacked weight, few tokens
+inline bool fused_decode(const paro_rotation *rot, const paro_w4_weight *w, int T)
+{
+    return rot && rot->plan && fast_weight(w) && T <= kFuseMaxTokens;
+}
 
 paro_status check_io(const void *X, int64_t ldx, int width_x, const void *Y, int64_t ldy, int width_y, int T,
                      int64_t ld_mult)
@@ -84,10 +84,11 @@ WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
         DecodeGeometry d = decode_geometry(w->c_in, w->c_out, T);
         size_t wide = decode_wide_partial_bytes(w->c_in, w->c_out, T);
         size_t part = d.partial_bytes > wide ? d.partial_bytes : wide;
-        L.exchange_bytes = round_up(part, 256);
+        // the bare linear without partial sums to exchange needs no workspace at all
+        L.exchange_bytes = (rot || part) ? kWsPartialOff + round_up(part, 256) : 0;
         if (T > kDecodeMaxTokens) L.gemm_bytes = round_up(gemm_scratch_bytes(*w, T), 256);
     }
-    const bool fused = rot && fast_weight(w) && rot->plan && T <= kFuseMaxTokens;
+    const bool fused = fused_decode(rot, w, T);
     L.xr_bytes = (rot && !fused) ? round_up((size_t)T * w->c_in * 2, 256) : 0;
     L.scratch_bytes = L.xr_bytes + L.gemm_bytes;
     L.total = L.exchange_bytes + L.scratch_bytes;
@@ -218,6 +219,9 @@ paro_status paro_select_pairs_host(const int32_t *order_host, int32_t group, int
     return PARO_OK;
 }
 
+size_t paro_workspace_error_offset(void) { return kWsErrorWord * sizeof(uint32_t); }
+size_t paro_workspace_partials_offset(void) { return kWsPartialOff; }
+
 size_t paro_rotation_plan_bytes(const paro_rotation *rot)
 {
     if (check_rotation(rot) != PARO_OK) return 0;
@@ -304,12 +308,11 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
     st = check_io(X, ldx, w->c_in, Y, ldy, w->c_out, T, 8);
     if (st != PARO_OK) return st;
     WsLayout L = ws_layout(rot, w, T);
-    if (!ws || ws_bytes < L.total) return PARO_ERR_WORKSPACE;
-    if (!aligned(ws, 256)) return PARO_ERR_ALIGN;
+    if (L.total && (!ws || ws_bytes < L.total)) return PARO_ERR_WORKSPACE;
+    if (L.total && !aligned(ws, 256)) return PARO_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
 
-    if (fast_weight(w) && rot->plan && T <= kFuseMaxTokens)
-        return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
+    if (fused_decode(rot, w, T)) return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
 
     // two passes: transform into the workspace, then the bare linear
     paro_half_t *xr = (paro_half_t *)ws_scratch(ws, ws_bytes, L);
@@ -381,7 +384,7 @@ static WsLayout ws_layout_multi(int32_t n_parts, const paro_rotation *const *rot
         if (one.scratch_bytes > M.scratch_bytes) M.scratch_bytes = one.scratch_bytes;
     }
     if (multi_one_launch(n_parts, rots, weights, T)) {
-        size_t m = round_up(paro::decode_multi_bytes(n_parts, weights, T), 256);
+        size_t m = kWsPartialOff + round_up(paro::decode_multi_bytes(n_parts, weights, T), 256);
         if (m > M.exchange_bytes) M.exchange_bytes = m;
         M.scratch_bytes = 0;
     }
@@ -468,8 +471,5 @@ paro_status paro_rotate_scale_quantize_mxfp4(const paro_rotation *rot, const par
     if (!rot->plan) return PARO_ERR_UNSUPPORTED;
     return from_hip(paro::launch_quantize_act_mxfp4(*rot, X, ldx, T, codes, scales, (hipStream_t)stream));
 }
-
-// Tuning knob (process-wide, not thread-safe): target number of wavefronts of a decode launch.
-void paro_tune_decode_waves(int waves) { paro::set_decode_target_waves(waves); }
 
 }  // extern "C"

@@ -72,6 +72,20 @@ __host__ __device__ inline PackedView packed_view(const void *blob, int c_in, in
     return v;
 }
 
+__host__ __device__ inline size_t packed_blob_bytes(int c_in, int c_out) {
+    return packed_tiles_bytes(c_in, c_out) + packed_scales_bytes(c_in, c_out) + packed_zeros_bytes(c_in, c_out);
+}
+
+// ---------------------------------------------------------------------------------------
+// Exchange part of the caller's workspace (zero-filled once by the caller):
+//   [0, 256)               header: word kWsErrorWord = error flags (non-zero: a bounded wait between
+//                          blocks of a launch ran out)
+//   [kWsPartialOff, ...)   fp32 split-K partial sums, every word reset by its reader
+// ---------------------------------------------------------------------------------------
+constexpr size_t kWsHeaderBytes = 256;
+constexpr size_t kWsPartialOff = kWsHeaderBytes;
+constexpr size_t kWsErrorWord = 2;          // index of the error word in the header
+
 // nibble position of logical element e (0..7) inside a repacked dword
 __host__ __device__ inline int packed_nibble_pos(int e) { return (e >> 1) + 4 * (e & 1); }
 
@@ -123,6 +137,7 @@ hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, con
                                void *ws, hipStream_t s);
 // Wide decode kernel (bare linear, T <= 16): all K-slices of a tile range in one block (up to 12),
 // reduced through LDS; wider layers spread the slices over several blocks and exchange partials.
+// ws: the exchange part of the workspace.
 size_t decode_wide_partial_bytes(int c_in, int c_out, int T);
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                               int T, void *ws, hipStream_t s);

@@ -204,7 +204,6 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
     // 16 contiguous bytes, and back on the way out.
     static_assert(kRotTU == 4, "8 bytes per channel");
     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
-    typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
     typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
     char *sp = (char *)s_stage[wave];                      // 128 channels x 8 bytes
     auto lo_pair = [](uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); };
@@ -253,9 +252,6 @@ static hipError_t launch_rotate_k(const paro_rotation &rot, const paro_half_t *X
     // long as there are still enough waves to fill 256 CUs several times over
     int tpw = 32;
     while (tpw > kRotTU && (int64_t)G * ((T + tpw - 1) / tpw) < 4096) tpw >>= 1;
-#ifdef PARO_ROT_TPW
-    tpw = PARO_ROT_TPW;
-#endif
     int waves_t = (T + tpw - 1) / tpw;
     dim3 grid(G, (waves_t + kRotWaves - 1) / kRotWaves);
     hipLaunchKernelGGL(rotate_planned_kernel<K>, grid, dim3(kRotWaves * 64), 0, s, (const uint32_t *)rot.plan,

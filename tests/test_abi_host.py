@@ -202,7 +202,7 @@ def test_row_stride_limit():
 
 def test_workspace_parts():
     """Exchange part <= total; a fused call (T <= 4, planned, repacked) needs no scratch, a separate rotation pass
-    adds T * c_in * 2 bytes of it (rounded to 256)."""
+    adds T * c_in * 2 bytes of it (rounded to 256).  The exchange part starts with the 256-byte header."""
     L = paro.lib()
     w = _w(c_in=2048, c_out=512, packed=FAKE)
     r = _rot(c_in=2048, plan=FAKE)
@@ -210,6 +210,7 @@ def test_workspace_parts():
         tot, ex = L.paro_workspace_bytes(ctypes.byref(r), ctypes.byref(w), T), L.paro_workspace_exchange_bytes(
             ctypes.byref(r), ctypes.byref(w), T)
         assert ex <= tot and ex % 256 == 0
+        assert ex >= 256
         xr = 0 if T <= 4 else (T * 2048 * 2 + 255) // 256 * 256
         bare = L.paro_workspace_bytes(None, ctypes.byref(w), T) - L.paro_workspace_exchange_bytes(None, ctypes.byref(w), T)
         assert tot - ex == xr + bare, (T, tot, ex)

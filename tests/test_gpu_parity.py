@@ -193,7 +193,7 @@ def test_bare_linear(P, packed, case):
     got = P.paro_w4a16_linear(w, dev(li.x), ws).cpu().numpy()
     _assert_linear(got, y, allowed, f"bare {case} packed={packed}")
     ex = P.paro_workspace_exchange_bytes(None, w, case["T"])
-    assert int(ws.buf[:ex].sum().item()) == 0                            # exchange part left zero-filled
+    assert ws.partials_clean(ex) and ws.error_word() == 0               # partial sums left zero-filled
 
 
 @pytest.mark.parametrize("case", [
@@ -224,7 +224,7 @@ def test_rotated_linear(P, case):
     got2 = P.paro_rotated_linear(rot, w, x, ws)
     assert (got == got2).all()
     if case["T"] <= 4 and case["plan"] and case["packed"]:
-        assert int(ws.buf.sum().item()) == 0                             # fused path leaves the workspace zero-filled
+        assert ws.partials_clean() and ws.error_word() == 0              # no partial sums left behind, no wait ran out
 
 
 @pytest.mark.parametrize("T", [1, 3, 16, 40, 300])
@@ -290,7 +290,7 @@ def test_graph_replays_match_eager(P):
         torch.cuda.synchronize()
         for o, e in zip(outs, eager):
             assert torch.equal(o, e), rep
-        assert int(ws.buf[:ws.exchange_bytes].sum().item()) == 0
+        assert ws.partials_clean(ws.exchange_bytes) and ws.error_word() == 0
         sequence()                                               # eager work between replays
         torch.cuda.synchronize()
         for o, e in zip(outs, eager):
@@ -325,21 +325,6 @@ def test_identity_transform_equals_bare_linear(P):
     a = P.paro_rotated_linear(rot, w, dev(li.x), ws)
     b = P.paro_w4a16_linear(w, dev(li.x), ws)
     assert (a == b).all()
-
-
-def test_tuning_knob_changes_only_summation_order(P):
-    li = pin.make_custom(32, 1, 2048, 16 * 50)
-    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
-    y, allowed = _linear_ref(li, u)
-    rot, w = make_rot(P, li), make_w(P, li)
-    ws = P.Workspace(P.paro_workspace_bytes(rot, w, 1))
-    try:
-        for blocks in (16, 256, 100000):
-            P.paro_tune_decode_waves(blocks)
-            got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
-            _assert_linear(got, y, allowed, f"decode blocks={blocks}")
-    finally:
-        P.paro_tune_decode_waves(0)
 
 
 # ----------------------------------------------------------------------------- full configs
@@ -446,7 +431,7 @@ def test_one_workspace_shared_by_many_calls(P):
             _assert_linear(got, c["y_bare"], c["a_bare"], f"seq {it} bare T={c['T']} C={c['li'].c_in}")
         # the part every later call may use for its exchange is zero again, whatever ran (a separate
         # rotation pass leaves its output in the scratch part at the end of the buffer only)
-        assert int(ws.buf[:ws.exchange_bytes].sum().item()) == 0, it
+        assert ws.partials_clean(ws.exchange_bytes) and ws.error_word() == 0, it
     torch.cuda.synchronize()
 
 
@@ -516,4 +501,4 @@ def test_seeded_sweep_of_shapes(P):
         x = dev(li.x)
         _assert_linear(P.paro_rotated_linear(rot, w, x, ws).cpu().numpy(), y, allowed, f"sweep fused {case}")
         _assert_linear(P.paro_w4a16_linear(w, x, ws).cpu().numpy(), yb, allowed_b, f"sweep bare {case}")
-        assert int(ws.buf[:ws.exchange_bytes].sum().item()) == 0, case
+        assert ws.partials_clean(ws.exchange_bytes) and ws.error_word() == 0, case
