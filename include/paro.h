@@ -179,6 +179,25 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
                                 const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                                 int32_t T, void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture
+ * that may not call hipMalloc, tight serving loops, harnesses that forbid allocation):
+ * paro_rotated_linear with the exchange part of the workspace held in a static device array of
+ * PARO_NOALLOC_SCRATCH_BYTES inside the library (one copy per GPU the library runs on, held until
+ * the process ends; zero when the library is loaded, and left consistent by every call like a
+ * caller-owned exchange part).  The call allocates and frees nothing.  It serves the calls that
+ * need no scratch part - the fused decode path: rotation planned, weight repacked, T <= 4 -
+ * and returns PARO_ERR_UNSUPPORTED for the others, PARO_ERR_WORKSPACE when the exchange part of
+ * the shape exceeds PARO_NOALLOC_SCRATCH_BYTES (4 MiB covers K-slices x T x c_out x 4 bytes of
+ * every benchmark shape at one token and of the 8B-class shapes at 4).  All calls on one GPU share
+ * that GPU's array: calls that overlap in time on one GPU race, exactly as two calls sharing a
+ * caller-owned workspace would.  The first call on a device looks the array's address up
+ * (no allocation); make it outside stream capture.  After a wait between blocks timed out
+ * (outputs NaN) the array is no longer consistent for the rest of the process. */
+#define PARO_NOALLOC_SCRATCH_BYTES (4u << 20)
+paro_status paro_rotated_linear_noalloc(const paro_rotation *rot, const paro_w4_weight *w,
+                                        const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                                        int32_t T, void *stream);
+
 /* Several linears that read the SAME activations, each with its own transform: in the method every
  * linear owns its pairs, angles and scales (Section 4.1, App. A.4), so the q / k / v projections
  * (or gate / up) of a decoder layer need three (two) transforms of one X.  Part p computes

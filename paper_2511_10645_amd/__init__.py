@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     paro_rotate_scale_quantize_mxfp4,
     paro_rotated_linear,
     paro_rotated_linear_multi,
+    paro_rotated_linear_noalloc,
     paro_rotation_plan_build,
     paro_select_pairs_host,
     paro_status_string,

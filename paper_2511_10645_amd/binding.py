@@ -71,6 +71,7 @@ def lib():
         L.paro_rotate_scale.argtypes = [rp, vp, i64, vp, i64, i32, vp]
         L.paro_w4a16_linear.argtypes = [wp, vp, i64, vp, i64, i32, vp, sz, vp]
         L.paro_rotated_linear.argtypes = [rp, wp, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.paro_rotated_linear_noalloc.argtypes = [rp, wp, vp, i64, vp, i64, i32, vp]
         L.paro_w4_unpack_codes.argtypes = [wp, vp, vp]
         L.paro_w4_unpack_zeros.argtypes = [wp, vp, vp]
         L.paro_w4_dequant.argtypes = [wp, vp, vp]
@@ -87,7 +88,7 @@ def lib():
         L.paro_diag_mfma_f16_flops.argtypes = [i32, i32]
         L.paro_diag_mfma_f16_flops.restype = ctypes.c_double
         for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
-                     "paro_w4a16_linear", "paro_rotated_linear", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
+                     "paro_w4a16_linear", "paro_rotated_linear", "paro_rotated_linear_noalloc", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
                      "paro_rotate_scale_quantize_int4", "paro_rotate_scale_quantize_mxfp4",
                      "paro_diag_read_stream", "paro_diag_mfma_f16"):
@@ -318,6 +319,15 @@ def paro_rotated_linear(rot: Rotation, w: W4Weight, X: torch.Tensor, ws: Workspa
     _, ldy = _rows(Y)
     _check(lib().paro_rotated_linear(rot.ref(), w.ref(), X.data_ptr(), ldx, Y.data_ptr(), ldy, T,
                                      ws.buf.data_ptr(), ws.nbytes, _stream()), "paro_rotated_linear")
+    return Y
+
+
+def paro_rotated_linear_noalloc(rot: Rotation, w: W4Weight, X: torch.Tensor, Y: torch.Tensor):
+    """paro_rotated_linear on the library's static exchange array: the caller passes inputs and outputs only."""
+    T, ldx = _rows(X)
+    _, ldy = _rows(Y)
+    _check(lib().paro_rotated_linear_noalloc(rot.ref(), w.ref(), X.data_ptr(), ldx, Y.data_ptr(), ldy, T, _stream()),
+           "paro_rotated_linear_noalloc")
     return Y
 
 

@@ -102,6 +102,27 @@ inline char *ws_scratch(void *ws, size_t ws_bytes, const WsLayout &L)
 
 paro_status from_hip(hipError_t e) { return e == hipSuccess ? PARO_OK : PARO_ERR_HIP; }
 
+// Exchange part for callers that cannot allocate (paro_rotated_linear_noalloc): one array per GPU,
+// part of the loaded code object, zero-initialised when the library is loaded on that GPU and
+// kept consistent by the calls themselves like any caller-owned exchange part.  In host code the
+// array's name is only a handle; its device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = PARO_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<void *> g_scratch_ptr[64];
+
+paro_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PARO_ERR_HIP;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PARO_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);      // same address from every thread: idempotent
+    }
+    *out = p;
+    return PARO_OK;
+}
+
 // bare linear on (already transformed) activations, any T
 paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int T,
                        void *ws, void *gemm_scratch, size_t gemm_bytes, hipStream_t s)
@@ -321,6 +342,25 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
     if (e != hipSuccess) return PARO_ERR_HIP;
     return run_linear(w, xr, w->c_in, Y, ldy, T, ws, L.gemm_bytes ? ws_scratch(ws, ws_bytes, L) + L.xr_bytes : nullptr,
                       L.gemm_bytes, s);
+}
+
+paro_status paro_rotated_linear_noalloc(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X,
+                                        int64_t ldx, paro_half_t *Y, int64_t ldy, int32_t T, void *stream)
+{
+    paro_status st = check_rotation(rot);
+    if (st != PARO_OK) return st;
+    st = check_weight(w, false);
+    if (st != PARO_OK) return st;
+    if (rot->c_in != w->c_in) return PARO_ERR_SHAPE;
+    st = check_io(X, ldx, w->c_in, Y, ldy, w->c_out, T, 8);
+    if (st != PARO_OK) return st;
+    const WsLayout L = ws_layout(rot, w, T);
+    if (L.scratch_bytes) return PARO_ERR_UNSUPPORTED;                 // needs a scratch part: only the allocating call serves it
+    if (L.exchange_bytes > kStaticScratchBytes) return PARO_ERR_WORKSPACE;
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != PARO_OK) return st;
+    return paro_rotated_linear(rot, w, X, ldx, Y, ldy, T, ws, kStaticScratchBytes, stream);
 }
 
 paro_status paro_w4_unpack_codes(const paro_w4_weight *w, uint8_t *codes, void *stream)
