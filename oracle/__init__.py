@@ -189,6 +189,20 @@ def mxfp4_quantize(u: np.ndarray):
     return codes, scales
 
 
+def fwht(x16) -> np.ndarray:
+    """y = H_n x / sqrt(n) per row, Sylvester order (H_n[i][j] = (-1)^popcount(i & j)), fp64 [T][n]."""
+    xb = _bits(x16)
+    T, n = xb.shape
+    y = np.empty((T, n), dtype=np.float64)
+    L = lib()
+    L.oracle_fwht.restype = ctypes.c_int
+    rc = L.oracle_fwht(_p(xb, ctypes.c_uint16), ctypes.c_int64(n), ctypes.c_int32(T), ctypes.c_int32(n),
+                       _p(y, ctypes.c_double), ctypes.c_int64(n))
+    if rc != 0:
+        raise ValueError("row length is not a power of two")
+    return y
+
+
 def unpack_codes(qweight: np.ndarray) -> np.ndarray:
     q = _c(qweight, np.uint32)
     N, C8 = q.shape

@@ -26,6 +26,8 @@
  *   Def. 1                                 : pairs of one layer are disjoint
  *   Eq. 1, Eq. 8 (weight side)             : W' = R_K ... R_1 . diag(alpha) . W per
  *                                           output row, then RTN per group
+ *   Section 4.3, speed-up figure           : the Hadamard transform it is compared with
+ *                                           (Sylvester order, orthonormal)
  *
  * Readings where the paper leaves a choice
  *   - theta on the activation side.  Eq. 5 right-multiplies a row vector by
@@ -48,6 +50,7 @@
  * inputs; exhaustive unpack; exhaustive fp64->fp16 rounding against numpy.
  * Weight side: hand-computed RTN groups, the s/2 error bound of Eq. 1, and
  * transformed weights times transformed activations reproducing W.x (Eq. 2).
+ * Hadamard yardstick: n = 2 and n = 4 by hand, scipy's Hadamard matrix, involution and norm.
  * The paper's accuracy tables are not on this path: parity unpinned for them.
  */
 #include <math.h>
@@ -391,4 +394,30 @@ void oracle_linear_samples(const double *u, int64_t ldu,
         y[s] = a + (bias16 ? oracle_fp16_to_f64(bias16[n]) : 0.0);
         if (w_sqnorm) w_sqnorm[s] = ww;
     }
+}
+
+/*
+ * Walsh-Hadamard transform of each row, Sylvester (natural) order, orthonormal scaling - the
+ * yardstick the transform kernel is compared with in Section 4.3 (figure "speedup of scaled
+ * pairwise rotation over the Hadamard transform"):
+ *      y = H_n x / sqrt(n),   H_1 = [1],  H_2m = [[H_m, H_m], [H_m, -H_m]],
+ * i.e. H_n[i][j] = (-1)^popcount(i & j).  Written as that definition, one dot product per output
+ * (O(n^2) per row): no butterfly, so that it can be read against the definition by eye.
+ * x16: [T][ldx] fp16 bits, y: [T][ldy] fp64, n a power of two.  Returns -1 if n is not.
+ */
+int oracle_fwht(const uint16_t *x16, int64_t ldx, int32_t T, int32_t n, double *y, int64_t ldy)
+{
+    if (n < 1 || (n & (n - 1))) return -1;
+    const double inv = 1.0 / sqrt((double)n);
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t i = 0; i < n; ++i) {
+            double acc = 0.0;
+            for (int32_t j = 0; j < n; ++j) {
+                double v = oracle_fp16_to_f64(x16[(int64_t)t * ldx + j]);
+                acc += (__builtin_popcount((unsigned)(i & j)) & 1) ? -v : v;
+            }
+            y[(int64_t)t * ldy + i] = acc * inv;
+        }
+    return 0;
 }
