@@ -268,6 +268,16 @@ paro_status paro_w4_unpack_zeros(const paro_w4_weight *w, uint8_t *zeros, void *
 /* W[n][c] = fp16( (q - z) * s ), exact product rounded once to nearest-even. */
 paro_status paro_w4_dequant(const paro_w4_weight *w, paro_half_t *W, void *stream);
 
+/* Yardstick of Section 4.3's figure ("speedup of scaled pairwise rotation over the Hadamard
+ * transform"): the fast Walsh-Hadamard transform of activation rows, the online transform of the
+ * Hadamard-based methods the paper compares its kernel with.  Not part of the method's path.
+ *      Y[t, :] = H_n X[t, :] / sqrt(n),  H_n[i][j] = (-1)^popcount(i & j)  (Sylvester order)
+ * fp32 butterflies, one fp16 rounding at the store.  n a power of two, 8 <= n <= 32768
+ * (PARO_ERR_UNSUPPORTED above); X, Y: fp16 [T][ld*], ld >= n and a multiple of 8, 16-byte
+ * aligned; Y == X (same ld) is allowed.  No workspace. */
+paro_status paro_fwht(const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy, int32_t T,
+                      int32_t n, void *stream);
+
 /* Diagnostics: measured ceilings of the machine (benchmark only; not part of the method) ------
  * A roofline fraction against the nominal peaks (8 TB/s, 2.5 PFLOP/s) says little unless one
  * knows what a kernel that does nothing else reaches on the same chip at the same size. */

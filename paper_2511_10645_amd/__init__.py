@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     ParoError,
     paro_diag_mfma_f16,
     paro_diag_read_stream,
+    paro_fwht,
     Rotation,
     W4Weight,
     lib,

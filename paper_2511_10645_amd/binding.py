@@ -83,6 +83,7 @@ def lib():
         L.paro_workspace_exchange_bytes_multi.restype = sz
         L.paro_workspace_exchange_bytes_multi.argtypes = [i32, vp, vp, i32]
         L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
+        L.paro_fwht.argtypes = [vp, i64, vp, i64, i32, i32, vp]
         L.paro_diag_read_stream.argtypes = [vp, sz, vp, i32, vp]
         L.paro_diag_mfma_f16.argtypes = [vp, sz, i32, i32, i32, vp]
         L.paro_diag_mfma_f16_flops.argtypes = [i32, i32]
@@ -91,7 +92,7 @@ def lib():
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_rotated_linear_noalloc", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
                      "paro_rotate_scale_quantize_int4", "paro_rotate_scale_quantize_mxfp4",
-                     "paro_diag_read_stream", "paro_diag_mfma_f16"):
+                     "paro_diag_read_stream", "paro_diag_mfma_f16", "paro_fwht"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -124,6 +125,17 @@ def paro_validate_pairs_host(pairs: np.ndarray, group: int = 128) -> int:
     G, K, P, two = p.shape
     assert two == 2
     return lib().paro_validate_pairs_host(p.ctypes.data, G, K, P, group)
+
+
+def paro_fwht(X: torch.Tensor, Y: torch.Tensor | None = None) -> torch.Tensor:
+    """Walsh-Hadamard transform of every row (Sylvester order, scaled by 1/sqrt(n))."""
+    T, ldx = _rows(X)
+    n = X.shape[1]
+    if Y is None:
+        Y = torch.empty((T, n), dtype=torch.float16, device=X.device)
+    _, ldy = _rows(Y)
+    _check(lib().paro_fwht(X.data_ptr(), ldx, Y.data_ptr(), ldy, T, n, _stream()), "paro_fwht")
+    return Y
 
 
 def paro_diag_read_stream(src: torch.Tensor, nbytes: int, blocks: int = 2048) -> None:

@@ -220,3 +220,12 @@ def test_workspace_parts():
     assert L.paro_workspace_bytes(ctypes.byref(r2), ctypes.byref(w), 1) - L.paro_workspace_exchange_bytes(
         ctypes.byref(r2), ctypes.byref(w), 1) == 4096
     assert L.paro_workspace_exchange_bytes(ctypes.byref(_rot(c_in=512)), ctypes.byref(w), 1) == 0     # mismatch: 0
+
+
+def test_fwht_argument_errors():
+    L = paro.lib()
+    assert L.paro_fwht(None, 64, FAKE, 64, 1, 64, None) == 1
+    assert L.paro_fwht(FAKE, 64, FAKE, 64, 1, 48, None) == 2          # not a power of two
+    assert L.paro_fwht(FAKE, 32, FAKE, 64, 1, 64, None) == 2          # ld < n
+    assert L.paro_fwht(FAKE, 65536, FAKE, 65536, 1, 65536, None) == 5
+    assert L.paro_fwht(FAKE + 2, 64, FAKE, 64, 1, 64, None) == 3
