@@ -8,9 +8,15 @@ Inputs are resident in HBM before the timed region.  Decode streams every weight
 token, so consecutive steps use different copies of the layer's weights from a pool larger
 than the 256 MB Infinity Cache - as successive layers of a real model would.
 
-Prints ONE JSON line (see the keys below).  `value` is the achieved algorithmic HBM bandwidth
-of the step: bytes that must move (packed codes + group scales + 4-bit zeros + X + Y + rotation
-parameters at 8 B per pair + channel scales) divided by the time per step.
+Prints ONE JSON line.  `value` is the achieved algorithmic HBM bandwidth of the step: bytes that
+must move (packed codes + group scales + 4-bit zeros + X + Y + rotation parameters at 8 B per
+pair + channel scales) divided by the time per step.  Beside the contract's keys the line carries:
+  per_linear           fused / bare launch times of config 1, each over a walk of the whole pool
+  config2, config4     the same step on the 16-token and the 32B-class shapes (compact records)
+  prefill              config 3 (2048 tokens): rotation pass, MFMA GEMM, fused call per linear
+  rotate_vs_fwht       transform kernel against the Walsh-Hadamard yardstick over channel counts
+  ceiling              what a pure-read kernel and a pure-MFMA loop reach on this machine, so that
+                       every roofline fraction can also be read against the measured ceiling
 """
 from __future__ import annotations
 
@@ -24,10 +30,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# `bench.py --pmc-probe`, scaled by the same counters on a 256 MiB copy (profiles/ has the runs)
-TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000}
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
+# HBM bytes per launch of the dominant fused kernel (gate/up) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of `bench.py --pmc-probe [--config 4]`, scaled by the same counters on a 256 MiB copy
+# (profiles/decode_stream_pmc.md).  Config 2 runs the transform as a launch of its own: no single dominant launch.
+TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 4: 156_700_000}
 
 
 def algorithmic_bytes(c_in: int, c_out: int, T: int, rotated: bool = True, K: int = 8) -> int:
@@ -46,11 +53,12 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="workload config (1: 8B decode b1, 2: b16, 4: 32B b1)")
-    ap.add_argument("--pool-mb", type=int, default=1200, help="minimum total size of the weight-copy pool")
+    ap.add_argument("--config", type=int, default=1, help="headline workload (1: 8B decode b1, 2: b16, 4: 32B b1)")
+    ap.add_argument("--pool-mb", type=int, default=1200, help="minimum total size of each linear's weight-copy pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (config 3) side measurement")
+    ap.add_argument("--no-extras", action="store_true", help="headline and per-linear figures only")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: 3 plain 256 MiB device copies, then on the dominant linear 3 fused "
                          "launches, 3 bare launches and 3 pure-read launches over the same bytes, each on distinct "
@@ -69,42 +77,47 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     paro.lib()
-    cfg = pin.CONFIGS[args.config]
-    T = cfg.tokens[0]
     dev = "cuda"
 
-    # ---- inputs, resident in HBM --------------------------------------------------------
-    lin = []
-    layer_packed_bytes = 0
-    for li_idx, shp in enumerate(cfg.linears):
-        li = pin.make_linear(args.config, li_idx, tokens=T, keep_codes=False)
-        rot = paro.Rotation(li.pairs, li.theta, li.ch_scale)
-        paro.paro_rotation_plan_build(rot)
-        w = paro.W4Weight(li.qweight, li.scales, li.qzeros)
-        paro.paro_w4_repack(w)
-        w.drop_interchange()
-        layer_packed_bytes += w.packed.numel()
-        lin.append(dict(shape=shp, li=li, rot=rot, w=w, x=torch.as_tensor(li.x).to(dev),
-                        y=torch.empty((T, shp.c_out), dtype=torch.float16, device=dev),
-                        bytes=algorithmic_bytes(shp.c_in, shp.c_out, T),
-                        bytes_bare=algorithmic_bytes(shp.c_in, shp.c_out, T, rotated=False)))
-    # every linear cycles through its own pool of >= pool_mb, so that it misses the Infinity Cache
-    # both inside the layer step and when it is timed alone
-    for L in lin:
-        copies = [L["w"]]
-        L["n_copies"] = max(2, -(-args.pool_mb * (1 << 20) // L["w"].packed.numel()))
-        for _ in range(L["n_copies"] - 1):
-            c = paro.W4Weight.__new__(paro.W4Weight)
-            c.c_in, c.c_out = L["w"].c_in, L["w"].c_out
-            c.qweight = c.scales = c.qzeros = c.bias = None
-            c.packed = L["w"].packed.clone()
-            c.c = type(L["w"].c)(c.c_in, c.c_out, 128, None, None, None, None, c.packed.data_ptr())
-            copies.append(c)
-        L["copies"] = copies
-        L["ws"] = paro.Workspace(paro.paro_workspace_bytes(L["rot"], L["w"], T))
-    torch.cuda.synchronize()
+    def clone_weight(w0):
+        c = paro.W4Weight.__new__(paro.W4Weight)
+        c.c_in, c.c_out = w0.c_in, w0.c_out
+        c.qweight = c.scales = c.qzeros = c.bias = None
+        c.packed = w0.packed.clone()
+        c.c = type(w0.c)(c.c_in, c.c_out, 128, None, None, None, None, c.packed.data_ptr())
+        return c
 
-    def step(i: int, which=None, bare: bool = False):
+    def build_layer(config: int, T: int, weights_from=None):
+        """The four linears of a config at T tokens, each with its own pool of >= pool_mb of weight copies (so that it
+        misses the Infinity Cache inside the layer step and when timed alone).  weights_from: reuse another layer's
+        rotations and pools (config 2 has config 1's shapes)."""
+        cfg = pin.CONFIGS[config]
+        lin = []
+        for k, shp in enumerate(cfg.linears):
+            if weights_from is not None:
+                src = weights_from[k]
+                rot, copies, li = src["rot"], src["copies"], None
+                x = torch.as_tensor(pin.make_x(config, k, T, shp.c_in, cfg.n_outlier(shp.c_in))[0]).to(dev)
+            else:
+                li = pin.make_linear(config, k, tokens=T, keep_codes=False)
+                rot = paro.Rotation(li.pairs, li.theta, li.ch_scale)
+                paro.paro_rotation_plan_build(rot)
+                w = paro.W4Weight(li.qweight, li.scales, li.qzeros)
+                paro.paro_w4_repack(w)
+                w.drop_interchange()
+                n_copies = max(2, -(-args.pool_mb * (1 << 20) // w.packed.numel()))
+                copies = [w] + [clone_weight(w) for _ in range(n_copies - 1)]
+                x = torch.as_tensor(li.x).to(dev)
+            lin.append(dict(shape=shp, li=li, rot=rot, copies=copies, n_copies=len(copies), x=x,
+                            y=torch.empty((T, shp.c_out), dtype=torch.float16, device=dev),
+                            ws=paro.Workspace(max(paro.paro_workspace_bytes(rot, copies[0], T),
+                                                  paro.paro_workspace_bytes(None, copies[0], T))),
+                            bytes=algorithmic_bytes(shp.c_in, shp.c_out, T),
+                            bytes_bare=algorithmic_bytes(shp.c_in, shp.c_out, T, rotated=False)))
+        torch.cuda.synchronize()
+        return lin
+
+    def step(lin, i: int, which=None, bare: bool = False):
         for k, L in enumerate(lin):
             if which is not None and k != which:
                 continue
@@ -114,28 +127,28 @@ def main() -> int:
             else:
                 paro.paro_rotated_linear(L["rot"], w, L["x"], L["ws"], L["y"])
 
-    def timed(n_steps: int, warmup: int, which=None, bare: bool = False) -> float:
-        """ms per step over exactly n_steps steps, HIP events on the launch stream."""
+    def graph_ms(fn, n: int, warmup: int) -> float:
+        """ms per call of fn(i) over exactly n calls, HIP events on the launch stream; the n calls are
+        captured once (launch-bound loop) and replayed as one graph."""
         stream = torch.cuda.current_stream()
         for i in range(warmup):
-            step(i, which, bare)
+            fn(i)
         torch.cuda.synchronize()
         start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         if args.no_graph:
             start.record(stream)
-            for i in range(n_steps):
-                step(i, which, bare)
+            for i in range(n):
+                fn(i)
             stop.record(stream)
             torch.cuda.synchronize()
-            return start.elapsed_time(stop) / n_steps
-        # capture the steps once (launch-bound loop), replay as one graph
+            return start.elapsed_time(stop) / n
         g = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(stream)
         with torch.cuda.stream(side):
             with torch.cuda.graph(g, stream=side):
-                for i in range(n_steps):
-                    step(i, which, bare)
+                for i in range(n):
+                    fn(i)
         stream.wait_stream(side)
         g.replay()                      # untimed: first replay uploads the graph
         torch.cuda.synchronize()
@@ -143,7 +156,50 @@ def main() -> int:
         g.replay()
         stop.record(stream)
         torch.cuda.synchronize()
-        return start.elapsed_time(stop) / n_steps
+        return start.elapsed_time(stop) / n
+
+    def time_layer(lin, n_steps: int, warmup: int):
+        """Layer step fused / bare over exactly n_steps steps, and every linear alone over a walk of its WHOLE pool
+        (so that no copy is reused within 1 GB, whatever n_steps is)."""
+        ms_step = graph_ms(lambda i: step(lin, i), n_steps, warmup)
+        ms_bare = graph_ms(lambda i: step(lin, i, bare=True), n_steps, min(warmup, 5))
+        per = {}
+        for k, L in enumerate(lin):
+            n = max(n_steps, L["n_copies"])
+            ms_f = graph_ms(lambda i: step(lin, i, which=k), n, 3)
+            ms_b = graph_ms(lambda i: step(lin, i, which=k, bare=True), n, 3)
+            per[L["shape"].name] = {
+                "us_fused": round(ms_f * 1e3, 3), "us_bare": round(ms_b * 1e3, 3),
+                "gbs_fused": round(L["bytes"] / (ms_f * 1e-3) / 1e9, 1),
+                "gbs_bare": round(L["bytes_bare"] / (ms_b * 1e-3) / 1e9, 1),
+                "overhead_pct": round(100.0 * (ms_f - ms_b) / ms_b, 1), "launches_timed": n,
+            }
+        return ms_step, ms_bare, per
+
+    def read_ceiling_us(L) -> float:
+        """A pure-read kernel over the same weight copies (same bytes, same pool walk)."""
+        nbytes = L["copies"][0].packed.numel() // 16 * 16
+        n = max(20, L["n_copies"])
+        return graph_ms(lambda i: paro.paro_diag_read_stream(L["copies"][i % L["n_copies"]].packed, nbytes), n, 3) * 1e3
+
+    def roofline_of(config: int, lin, per, T: int):
+        dom = max(lin, key=lambda L: L["bytes"])
+        dom_us = per[dom["shape"].name]["us_fused"]
+        achieved = dom["bytes"] / (dom_us * 1e-6) / 1e9
+        read_us = read_ceiling_us(dom)
+        read_bytes = dom["copies"][0].packed.numel()
+        return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(config),
+                "kernel": (f"decode_kernel (fused, split-K, T={T})" if T <= 4 else
+                           f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})")
+                          + f" on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
+                "algorithmic_bytes_per_launch": dom["bytes"], "avg_launch_us": dom_us,
+                "pure_read_us_same_bytes": round(read_us, 3),
+                "frac_of_measured": round((dom["bytes"] / dom_us) / (read_bytes / read_us), 4)}
+
+    cfg = pin.CONFIGS[args.config]
+    T = cfg.tokens[0]
+    lin = build_layer(args.config, T)
 
     if args.pmc_probe:
         dom = max(lin, key=lambda L: L["bytes"])
@@ -153,9 +209,9 @@ def main() -> int:
             dst.copy_(src)
         k = lin.index(dom)
         for i in range(3):
-            step(i, which=k)
+            step(lin, i, which=k)
         for i in range(3, 6):
-            step(i, which=k, bare=True)
+            step(lin, i, which=k, bare=True)
         for i in range(6, 9):
             c = dom["copies"][i % dom["n_copies"]]
             paro.paro_diag_read_stream(c.packed, c.packed.numel() // 16 * 16)
@@ -163,34 +219,33 @@ def main() -> int:
         return 0
 
     # ---- the timed region: exactly --steps steps of the whole layer ---------------------------
-    ms_step = timed(args.steps, args.warmup)
+    ms_step, ms_bare_step, per = time_layer(lin, args.steps, args.warmup)
     step_bytes = sum(L["bytes"] for L in lin)
     value = step_bytes / (ms_step * 1e-3) / 1e9
-
-    # ---- per-linear launch durations (same pool, same launch configuration) ---------------------
-    per = {}
-    for k, L in enumerate(lin):
-        ms_f = timed(args.steps, 5, which=k)
-        ms_b = timed(args.steps, 5, which=k, bare=True)
-        per[L["shape"].name] = {
-            "us_fused": round(ms_f * 1e3, 3), "us_bare": round(ms_b * 1e3, 3),
-            "gbs_fused": round(L["bytes"] / (ms_f * 1e-3) / 1e9, 1),
-            "gbs_bare": round(L["bytes_bare"] / (ms_b * 1e-3) / 1e9, 1),
-        }
-    ms_bare_step = timed(args.steps, 5, bare=True)
     overhead_pct = 100.0 * (ms_step - ms_bare_step) / ms_bare_step
+    roofline = roofline_of(args.config, lin, per, T)
 
-    dom = max(lin, key=lambda L: L["bytes"])
-    dom_us = per[dom["shape"].name]["us_fused"]
-    achieved = dom["bytes"] / (dom_us * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.config),
-                "kernel": (f"decode_kernel (fused, split-K, T={T})" if T <= 4 else
-                           f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})")
-                          + f" on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
-                "algorithmic_bytes_per_launch": dom["bytes"], "avg_launch_us": dom_us}
+    def compact(config: int, layer, Tc: int):
+        ms_f, ms_b, per_c = time_layer(layer, args.steps, 5)
+        nbytes = sum(L["bytes"] for L in layer)
+        return {"workload": f"config {config} ({pin.CONFIGS[config].name}), T={Tc}", "tokens": Tc,
+                "us_fused_layer": round(ms_f * 1e3, 3), "us_bare_layer": round(ms_b * 1e3, 3),
+                "gbs": round(nbytes / (ms_f * 1e-3) / 1e9, 1), "pct_of_hbm_peak": round(100.0 * nbytes / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+                "overhead_pct_vs_bare_w4a16": round(100.0 * (ms_f - ms_b) / ms_b, 2),
+                "per_linear": {k: {"us_fused": v["us_fused"], "us_bare": v["us_bare"]} for k, v in per_c.items()},
+                "roofline": roofline_of(config, layer, per_c, Tc)}
+
+    extras = not args.no_extras
+    config2 = config4 = None
+    if extras and args.config == 1:
+        lin2 = build_layer(2, 16, weights_from=lin)
+        config2 = compact(2, lin2, 16)
+        del lin2
 
     # ---- prefill side (config 3: 2048 tokens): rotation pass + MFMA GEMM per linear ----------------
+    def t_us(fn, n=10):
+        return graph_ms(lambda i: fn(), n, 2) * 1e3
+
     prefill = None
     if not args.no_prefill and args.config in (1, 4):
         pcfg = 3 if args.config == 1 else 4             # config 3 = the 8B shapes at 2048 tokens; config 4 has its own 4096
@@ -199,36 +254,14 @@ def main() -> int:
         tot_fl = tot_us = tot_us_bare = 0.0
         for k, L in enumerate(lin):
             shp = L["shape"]
+            w0 = L["copies"][0]
             xp = torch.as_tensor(pin.make_x(pcfg, k, Tp, shp.c_in, pin.CONFIGS[pcfg].n_outlier(shp.c_in))[0]).to(dev)
             xr = torch.empty_like(xp)
             yp = torch.empty((Tp, shp.c_out), dtype=torch.float16, device=dev)
-            wsp = paro.Workspace(paro.paro_workspace_bytes(L["rot"], L["w"], Tp))
-
-            def t_us(fn, n=10):
-                # graph replay, so that host launch time does not count against the short kernels
-                for _ in range(2):
-                    fn()
-                torch.cuda.synchronize()
-                g = torch.cuda.CUDAGraph()
-                side = torch.cuda.Stream()
-                side.wait_stream(torch.cuda.current_stream())
-                with torch.cuda.stream(side):
-                    with torch.cuda.graph(g, stream=side):
-                        for _ in range(n):
-                            fn()
-                torch.cuda.current_stream().wait_stream(side)
-                g.replay()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                g.replay()
-                e1.record()
-                torch.cuda.synchronize()
-                return e0.elapsed_time(e1) / n * 1e3
-
+            wsp = paro.Workspace(paro.paro_workspace_bytes(L["rot"], w0, Tp))
             us_rot = t_us(lambda: paro.paro_rotate_scale(L["rot"], xp, xr))
-            us_gemm = t_us(lambda: paro.paro_w4a16_linear(L["w"], xr, wsp, yp))
-            us_full = t_us(lambda: paro.paro_rotated_linear(L["rot"], L["w"], xp, wsp, yp))
+            us_gemm = t_us(lambda: paro.paro_w4a16_linear(w0, xr, wsp, yp))
+            us_full = t_us(lambda: paro.paro_rotated_linear(L["rot"], w0, xp, wsp, yp))
             fl = 2.0 * Tp * shp.c_in * shp.c_out
             prefill["per_linear"][shp.name] = {
                 "us_rotate": round(us_rot, 1), "rotate_gbs": round(Tp * shp.c_in * 4 / us_rot / 1e3, 1),
@@ -243,7 +276,7 @@ def main() -> int:
 
     # ---- per-linear transforms (the method gives q / k / v and gate / up their own): one launch --------
     multi = None
-    if not args.no_prefill and args.config == 1:
+    if extras and not args.no_prefill and args.config == 1:
         multi = {}
         xm = lin[0]["x"]
         for name, outs in (("qkv", (4096, 1024, 1024)), ("gate_up", (14336, 14336))):
@@ -259,15 +292,7 @@ def main() -> int:
                                    np.zeros((32, n_out // 8), dtype=np.uint32))
                 paro.paro_w4_repack(w0)
                 w0.drop_interchange()
-                cps = [w0]
-                for _ in range(n_cp - 1):
-                    c = paro.W4Weight.__new__(paro.W4Weight)
-                    c.c_in, c.c_out = w0.c_in, w0.c_out
-                    c.qweight = c.scales = c.qzeros = c.bias = None
-                    c.packed = w0.packed.clone()
-                    c.c = type(w0.c)(c.c_in, c.c_out, 128, None, None, None, None, c.packed.data_ptr())
-                    cps.append(c)
-                pools.append(cps)
+                pools.append([w0] + [clone_weight(w0) for _ in range(n_cp - 1)])
             ys_m = [torch.empty((T, n_out), dtype=torch.float16, device=dev) for n_out in outs]
             ws_s = paro.Workspace(max(paro.paro_workspace_bytes(r, p[0], T) for r, p in zip(rots_m, pools)))
             ws_m = paro.Workspace(paro.paro_workspace_bytes_multi(rots_m, [p[0] for p in pools], T))
@@ -279,29 +304,49 @@ def main() -> int:
             def run_one(i):
                 paro.paro_rotated_linear_multi(rots_m, [p[i % n_cp] for p in pools], xm, ws_m, ys_m)
 
-            res = {}
-            for label, fn in (("us_separate_launches", run_sep), ("us_one_launch", run_one)):
-                g = torch.cuda.CUDAGraph()
-                side = torch.cuda.Stream()
-                side.wait_stream(torch.cuda.current_stream())
-                with torch.cuda.stream(side):
-                    fn(0)
-                    torch.cuda.synchronize()
-                    with torch.cuda.graph(g, stream=side):
-                        for i in range(args.steps):
-                            fn(i)
-                torch.cuda.current_stream().wait_stream(side)
-                g.replay()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                g.replay()
-                e1.record()
-                torch.cuda.synchronize()
-                res[label] = round(e0.elapsed_time(e1) / args.steps * 1e3, 3)
-            res["parts"] = [f"4096->{n}" for n in outs]
-            multi[name] = res
+            multi[name] = {"us_separate_launches": round(graph_ms(run_sep, max(args.steps, n_cp), 2) * 1e3, 3),
+                           "us_one_launch": round(graph_ms(run_one, max(args.steps, n_cp), 2) * 1e3, 3),
+                           "parts": [f"4096->{n}" for n in outs]}
             del pools, rots_m, ys_m
+
+    # ---- the transform kernel against the Walsh-Hadamard yardstick (Section 4.3's figure) ----------------
+    fwht = None
+    if extras and not args.no_prefill:
+        fwht = {"tokens": 2048, "by_channels": {}}
+        for C in (1024, 2048, 4096, 8192, 16384, 32768):
+            pairs, theta, chs = pin.make_rotation(9, 0, C)
+            r = paro.Rotation(pairs, theta, chs)
+            paro.paro_rotation_plan_build(r)
+            n_buf = max(2, min(8, int(600e6 // (2048 * C * 2))))
+            xs = [torch.randn(2048, C, device=dev, dtype=torch.float16) for _ in range(n_buf)]
+            ys = [torch.empty_like(xb) for xb in xs]
+            us_r = graph_ms(lambda i: paro.paro_rotate_scale(r, xs[i % n_buf], ys[i % n_buf]), 20, 2) * 1e3
+            us_h = graph_ms(lambda i: paro.paro_fwht(xs[i % n_buf], ys[i % n_buf]), 20, 2) * 1e3
+            fwht["by_channels"][str(C)] = {"us_rotate_k8": round(us_r, 1), "us_fwht": round(us_h, 1),
+                                           "rotate_gbs": round(2048 * C * 4 / us_r / 1e3, 1),
+                                           "speedup_over_fwht": round(us_h / us_r, 2)}
+            del xs, ys
+
+    # ---- measured ceilings of this machine ---------------------------------------------------------------
+    ceiling = None
+    if extras:
+        ceiling = {"pure_read_us": {L["shape"].name: round(read_ceiling_us(L), 3) for L in lin}}
+        ceiling["pure_read_layer_us"] = round(sum(ceiling["pure_read_us"].values()), 3)
+        ceiling["frac_of_measured_layer"] = round(ceiling["pure_read_layer_us"] / (ms_step * 1e3), 4)
+        out_f = torch.empty(1024 * 256, dtype=torch.float32, device=dev)
+        mf = {}
+        for label, rnd in (("constant_operands", False), ("random_operands", True)):
+            fl = paro.paro_diag_mfma_f16(out_f, 1024, 2000, rnd)      # warm-up
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = paro.paro_diag_mfma_f16(out_f, 1024, 2000, rnd)
+            e1.record()
+            torch.cuda.synchronize()
+            mf[label] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        ceiling["mfma_f16_tflops"] = mf
+        if prefill:
+            prefill["frac_of_measured_mfma_random"] = round(prefill["layer_tflops"] / mf["random_operands"], 4)
 
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
     cpu = None
@@ -325,6 +370,14 @@ def main() -> int:
                "sample": f"{reps} full steps (all 4 linears, T={T}) of the fp64 oracle, {dt * 1e3:.1f} ms per step",
                "ms_per_step": round(dt * 1e3, 2)}
 
+    # the 32B-class layer last: its pools replace config 1's in HBM
+    if extras and args.config == 1:
+        del lin
+        torch.cuda.empty_cache()
+        lin4 = build_layer(4, 1)
+        config4 = compact(4, lin4, 1)
+        del lin4
+
     out = {
         "metric": "fused rotated-W4A16 linear: decode HBM GB/s",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -339,7 +392,9 @@ def main() -> int:
         "overhead_pct_vs_bare_w4a16": round(overhead_pct, 2),
         "ms_per_step_bare": round(ms_bare_step, 6),
         "per_linear": per,
+        "config2": config2, "config4": config4,
         "prefill": prefill, "own_transform_per_projection": multi,
+        "rotate_vs_fwht": fwht, "ceiling": ceiling,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -158,11 +158,11 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, c
             }
         }
     };
-    // Fully unrolled (n_iter <= kMaxIter, guaranteed by the host): straight-line code with uniform
+    // Fully unrolled (n_iter <= decode_max_iter(W), guaranteed by the host): straight-line code with uniform
     // early exits and no back edge, so the waits inserted by the compiler are exact - a stage is
     // awaited while the two younger ones stay in flight.
 #pragma unroll
-    for (int i = 0; i < kMaxIter; i += 3) {
+    for (int i = 0; i < decode_max_iter(W); i += 3) {
         load_stage(blob, a, tile_of(i + 2), ks, lane, st2);
         emit(st0, tile_of(i));
         if (i + 1 >= n_iter) break;
@@ -232,7 +232,7 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
     if (nb < 1) nb = 1;
     int tpb = (NT + nb - 1) / nb;
     tpb = (tpb + d.waves - 1) / d.waves * d.waves;           // whole rounds of the block's waves
-    if (tpb > kMaxIter * d.waves) tpb = kMaxIter * d.waves;
+    if (tpb > decode_max_iter(d.waves) * d.waves) tpb = decode_max_iter(d.waves) * d.waves;
     d.tiles_per_block = tpb;
     d.nb = (NT + tpb - 1) / tpb;
     if (d.waves > kDecWaves && d.ks * d.nb > 256) {           // would not fit one round of 8-wave blocks
@@ -242,7 +242,7 @@ DecodeGeometry decode_geometry(int c_in, int c_out, int T, int target_blocks)
         if (nb < 1) nb = 1;
         tpb = (NT + nb - 1) / nb;
         tpb = (tpb + d.waves - 1) / d.waves * d.waves;
-        if (tpb > kMaxIter * d.waves) tpb = kMaxIter * d.waves;
+        if (tpb > decode_max_iter(d.waves) * d.waves) tpb = decode_max_iter(d.waves) * d.waves;
         d.tiles_per_block = tpb;
         d.nb = (NT + tpb - 1) / tpb;
     }

@@ -17,7 +17,10 @@ constexpr int kSliceCh = kSliceGroups * kGroup;      // 512
 constexpr int kXPad = 8;                             // halfs of padding per LDS row
 constexpr int kReducePerThread = 4;                   // partial words requested per thread and round
 constexpr int kReduceWords = kReducePerThread * 256;  // partial words gathered per reduction round (LDS floats)
-constexpr int kMaxIter = 9;                          // tiles per wave (unrolled stream), multiple of 3
+// tiles per wave of the K-major kernel (unrolled stream, multiple of 3).  Longer streams in 8-wave blocks, so that
+// 5120 -> 55296 fits one round of blocks, were measured and are slower (32.0 against 31.1 us; 27648 -> 5120: 21.8
+// against 18.2 us).
+__host__ __device__ constexpr int decode_max_iter(int) { return 9; }
 constexpr int kSpinLimit = 1 << 22;                  // bounded wait for a partial word to fill
 
 struct DecodeArgs {

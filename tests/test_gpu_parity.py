@@ -329,9 +329,26 @@ def test_identity_transform_equals_bare_linear(P):
 
 # ----------------------------------------------------------------------------- full configs
 
+def _column_subset(li, cols):
+    """The linear restricted to the output columns `cols` (a multiple of 8 of them), interchange layout."""
+    z = oracle.unpack_zeros(li.qzeros)[:, cols]
+    return np.ascontiguousarray(li.qweight[cols]), np.ascontiguousarray(li.scales[:, cols]), pin.pack_nibbles_u32(z)
+
+
+def _check_block(got, u, qw, sc, qz, c_in, label):
+    """Every element of `got` ([rows of u] x [all columns of the given weight]) against the oracle."""
+    y = oracle.linear(u, qw, sc, qz)
+    allowed = linear_allowed(oracle.row_sqnorms(qw, sc, qz), u)
+    worst = float((np.abs(got.astype(np.float64) - y) / allowed).max())
+    say(f"  {label}: worst err/allowed = {worst:.3f} over {y.size} outputs")
+    assert worst <= 1.0, label
+
+
 def _full_config_case(P, config, linear, T, n_samples=4096):
-    """Full-size check in the launch configuration the benchmark times: rotation against the
-    oracle on every element, linear outputs on sampled (t, n) computed one by one."""
+    """Full-size check in the launch configuration the benchmark times.  Rotation: every element against the
+    oracle, and the strict 2-ulp statistic.  Linear outputs: up to 16 tokens EVERY output; beyond that whole stripes
+    (all outputs of the first and the last 32 tokens; all tokens of 256 output columns: the first 64, the last 128 -
+    the last output tile and the separately launched tail - and 64 spread over the middle) plus random samples."""
     li = pin.make_linear(config, linear, tokens=T, keep_codes=False)
     say(f"config {config} {li.shape.name} T={T} C={li.c_in} N={li.c_out}")
     u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
@@ -341,29 +358,37 @@ def _full_config_case(P, config, linear, T, n_samples=4096):
     ok, stats = rotation_check(xr, u)
     say(f"  rotation {stats}")
     assert ok, stats
+    assert stats["frac_within_2ulp_strict"] >= 0.9999, stats
     ws = P.Workspace(P.paro_workspace_bytes(rot, w, T))
     w.drop_interchange()
     got = P.paro_rotated_linear(rot, w, x, ws).cpu().numpy()
+    assert np.isfinite(got.astype(np.float32)).all()
+    # the bare linear on the rotated fp16 activations (oracle fed with those bits)
+    yb = P.paro_w4a16_linear(w, dev(xr), ws).cpu().numpy()
+    ub = xr.astype(np.float64)
+    assert ws.error_word() == 0
+    if T <= 16:
+        _check_block(got, u, li.qweight, li.scales, li.qzeros, li.c_in, "fused, every output")
+        _check_block(yb, ub, li.qweight, li.scales, li.qzeros, li.c_in, "bare, every output")
+        return
+    rows = np.r_[0:32, T - 32:T]
+    _check_block(got[rows], u[rows], li.qweight, li.scales, li.qzeros, li.c_in, "fused, all outputs of 64 tokens")
+    _check_block(yb[rows], ub[rows], li.qweight, li.scales, li.qzeros, li.c_in, "bare, all outputs of 64 tokens")
+    N = li.c_out
+    cols = np.unique(np.r_[0:64, N - 128:N, np.linspace(64, N - 129, 64).astype(np.int64)])
+    cols = cols[: len(cols) // 8 * 8]
+    qw, sc, qz = _column_subset(li, cols)
+    _check_block(got[:, cols], u, qw, sc, qz, li.c_in, f"fused, all tokens of {len(cols)} columns")
+    _check_block(yb[:, cols], ub, qw, sc, qz, li.c_in, f"bare, all tokens of {len(cols)} columns")
     rng = np.random.default_rng(config * 10 + linear)
     ns = min(n_samples, T * li.c_out)
     t_idx = rng.integers(0, T, ns)
     n_idx = rng.integers(0, li.c_out, ns)
-    n_idx[:16] = np.arange(li.c_out - 16, li.c_out)                  # always include the last tile
     ys, ww = oracle.linear_samples(u, li.qweight, li.scales, li.qzeros, t_idx, n_idx)
     allowed = 5e-3 * np.sqrt(ww) * np.linalg.norm(u, axis=1)[t_idx] / np.sqrt(li.c_in)
-    err = np.abs(got[t_idx, n_idx].astype(np.float64) - ys)
-    worst = float((err / allowed).max())
-    say(f"  linear worst err/allowed = {worst:.3f} over {ns} samples")
+    worst = float((np.abs(got[t_idx, n_idx].astype(np.float64) - ys) / allowed).max())
+    say(f"  fused, {ns} random samples: worst err/allowed = {worst:.3f}")
     assert worst <= 1.0
-    assert np.isfinite(got.astype(np.float32)).all()
-    # the bare linear on the rotated fp16 activations, same samples (oracle fed with those bits)
-    yb = P.paro_w4a16_linear(w, dev(xr), ws).cpu().numpy()
-    ub = xr.astype(np.float64)
-    ys_b, _ = oracle.linear_samples(ub, li.qweight, li.scales, li.qzeros, t_idx, n_idx)
-    allowed_b = 5e-3 * np.sqrt(ww) * np.linalg.norm(ub, axis=1)[t_idx] / np.sqrt(li.c_in)
-    worst_b = float((np.abs(yb[t_idx, n_idx].astype(np.float64) - ys_b) / allowed_b).max())
-    say(f"  bare linear worst err/allowed = {worst_b:.3f}")
-    assert worst_b <= 1.0
 
 
 @pytest.mark.parametrize("linear", [0, 1, 2, 3])
