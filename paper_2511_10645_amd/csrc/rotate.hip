@@ -12,6 +12,7 @@
 //   weight into a "plan" (paro_rotation_plan_build).
 #include "paro_internal.h"
 #include "rotate_lane.h"
+#include <type_traits>
 
 namespace paro {
 
@@ -158,6 +159,16 @@ hipError_t launch_plan_build(const paro_rotation &rot, void *plan_out, hipStream
 // ------------------------------------------------------------------------------------------
 constexpr int kRotWaves = 4;   // waves per block
 constexpr int kRotTU = 4;      // tokens in flight per wave
+constexpr int kRotMaxBatches = 8;   // batches of kRotTU tokens per wave (the batch loop is unrolled)
+
+// f(0), f(1), ... while f returns true, at most N times; nested, so that stopping is one forward jump
+template <int N, class F, int I = 0>
+__device__ __forceinline__ void static_while_rot(F &&f)
+{
+    if constexpr (I < N) {
+        if (f(std::integral_constant<int, I>{})) static_while_rot<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
 
 // A wave owns one group and a run of tokens.  Global traffic is one coalesced 4-byte access per
 // lane, token and direction (a group row is 256 contiguous bytes); the permutation between
@@ -209,7 +220,13 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
     auto lo_pair = [](uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); };
     auto hi_pair = [](uint32_t x, uint32_t y) { return (x >> 16) | (y & 0xffff0000u); };
 
-    for (int t = 0; t < n_tok; t += kRotTU) {
+    // Unrolled over the wave's batches (at most kRotMaxBatches, guaranteed by the launcher) with one early exit:
+    // with a back edge the compiler waits for ALL outstanding memory operations at the loop head, i.e. for the
+    // previous batch's stores to be acknowledged before the next batch may be touched; straight-line code waits
+    // for the loads only.
+    static_while_rot<kRotMaxBatches>([&](auto I) {
+        constexpr int t = I * kRotTU;
+        if (t >= n_tok) return false;
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) nxt[u] = __builtin_amdgcn_raw_buffer_load_b32(xr, v4 + (t + kRotTU + u) * row_x, 0, 0);
         const u32x4v in = {lo_pair(cur[0], cur[1]), lo_pair(cur[2], cur[3]), hi_pair(cur[0], cur[1]), hi_pair(cur[2], cur[3])};
@@ -240,7 +257,8 @@ __global__ __launch_bounds__(kRotWaves * 64) void rotate_planned_kernel(const ui
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < kRotTU; ++u) cur[u] = nxt[u];
-    }
+        return true;
+    });
 }
 
 template <int K>
@@ -250,7 +268,7 @@ static hipError_t launch_rotate_k(const paro_rotation &rot, const paro_half_t *X
     int G = rot.c_in / kGroup;
     // the plan (7.4 KB per wave at K = 8) is re-read by every wave: long token runs per wave, as
     // long as there are still enough waves to fill 256 CUs several times over
-    int tpw = 32;
+    int tpw = kRotMaxBatches * kRotTU;
     while (tpw > kRotTU && (int64_t)G * ((T + tpw - 1) / tpw) < 4096) tpw >>= 1;
     int waves_t = (T + tpw - 1) / tpw;
     dim3 grid(G, (waves_t + kRotWaves - 1) / kRotWaves);
