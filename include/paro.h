@@ -59,7 +59,9 @@ typedef struct {
     int32_t pairs_per_layer;  /* slots per layer and group, 1..64                              */
     const int16_t *pairs;     /* [c_in/group][n_layers][pairs_per_layer][2]; 0-based indices
                                  LOCAL to the group; i == j marks an empty slot; within one
-                                 layer and group no channel may appear twice (Def. 1)          */
+                                 layer and group no channel may appear twice (Def. 1): a table
+                                 that breaks this, or holds an index outside the group, makes
+                                 every output of that group NaN, with or without a plan        */
     const float *theta;       /* [c_in/group][n_layers][pairs_per_layer], radians              */
     const paro_half_t *ch_scale; /* [c_in] multiplier applied to x; NULL = all ones            */
     int32_t scale_order;      /* 0: scale, then rotate (Eq. 8 inverted; default)

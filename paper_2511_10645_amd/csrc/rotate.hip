@@ -32,6 +32,7 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
     __shared__ uint8_t s_src[kMaxLayers][64];                         // lane to pull from after layer l
     __shared__ uint8_t s_keep[kMaxLayers][64], s_send[kMaxLayers][64];
     __shared__ uint8_t s_tmp[3][128];
+    __shared__ int s_bad;                                             // the table violates Def. 1 (or an index is out of range)
 
     const int g = blockIdx.x;
     const int lane = threadIdx.x;
@@ -42,13 +43,14 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
     // no pair of the layer names are paired among themselves with the identity rotation.
     if (lane == 0) {
         uint8_t *used = s_tmp[0];
+        s_bad = 0;
         for (int l = 0; l < n_layers; ++l) {
             for (int c = 0; c < kGroup; ++c) used[c] = 0;
             int cnt = 0;
             for (int p = 0; p < ppl && cnt < 64; ++p) {
                 int i = gp[((size_t)l * ppl + p) * 2], j = gp[((size_t)l * ppl + p) * 2 + 1];
-                if (i == j || i < 0 || j < 0 || i >= kGroup || j >= kGroup) continue;
-                if (used[i] || used[j]) continue;   // table violates Def. 1: ignore the slot
+                if (i == j) continue;                                   // empty slot
+                if (i < 0 || j < 0 || i >= kGroup || j >= kGroup || used[i] || used[j]) { s_bad = 1; continue; }
                 used[i] = used[j] = 1;
                 s_pi[l][cnt] = (uint8_t)i; s_pj[l][cnt] = (uint8_t)j; s_slot[l][cnt] = (int16_t)p;
                 ++cnt;
@@ -132,6 +134,9 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
         if (scale_order == 0) { sia = (float)cs[(size_t)g * kGroup + in_a]; sib = (float)cs[(size_t)g * kGroup + in_b]; }
         else                  { soa = (float)cs[(size_t)g * kGroup + out_a]; sob = (float)cs[(size_t)g * kGroup + out_b]; }
     }
+    // A pair table that is not an independent rotation (Def. 1) has no defined result: the group's outputs
+    // become NaN on every path that uses this plan, as they do on the planless path.
+    if (s_bad) sia = sib = soa = sob = __builtin_nanf("");
     out[1 * 64 + lane] = __float_as_uint(sia); out[2 * 64 + lane] = __float_as_uint(sib);
     out[3 * 64 + lane] = __float_as_uint(soa); out[4 * 64 + lane] = __float_as_uint(sob);
     for (int l = 0; l < n_layers; ++l) {
@@ -307,14 +312,20 @@ __global__ __launch_bounds__(64) void rotate_generic_kernel(const int16_t *__res
     __shared__ float s_c[kMaxLayers][64], s_s[kMaxLayers][64];
     __shared__ int16_t s_i[kMaxLayers][64], s_j[kMaxLayers][64];
     __shared__ float s_u[kGroup];
+    __shared__ int s_claims[kGroup];                                  // slots of the current layer that name a channel
+    __shared__ int s_bad;                                             // Def. 1 violated / index out of range: outputs NaN
     const int g = blockIdx.x, lane = threadIdx.x;
+    if (lane == 0) s_bad = 0;
     for (int l = 0; l < n_layers; ++l) {
+        s_claims[lane] = 0; s_claims[64 + lane] = 0;
+        __syncthreads();
         int i = 0, j = 0;
         float c = 1.0f, s = 0.0f;
         if (lane < ppl) {
             size_t k = ((size_t)g * n_layers + l) * ppl + lane;
             i = pairs[2 * k]; j = pairs[2 * k + 1];
-            if (i < 0 || j < 0 || i >= kGroup || j >= kGroup) { i = 0; j = 0; }
+            if (i < 0 || j < 0 || i >= kGroup || j >= kGroup) { i = 0; j = 0; s_bad = 1; }
+            if (i != j && (atomicAdd(&s_claims[i], 1) > 0 || atomicAdd(&s_claims[j], 1) > 0)) { s_bad = 1; i = j = 0; }
             if (i != j) {
                 double sd, cd;
                 sincos((double)theta[k], &sd, &cd);
@@ -326,6 +337,7 @@ __global__ __launch_bounds__(64) void rotate_generic_kernel(const int16_t *__res
     float sc0 = 1.0f, sc1 = 1.0f;
     if (ch_scale) { sc0 = (float)ch_scale[(size_t)g * kGroup + lane]; sc1 = (float)ch_scale[(size_t)g * kGroup + 64 + lane]; }
     __syncthreads();
+    const bool bad = s_bad != 0;
     const int t0 = blockIdx.y * tokens_per_block, t1 = min(T, t0 + tokens_per_block);
     for (int t = t0; t < t1; ++t) {
         float v0 = (float)X[(size_t)t * ldx + (size_t)g * kGroup + lane];
@@ -346,8 +358,8 @@ __global__ __launch_bounds__(64) void rotate_generic_kernel(const int16_t *__res
         }
         v0 = s_u[lane]; v1 = s_u[64 + lane];
         if (scale_order == 1) { v0 *= sc0; v1 *= sc1; }
-        Xr[(size_t)t * ldxr + (size_t)g * kGroup + lane] = (_Float16)v0;
-        Xr[(size_t)t * ldxr + (size_t)g * kGroup + 64 + lane] = (_Float16)v1;
+        Xr[(size_t)t * ldxr + (size_t)g * kGroup + lane] = (_Float16)(bad ? __builtin_nanf("") : v0);
+        Xr[(size_t)t * ldxr + (size_t)g * kGroup + 64 + lane] = (_Float16)(bad ? __builtin_nanf("") : v1);
         __syncthreads();
     }
 }

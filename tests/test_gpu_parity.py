@@ -255,6 +255,25 @@ def test_linear_with_padded_rows(P, T, fused):
     assert (xbuf[:, :8] == 3.0).all() and (xbuf[:, 8:8 + c_in].cpu().numpy() == li.x).all()          # input untouched
 
 
+def test_pair_table_that_breaks_def1_gives_nan_on_both_paths(P):
+    """A channel named twice in one layer (or an index outside the group) has no defined result: the affected
+    group comes out as NaN with and without a plan, the other groups are untouched."""
+    li = pin.make_custom(55, 3, 384, 64)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    bad = li.pairs.copy()
+    bad[1, 2, 7, 1] = bad[1, 2, 9, 0]                                  # group 1, layer 2: a channel twice
+    bad[2, 5, 0, 0] = 128                                              # group 2: index out of range
+    assert P.paro_validate_pairs_host(bad) != 0
+    for plan in (True, False):
+        rot = P.Rotation(bad, li.theta, li.ch_scale)
+        if plan:
+            P.paro_rotation_plan_build(rot)
+        got = P.paro_rotate_scale(rot, dev(li.x)).cpu().numpy()
+        assert np.isnan(got[:, 128:384].astype(np.float32)).all(), plan
+        ok, stats = rotation_check(got[:, :128], u[:, :128])
+        assert ok, (plan, stats)
+
+
 def test_graph_replays_match_eager(P):
     """The calls only enqueue kernels (no memset nodes, no allocation), so a captured sequence can be replayed:
     every replay, with eager work in between, must reproduce the eager bits and leave the workspace zero-filled."""
