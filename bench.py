@@ -34,7 +34,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
 # HBM bytes per launch of the dominant fused kernel (gate/up) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --pmc-probe [--config 4]`, scaled by the same counters on a 256 MiB copy
 # (profiles/decode_stream_pmc.md).  Config 2 runs the transform as a launch of its own: no single dominant launch.
-TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 4: 156_700_000}
+TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 4: 156_600_000}
 
 
 def algorithmic_bytes(c_in: int, c_out: int, T: int, rotated: bool = True, K: int = 8) -> int:
@@ -177,10 +177,11 @@ def main() -> int:
         return ms_step, ms_bare, per
 
     def read_ceiling_us(L) -> float:
-        """A pure-read kernel over the same weight copies (same bytes, same pool walk)."""
+        """A pure-read kernel over the same weight copies (same bytes, same pool walk), best of several grid sizes."""
         nbytes = L["copies"][0].packed.numel() // 16 * 16
         n = max(20, L["n_copies"])
-        return graph_ms(lambda i: paro.paro_diag_read_stream(L["copies"][i % L["n_copies"]].packed, nbytes), n, 3) * 1e3
+        return min(graph_ms(lambda i: paro.paro_diag_read_stream(L["copies"][i % L["n_copies"]].packed, nbytes, blocks), n, 3)
+                   for blocks in (512, 1024, 2048, 4096)) * 1e3
 
     def roofline_of(config: int, lin, per, T: int):
         dom = max(lin, key=lambda L: L["bytes"])

@@ -9,7 +9,8 @@
 // request for the next tile is issued before the multiplication of the current one starts.
 // Deeper staging was measured and is slower on this part (gate/up 4096 -> 28672, one token:
 // 12.6 us with 3 stages, 13.0 with 4, 14.4 with 6): what bounds the stream is not the number of
-// bytes a wave has requested.  One block per compute unit; for one token the partial sums of a
+// bytes a wave has requested.  Nor is it the order of the tiles: a walk in which the blocks of the
+// grid read one contiguous window of the blob at any moment (tiles nb, nb + grid, ...) is no faster.  One block per compute unit; for one token the partial sums of a
 // tile take 64 bytes of LDS per wave, so a block can run up to 16 tiles per wave and every shape
 // of the benchmark fits one round of blocks.
 //
