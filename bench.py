@@ -34,7 +34,9 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
 # HBM bytes per launch of the dominant fused kernel (gate/up) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --pmc-probe [--config 4]`, scaled by the same counters on a 256 MiB copy
 # (profiles/decode_stream_pmc.md).  Config 2 runs the transform as a launch of its own: no single dominant launch.
-TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 4: 156_600_000}
+# Config 4's gate/up takes the two-launch route (rotation pass + bare kernel): the bare launch's counters (147.5 MB read,
+# 0.1 MB written) plus the pass's own 0.3 MB (plan, X, X').
+TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 4: 147_900_000}
 
 
 def algorithmic_bytes(c_in: int, c_out: int, T: int, rotated: bool = True, K: int = 8) -> int:
@@ -183,6 +185,11 @@ def main() -> int:
         return min(graph_ms(lambda i: paro.paro_diag_read_stream(L["copies"][i % L["n_copies"]].packed, nbytes, blocks), n, 3)
                    for blocks in (512, 1024, 2048, 4096)) * 1e3
 
+    def two_launches(L, T: int) -> bool:
+        # the call asks for a scratch part exactly when the transform runs as a pass of its own
+        w = L["copies"][0]
+        return paro.paro_workspace_bytes(L["rot"], w, T) > paro.paro_workspace_exchange_bytes(L["rot"], w, T)
+
     def roofline_of(config: int, lin, per, T: int):
         dom = max(lin, key=lambda L: L["bytes"])
         dom_us = per[dom["shape"].name]["us_fused"]
@@ -191,8 +198,8 @@ def main() -> int:
         read_bytes = dom["copies"][0].packed.numel()
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(config),
-                "kernel": (f"decode_kernel (fused, split-K, T={T})" if T <= 4 else
-                           f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})")
+                "kernel": (f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})" if two_launches(dom, T) else
+                           f"decode_kernel (fused, split-K, T={T})")
                           + f" on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
                 "algorithmic_bytes_per_launch": dom["bytes"], "avg_launch_us": dom_us,
                 "pure_read_us_same_bytes": round(read_us, 3),

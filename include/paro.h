@@ -148,7 +148,8 @@ paro_status paro_w4_repack(const paro_w4_weight *w, void *packed_out, void *stre
  *     was cancelled or faulted) zero-fill the exchange part again before the next call.
  *   - the scratch part, the LAST paro_workspace_bytes() - paro_workspace_exchange_bytes() bytes
  *     of the buffer as given by ws_bytes (rounded down to 256): transformed activations when the
- *     rotation runs as a pass of its own (T > 4, or no plan / no repacked weight), and fp32
+ *     rotation runs as a pass of its own (T > 4, no plan / no repacked weight, or a shape on
+ *     which two launches are faster than the exchange of the fused kernel), and fp32
  *     partial tiles where the GEMM splits K (some tens to hundreds of tokens).  No requirement
  *     before a call, any contents after it.
  * paro_workspace_bytes() is the sum: enough for a buffer that only serves calls of that one shape.
@@ -186,9 +187,10 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
  * paro_rotated_linear with the exchange part of the workspace held in a static device array of
  * PARO_NOALLOC_SCRATCH_BYTES inside the library (one copy per GPU the library runs on, held until
  * the process ends; zero when the library is loaded, and left consistent by every call like a
- * caller-owned exchange part).  The call allocates and frees nothing.  It serves the calls that
- * need no scratch part - the fused decode path: rotation planned, weight repacked, T <= 4 -
- * and returns PARO_ERR_UNSUPPORTED for the others, PARO_ERR_WORKSPACE when the exchange part of
+ * caller-owned exchange part).  The call allocates and frees nothing.  It always takes the fused
+ * decode kernel (rotation planned, weight repacked, T <= 4), which needs no scratch part - also
+ * on the shapes where paro_rotated_linear prefers two launches; there the two calls agree to
+ * rounding, elsewhere bit for bit - and returns PARO_ERR_UNSUPPORTED for the others, PARO_ERR_WORKSPACE when the exchange part of
  * the shape exceeds PARO_NOALLOC_SCRATCH_BYTES (4 MiB covers K-slices x T x c_out x 4 bytes of
  * every benchmark shape at one token and of the 8B-class shapes at 4).  All calls on one GPU share
  * that GPU's array: calls that overlap in time on one GPU race, exactly as two calls sharing a

@@ -48,10 +48,24 @@ inline bool fast_weight(const paro_w4_weight *w)
     return w->packed && (w->c_in / kGroup) % kSliceGroups == 0 && packed_blob_bytes(w->c_in, w->c_out) < (1ull << 31);
 }
 
-// the K-major decode kernel hosts the rotation: planned rotation, repacked weight, few tokens
-inline bool fused_decode(const paro_rotation *rot, const paro_w4_weight *w, int T)
+// The K-major decode kernel can host the rotation: planned rotation, repacked weight, few tokens.
+inline bool can_fuse_decode(const paro_rotation *rot, const paro_w4_weight *w, int T)
 {
     return rot && rot->plan && fast_weight(w) && T <= kFuseMaxTokens;
+}
+
+// Whether it does.  Its blocks exchange KS x T x c_out fp32 partial sums at the end, which costs a
+// device-scope round trip plus the volume; a rotation pass followed by the bare kernel (all K-slices
+// in one block, no exchange up to 6144 channels) costs one more launch, 2.6 us on the small
+// linears and well under 1 us in front of a long weight stream.  Measured break-even on MI355X
+// (4096 / 5120 / 14336 / 27648 input channels, 4096 .. 55296 outputs): 1 - 2 MB of partial sums
+// for one token, 0.5 MB for 2..4 tokens.  `always`: for callers without a scratch part.
+constexpr size_t kFusePartialOne = 3u << 19, kFusePartialFew = 1u << 19;
+inline bool fused_decode(const paro_rotation *rot, const paro_w4_weight *w, int T, bool always = false)
+{
+    if (!can_fuse_decode(rot, w, T)) return false;
+    if (always) return true;
+    return decode_geometry(w->c_in, w->c_out, T).partial_bytes <= (T == 1 ? kFusePartialOne : kFusePartialFew);
 }
 
 paro_status check_io(const void *X, int64_t ldx, int width_x, const void *Y, int64_t ldy, int width_y, int T,
@@ -77,7 +91,7 @@ struct WsLayout {
     size_t total;
 };
 
-WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
+WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T, bool always_fuse = false)
 {
     WsLayout L{0, 0, 0, 0, 0};
     if (fast_weight(w)) {
@@ -88,7 +102,7 @@ WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T)
         L.exchange_bytes = (rot || part) ? kWsPartialOff + round_up(part, 256) : 0;
         if (T > kDecodeMaxTokens) L.gemm_bytes = round_up(gemm_scratch_bytes(*w, T), 256);
     }
-    const bool fused = fused_decode(rot, w, T);
+    const bool fused = fused_decode(rot, w, T, always_fuse);
     L.xr_bytes = (rot && !fused) ? round_up((size_t)T * w->c_in * 2, 256) : 0;
     L.scratch_bytes = L.xr_bytes + L.gemm_bytes;
     L.total = L.exchange_bytes + L.scratch_bytes;
@@ -318,8 +332,9 @@ paro_status paro_w4a16_linear(const paro_w4_weight *w, const paro_half_t *X, int
                       L.gemm_bytes, (hipStream_t)stream);
 }
 
-paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X, int64_t ldx,
-                                paro_half_t *Y, int64_t ldy, int32_t T, void *ws, size_t ws_bytes, void *stream)
+static paro_status rotated_linear(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X, int64_t ldx,
+                                  paro_half_t *Y, int64_t ldy, int32_t T, void *ws, size_t ws_bytes, void *stream,
+                                  bool always_fuse)
 {
     paro_status st = check_rotation(rot);
     if (st != PARO_OK) return st;
@@ -328,12 +343,12 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
     if (rot->c_in != w->c_in) return PARO_ERR_SHAPE;
     st = check_io(X, ldx, w->c_in, Y, ldy, w->c_out, T, 8);
     if (st != PARO_OK) return st;
-    WsLayout L = ws_layout(rot, w, T);
+    WsLayout L = ws_layout(rot, w, T, always_fuse);
     if (L.total && (!ws || ws_bytes < L.total)) return PARO_ERR_WORKSPACE;
     if (L.total && !aligned(ws, 256)) return PARO_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
 
-    if (fused_decode(rot, w, T)) return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
+    if (fused_decode(rot, w, T, always_fuse)) return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
 
     // two passes: transform into the workspace, then the bare linear
     paro_half_t *xr = (paro_half_t *)ws_scratch(ws, ws_bytes, L);
@@ -344,6 +359,14 @@ paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *
                       L.gemm_bytes, s);
 }
 
+paro_status paro_rotated_linear(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X, int64_t ldx,
+                                paro_half_t *Y, int64_t ldy, int32_t T, void *ws, size_t ws_bytes, void *stream)
+{
+    return rotated_linear(rot, w, X, ldx, Y, ldy, T, ws, ws_bytes, stream, false);
+}
+
+// Always the kernel that hosts the rotation where it can (it needs no scratch part), also for the
+// shapes on which paro_rotated_linear prefers the two-pass route.
 paro_status paro_rotated_linear_noalloc(const paro_rotation *rot, const paro_w4_weight *w, const paro_half_t *X,
                                         int64_t ldx, paro_half_t *Y, int64_t ldy, int32_t T, void *stream)
 {
@@ -354,13 +377,13 @@ paro_status paro_rotated_linear_noalloc(const paro_rotation *rot, const paro_w4_
     if (rot->c_in != w->c_in) return PARO_ERR_SHAPE;
     st = check_io(X, ldx, w->c_in, Y, ldy, w->c_out, T, 8);
     if (st != PARO_OK) return st;
-    const WsLayout L = ws_layout(rot, w, T);
+    const WsLayout L = ws_layout(rot, w, T, true);
     if (L.scratch_bytes) return PARO_ERR_UNSUPPORTED;                 // needs a scratch part: only the allocating call serves it
     if (L.exchange_bytes > kStaticScratchBytes) return PARO_ERR_WORKSPACE;
     void *ws = nullptr;
     st = static_scratch(&ws);
     if (st != PARO_OK) return st;
-    return paro_rotated_linear(rot, w, X, ldx, Y, ldy, T, ws, kStaticScratchBytes, stream);
+    return rotated_linear(rot, w, X, ldx, Y, ldy, T, ws, kStaticScratchBytes, stream, true);
 }
 
 paro_status paro_w4_unpack_codes(const paro_w4_weight *w, uint8_t *codes, void *stream)

@@ -222,6 +222,25 @@ def test_workspace_parts():
     assert L.paro_workspace_exchange_bytes(ctypes.byref(_rot(c_in=512)), ctypes.byref(w), 1) == 0     # mismatch: 0
 
 
+def test_fused_or_two_launches_by_shape():
+    """Up to 4 tokens the decode kernel hosts the rotation (no scratch part) unless the partial sums its blocks
+    would exchange (K-slices x T x c_out x 4 bytes) exceed 1.5 MB at one token or 0.5 MB at 2..4: then the
+    rotation runs as a pass of its own, which shows as a scratch part of T * c_in * 2 bytes."""
+    L = paro.lib()
+
+    def scratch(c_in, c_out, T):
+        r, w = _rot(c_in=c_in, plan=FAKE), _w(c_in=c_in, c_out=c_out, packed=FAKE)
+        return L.paro_workspace_bytes(ctypes.byref(r), ctypes.byref(w), T) - L.paro_workspace_exchange_bytes(
+            ctypes.byref(r), ctypes.byref(w), T)
+
+    assert scratch(4096, 6144, 1) == 0 and scratch(4096, 28672, 1) == 0 and scratch(14336, 4096, 1) == 0
+    assert scratch(27648, 5120, 1) == 0                    # 54 slices x 5120 x 4 = 1.1 MB
+    assert scratch(5120, 55296, 1) == 5120 * 2             # 10 x 55296 x 4 = 2.2 MB: two launches
+    assert scratch(4096, 6144, 2) == 0 and scratch(4096, 4096, 3) == 0
+    assert scratch(4096, 6144, 4) == 4 * 4096 * 2          # 8 x 4 x 6144 x 4 = 786 KB
+    assert scratch(4096, 28672, 2) == 2 * 4096 * 2
+
+
 def test_fwht_argument_errors():
     L = paro.lib()
     assert L.paro_fwht(None, 64, FAKE, 64, 1, 64, None) == 1
