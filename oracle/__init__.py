@@ -189,6 +189,35 @@ def mxfp4_quantize(u: np.ndarray):
     return codes, scales
 
 
+def mxfp4_dequant(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """Values of MXFP4 elements: codes uint8 [T][C], scales uint8 [T][C/32] -> fp64 [T][C]."""
+    codes, scales = _c(codes, np.uint8), _c(scales, np.uint8)
+    T, C = codes.shape
+    assert scales.shape == (T, C // 32)
+    out = np.empty((T, C), dtype=np.float64)
+    L = lib()
+    L.oracle_mxfp4_dequant.restype = None
+    L.oracle_mxfp4_dequant(_p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8), ctypes.c_int32(T), ctypes.c_int32(C),
+                           _p(out, ctypes.c_double))
+    return out
+
+
+def mxfp4_linear(x_codes, x_scales, w_codes, w_scales, bias16=None) -> np.ndarray:
+    """Y' = Q(X T^-1) . Q(T W) + b on MXFP4 operands (App. A.3): fp64 [T][N]."""
+    xc, xs, wc, ws = _c(x_codes, np.uint8), _c(x_scales, np.uint8), _c(w_codes, np.uint8), _c(w_scales, np.uint8)
+    T, C = xc.shape
+    N = wc.shape[0]
+    assert wc.shape == (N, C) and xs.shape == (T, C // 32) and ws.shape == (N, C // 32)
+    y = np.empty((T, N), dtype=np.float64)
+    bb = _bits(bias16) if bias16 is not None else None
+    L = lib()
+    L.oracle_mxfp4_linear.restype = None
+    L.oracle_mxfp4_linear(_p(xc, ctypes.c_uint8), _p(xs, ctypes.c_uint8), ctypes.c_int32(T), _p(wc, ctypes.c_uint8),
+                          _p(ws, ctypes.c_uint8), ctypes.c_int32(N), ctypes.c_int32(C),
+                          _p(bb, ctypes.c_uint16) if bb is not None else None, _p(y, ctypes.c_double))
+    return y
+
+
 def fwht(x16) -> np.ndarray:
     """y = H_n x / sqrt(n) per row, Sylvester order (H_n[i][j] = (-1)^popcount(i & j)), fp64 [T][n]."""
     xb = _bits(x16)

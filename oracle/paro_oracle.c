@@ -28,6 +28,10 @@
  *                                           output row, then RTN per group
  *   Section 4.3, speed-up figure           : the Hadamard transform it is compared with
  *                                           (Sylvester order, orthonormal)
+ *   App. A.3, first equation               : Y' = Q(X T^-1) . Q(T W) + b with both
+ *                                           operands in MXFP4 (element and scale
+ *                                           formats of the OCP Microscaling
+ *                                           Formats specification)
  *
  * Readings where the paper leaves a choice
  *   - theta on the activation side.  Eq. 5 right-multiplies a row vector by
@@ -299,6 +303,51 @@ void oracle_mxfp4_quantize(const double *u, int64_t ldu, int32_t T, int32_t C, u
                 codes[(int64_t)t * C + (int64_t)b * 32 + i] = (uint8_t)code;
             }
         }
+}
+
+/*
+ * The value an MXFP4 element stands for (OCP Microscaling Formats specification):
+ *      v = (-1)^sign * M[code & 7] * 2^(scale_byte - 127),   M = 0, 0.5, 1, 1.5, 2, 3, 4, 6
+ * (E2M1: exponent bias 1, subnormal 0.5; E8M0 scale: bias 127).  Exact in fp64.
+ * codes: [T][C] bytes, scales: [T][C/32] bytes, out: [T][C] fp64.
+ */
+void oracle_mxfp4_dequant(const uint8_t *codes, const uint8_t *scales, int32_t T, int32_t C, double *out)
+{
+    for (int64_t t = 0; t < T; ++t)
+        for (int32_t c = 0; c < C; ++c) {
+            int code = codes[t * C + c];
+            int e = (code >> 1) & 3, m = code & 1;
+            double mag = e == 0 ? 0.5 * m : ldexp(1.0 + 0.5 * m, e - 1);
+            double v = ldexp(mag, (int)scales[t * (C / 32) + c / 32] - 127);
+            out[t * C + c] = (code & 8) ? -v : v;
+        }
+}
+
+/*
+ * The weight-activation form of the linear layer (App. A.3, first equation):
+ *      Y' = Q(X T^-1) . Q(T W) + b
+ * for operands that are already quantised to MXFP4: y[t][n] = sum_c x^[t][c] w^[n][c] (+ bias[n]),
+ * x^ and w^ the values the codes stand for.  fp64; every product is exact and the sum is exact as
+ * long as the block exponents of a row span fewer than ~40 binades.
+ * xc: [T][C], xs: [T][C/32], wc: [N][C], ws: [N][C/32], bias16: [N] fp16 bits or NULL, y: [T][N].
+ */
+void oracle_mxfp4_linear(const uint8_t *xc, const uint8_t *xs, int32_t T, const uint8_t *wc, const uint8_t *ws,
+                         int32_t N, int32_t C, const uint16_t *bias16, double *y)
+{
+    double *xv = (double *)malloc((size_t)T * C * sizeof(double));
+    double *wv = (double *)malloc((size_t)N * C * sizeof(double));
+    oracle_mxfp4_dequant(xc, xs, T, C, xv);
+    oracle_mxfp4_dequant(wc, ws, N, C, wv);
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t t = 0; t < T; ++t) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < C; ++c) acc += xv[t * C + c] * wv[n * C + c];
+            if (bias16) acc += oracle_fp16_to_f64(bias16[n]);
+            y[t * N + n] = acc;
+        }
+    free(xv);
+    free(wv);
 }
 
 /* ---- INT4 unpack and dequantisation (Eq. 1 inverted, group rule) --------- */
