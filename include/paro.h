@@ -246,7 +246,8 @@ paro_status paro_w4_quantize(const paro_rotation *rot, const paro_half_t *W, int
  * scale floor 2^-14, zero point clamped to 0..15).  The rotation needs its plan.
  * codes [T][c_in/8] (bits 4k..4k+3 of word w hold channel 8w+k), scales [T][c_in/128] fp16,
  * zeros [T][c_in/128] bytes; all device, written completely.  X as in paro_rotate_scale.
- * No INT4 x INT4 contraction is part of this library: the call ends at the quantised activations. */
+ * No INT4 x INT4 contraction is part of this library: the call ends at the quantised activations
+ * (the MXFP4 form below goes on to the contraction). */
 paro_status paro_rotate_scale_quantize_int4(const paro_rotation *rot, const paro_half_t *X, int64_t ldx,
                                             int32_t T, uint32_t *codes, paro_half_t *scales,
                                             uint8_t *zeros, void *stream);
@@ -258,10 +259,61 @@ paro_status paro_rotate_scale_quantize_int4(const paro_rotation *rot, const paro
  * of v / 2^e, round to nearest, ties to the even code, saturating at 6 (magnitudes by code 0..7:
  * 0, 0.5, 1, 1.5, 2, 3, 4, 6; bit 3 = sign).  Inputs must be finite.  The rotation needs its plan.
  * codes [T][c_in/8] (bits 4k..4k+3 of word w hold channel 8w+k), scales [T][c_in/32] bytes; all
- * device, written completely.  X as in paro_rotate_scale.  The call ends at the quantised
- * activations, as paro_rotate_scale_quantize_int4 does. */
+ * device (codes and scales 16-byte aligned if they feed paro_mxfp4_linear), written completely.
+ * X as in paro_rotate_scale. */
 paro_status paro_rotate_scale_quantize_mxfp4(const paro_rotation *rot, const paro_half_t *X, int64_t ldx,
                                              int32_t T, uint32_t *codes, uint8_t *scales, void *stream);
+
+/* ---- The weight-activation linear with both operands in MXFP4 (App. A.3, first equation) --------
+ *      Y' = Q(X T^-1) . Q(T W) + b
+ * contracted on the block-scaled FP4 matrix instruction of gfx950: E2M1 codes and E8M0 block scales
+ * go to the matrix cores as they are, products are exact, accumulation is fp32, one fp16 rounding at
+ * the store.  Element and scale formats as documented at paro_rotate_scale_quantize_mxfp4. */
+typedef struct paro_mxfp4_weight {
+    int32_t c_in;             /* multiple of 512 for paro_mxfp4_repack / paro_mxfp4_linear, of 128 otherwise */
+    int32_t c_out;            /* multiple of 16 for paro_mxfp4_repack / paro_mxfp4_linear                   */
+    const uint32_t *codes;    /* device [c_out][c_in/8]: bits 4k..4k+3 of word w of a row = channel 8w+k;
+                                 may be NULL once `packed` is set                                           */
+    const uint8_t *scales;    /* device [c_out][c_in/32] E8M0 bytes; may be NULL once `packed` is set       */
+    const paro_half_t *bias;  /* device [c_out] fp16, or NULL                                               */
+    const void *packed;       /* device blob written by paro_mxfp4_repack (operand order of the matrix
+                                 instruction), or NULL; 256-byte aligned; owned by the caller               */
+} paro_mxfp4_weight;
+
+/* Q(T W): every output row of the dense fp16 W[c_out][c_in] (row n at W + n*ldw, device) takes the
+ * weight side of the transform, w'_n = R_K ... R_1 . diag(1/ch_scale) . w_n in fp32 exactly as in
+ * paro_w4_quantize (rot == NULL: none; a rotation needs its plan), and is converted to MXFP4 per
+ * 32 channels.  codes [c_out][c_in/8], scales [c_out][c_in/32]: device, written completely.
+ * c_in % 128 == 0, ldw >= c_in and even, W 4-byte aligned, codes 4-byte aligned. */
+paro_status paro_mxfp4_quantize_weight(const paro_rotation *rot, const paro_half_t *W, int64_t ldw,
+                                       int32_t c_in, int32_t c_out, uint32_t *codes, uint8_t *scales,
+                                       void *stream);
+
+/* Repack codes + scales into the operand order of the matrix instruction (tiles of 16 rows x 128
+ * channels, then one dword of four K-steps' scale bytes per lane).  packed_out: device,
+ * paro_mxfp4_packed_bytes() bytes (= c_out*c_in/2 + c_out*c_in/32), 256-byte aligned. */
+size_t paro_mxfp4_packed_bytes(const paro_mxfp4_weight *w);
+paro_status paro_mxfp4_repack(const paro_mxfp4_weight *w, void *packed_out, void *stream);
+/* Test hook: codes[n][c] as bytes 0..15 and scales[n][c/32], from w->packed if set, else from the
+ * plain arrays (codes: c_out*c_in bytes, scales: c_out*c_in/32 bytes, device). */
+paro_status paro_mxfp4_unpack(const paro_mxfp4_weight *w, uint8_t *codes, uint8_t *scales, void *stream);
+
+/* Y[t][n] = sum_c x^[t][c] w^[n][c] (+ bias[n]) for t < T, x^ / w^ the values the MXFP4 codes stand
+ * for.  x_codes [T][c_in/8], x_scales [T][c_in/32]: device, 16-byte aligned, in the layout
+ * paro_rotate_scale_quantize_mxfp4 writes.  Y: fp16 [T][ldy], ldy >= c_out, 2-byte aligned rows.
+ * Needs w->packed (PARO_ERR_UNSUPPORTED otherwise; also for c_in > 30720 or a blob of 2 GiB or
+ * more).  No workspace. */
+paro_status paro_mxfp4_linear(const paro_mxfp4_weight *w, const uint32_t *x_codes, const uint8_t *x_scales,
+                              int32_t T, paro_half_t *Y, int64_t ldy, void *stream);
+
+/* The whole of App. A.3's equation for fp16 activations: paro_rotate_scale_quantize_mxfp4 into the
+ * workspace, then paro_mxfp4_linear.  ws: device, >= paro_workspace_bytes_mxfp4(c_in, T) bytes
+ * (= T*c_in/2 for the codes, rounded up to 256, + T*c_in/32 for the scales), 256-byte aligned, no
+ * requirement on its contents before the call, any contents after it. */
+size_t paro_workspace_bytes_mxfp4(int32_t c_in, int32_t T);
+paro_status paro_rotated_linear_mxfp4(const paro_rotation *rot, const paro_mxfp4_weight *w,
+                                      const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
+                                      int32_t T, void *ws, size_t ws_bytes, void *stream);
 
 /* Test hooks for the bit-exact gate --------------------------------------------------- */
 

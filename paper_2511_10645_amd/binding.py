@@ -37,6 +37,13 @@ class _CW4Weight(ctypes.Structure):
     ]
 
 
+class _CMxfp4Weight(ctypes.Structure):
+    _fields_ = [
+        ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32),
+        ("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("packed", ctypes.c_void_p),
+    ]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -84,6 +91,16 @@ def lib():
         L.paro_workspace_exchange_bytes_multi.argtypes = [i32, vp, vp, i32]
         L.paro_rotated_linear_multi.argtypes = [i32, vp, vp, vp, i64, vp, vp, i32, vp, sz, vp]
         L.paro_fwht.argtypes = [vp, i64, vp, i64, i32, i32, vp]
+        mp = ctypes.POINTER(_CMxfp4Weight)
+        L.paro_mxfp4_quantize_weight.argtypes = [rp, vp, i64, i32, i32, vp, vp, vp]
+        L.paro_mxfp4_packed_bytes.restype = sz
+        L.paro_mxfp4_packed_bytes.argtypes = [mp]
+        L.paro_mxfp4_repack.argtypes = [mp, vp, vp]
+        L.paro_mxfp4_unpack.argtypes = [mp, vp, vp, vp]
+        L.paro_mxfp4_linear.argtypes = [mp, vp, vp, i32, vp, i64, vp]
+        L.paro_workspace_bytes_mxfp4.restype = sz
+        L.paro_workspace_bytes_mxfp4.argtypes = [i32, i32]
+        L.paro_rotated_linear_mxfp4.argtypes = [rp, mp, vp, i64, vp, i64, i32, vp, sz, vp]
         L.paro_diag_read_stream.argtypes = [vp, sz, vp, i32, vp]
         L.paro_diag_mfma_f16.argtypes = [vp, sz, i32, i32, i32, vp]
         L.paro_diag_mfma_f16_flops.argtypes = [i32, i32]
@@ -92,7 +109,8 @@ def lib():
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_rotated_linear_noalloc", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
                      "paro_rotate_scale_quantize_int4", "paro_rotate_scale_quantize_mxfp4",
-                     "paro_diag_read_stream", "paro_diag_mfma_f16", "paro_fwht"):
+                     "paro_diag_read_stream", "paro_diag_mfma_f16", "paro_fwht", "paro_mxfp4_quantize_weight",
+                     "paro_mxfp4_repack", "paro_mxfp4_unpack", "paro_mxfp4_linear", "paro_rotated_linear_mxfp4"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -411,3 +429,87 @@ def paro_rotate_scale_quantize_mxfp4(rot: Rotation, X: torch.Tensor):
     _check(lib().paro_rotate_scale_quantize_mxfp4(rot.ref(), X.data_ptr(), ldx, T, codes.data_ptr(), scales.data_ptr(),
                                                   _stream()), "paro_rotate_scale_quantize_mxfp4")
     return codes, scales
+
+
+class Mxfp4Weight:
+    """Device-side MXFP4 weight (struct paro_mxfp4_weight): codes int32 [c_out][c_in/8], scales uint8 [c_out][c_in/32]."""
+
+    def __init__(self, codes: torch.Tensor, scales: torch.Tensor, bias: torch.Tensor | None = None):
+        self.c_out, c8 = codes.shape
+        self.c_in = c8 * 8
+        assert codes.dtype == torch.int32 and scales.dtype == torch.uint8 and scales.shape == (self.c_out, self.c_in // 32)
+        self.codes, self.scales, self.bias, self.packed = codes, scales, bias, None
+        self.c = _CMxfp4Weight(self.c_in, self.c_out, _ptr(codes), _ptr(scales), _ptr(bias), None)
+
+    @classmethod
+    def from_host(cls, codes_bytes: np.ndarray, scales: np.ndarray, bias=None, device="cuda"):
+        """codes_bytes: uint8 [c_out][c_in] (one E2M1 code per byte), scales: uint8 [c_out][c_in/32]."""
+        cb = np.ascontiguousarray(codes_bytes, dtype=np.uint8)
+        n, c = cb.shape
+        words = np.zeros((n, c // 8), dtype=np.uint32)
+        for k in range(8):
+            words |= cb[:, k::8].astype(np.uint32) << np.uint32(4 * k)
+        b = None if bias is None else torch.as_tensor(np.ascontiguousarray(bias, dtype=np.float16)).to(device)
+        return cls(torch.as_tensor(words.view(np.int32)).to(device),
+                   torch.as_tensor(np.ascontiguousarray(scales, dtype=np.uint8)).to(device), b)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def paro_mxfp4_quantize_weight(rot: Rotation | None, W: torch.Tensor, bias: torch.Tensor | None = None) -> Mxfp4Weight:
+    """Q(T W) of App. A.3: weight-side transform, then MXFP4 per 32 channels, of a dense fp16 weight [c_out][c_in]."""
+    assert W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
+    c_out, c_in = W.shape
+    codes = torch.empty((c_out, c_in // 8), dtype=torch.int32, device=W.device)
+    scales = torch.empty((c_out, c_in // 32), dtype=torch.uint8, device=W.device)
+    _check(lib().paro_mxfp4_quantize_weight(rot.ref() if rot is not None else None, W.data_ptr(), W.stride(0), c_in, c_out,
+                                            codes.data_ptr(), scales.data_ptr(), _stream()), "paro_mxfp4_quantize_weight")
+    return Mxfp4Weight(codes, scales, bias)
+
+
+def paro_mxfp4_repack(w: Mxfp4Weight) -> None:
+    n = lib().paro_mxfp4_packed_bytes(w.ref())
+    if n == 0:
+        raise ParoError(5, "paro_mxfp4_packed_bytes")
+    blob = torch.empty(n, dtype=torch.uint8, device=w.codes.device)
+    _check(lib().paro_mxfp4_repack(w.ref(), blob.data_ptr(), _stream()), "paro_mxfp4_repack")
+    w.packed = blob
+    w.c.packed = blob.data_ptr()
+
+
+def paro_mxfp4_unpack(w: Mxfp4Weight):
+    """Test hook: (codes uint8 [c_out][c_in], scales uint8 [c_out][c_in/32]) from the repacked blob if present."""
+    dev = w.packed.device if w.packed is not None else w.codes.device
+    codes = torch.empty((w.c_out, w.c_in), dtype=torch.uint8, device=dev)
+    scales = torch.empty((w.c_out, w.c_in // 32), dtype=torch.uint8, device=dev)
+    _check(lib().paro_mxfp4_unpack(w.ref(), codes.data_ptr(), scales.data_ptr(), _stream()), "paro_mxfp4_unpack")
+    return codes, scales
+
+
+def paro_mxfp4_linear(w: Mxfp4Weight, x_codes: torch.Tensor, x_scales: torch.Tensor, Y: torch.Tensor | None = None):
+    """Y' = Q(X T^-1) . Q(T W) + b on MXFP4 operands (App. A.3)."""
+    T = x_codes.shape[0]
+    assert x_codes.dtype == torch.int32 and x_codes.shape == (T, w.c_in // 8) and x_codes.is_contiguous()
+    assert x_scales.dtype == torch.uint8 and x_scales.shape == (T, w.c_in // 32) and x_scales.is_contiguous()
+    if Y is None:
+        Y = torch.empty((T, w.c_out), dtype=torch.float16, device=x_codes.device)
+    _, ldy = _rows(Y)
+    _check(lib().paro_mxfp4_linear(w.ref(), x_codes.data_ptr(), x_scales.data_ptr(), T, Y.data_ptr(), ldy, _stream()),
+           "paro_mxfp4_linear")
+    return Y
+
+
+def paro_workspace_bytes_mxfp4(c_in: int, T: int) -> int:
+    return lib().paro_workspace_bytes_mxfp4(c_in, T)
+
+
+def paro_rotated_linear_mxfp4(rot: Rotation, w: Mxfp4Weight, X: torch.Tensor, ws: torch.Tensor, Y: torch.Tensor | None = None):
+    """Transform + MXFP4-quantise the activations into `ws` (uint8 tensor), then the MXFP4 x MXFP4 linear."""
+    T, ldx = _rows(X)
+    if Y is None:
+        Y = torch.empty((T, w.c_out), dtype=torch.float16, device=X.device)
+    _, ldy = _rows(Y)
+    _check(lib().paro_rotated_linear_mxfp4(rot.ref(), w.ref(), X.data_ptr(), ldx, Y.data_ptr(), ldy, T, ws.data_ptr(),
+                                           ws.numel(), _stream()), "paro_rotated_linear_mxfp4")
+    return Y

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libparo.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["paro_api.hip", "rotate.hip", "w4_layout.hip", "decode.hip", "decode_wide.hip", "gemm.hip", "quantize.hip", "ceilings.hip", "fwht.hip"]
+SOURCES = ["paro_api.hip", "rotate.hip", "w4_layout.hip", "decode.hip", "decode_wide.hip", "gemm.hip", "quantize.hip", "ceilings.hip", "fwht.hip", "mxfp4.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

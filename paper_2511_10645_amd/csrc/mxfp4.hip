@@ -1,0 +1,289 @@
+// Weight-activation form of the linear layer with both operands in MXFP4 (App. A.3, first equation):
+//      Y' = Q(X T^-1) . Q(T W) + b
+// on the block-scaled FP4 matrix instruction of this chip, which takes E2M1 codes and one E8M0 scale per
+// 32 elements of each operand directly: nothing is dequantised, the codes go from memory to the matrix
+// core as they are and the products are accumulated in fp32.
+//
+// v_mfma_scale_f32_16x16x128_f8f6f4 (FP4 x FP4): lane l of the A operand holds row l % 16, elements
+// 32 (l / 16) .. + 31 of the 128-wide K-step as 16 bytes (element k in nibble k % 8 of dword k / 8), and
+// ONE scale byte for those 32 elements - an MX block is exactly a lane's share; B likewise with column
+// l % 16; D as for the other 16x16 shapes (lane: column l % 16, rows 4 (l / 16) + r).  The scale operand
+// is a dword of which an immediate picks the byte, so one register serves four K-steps.
+//
+// Weights are repacked once into that operand order ("tiles" of 16 rows x 128 channels = 1 KB, then
+// per 16 rows x 512 channels one dword per lane with the four K-steps' scale bytes), so a wave's load of
+// a tile is one contiguous kilobyte.  Activations stay in the plain row order their quantiser writes:
+// a lane's 32 elements are 16 contiguous bytes of its token's row.
+//
+// Two kernels.  Up to 16 tokens: HBM-bound stream of the weight tiles (0.53 B per weight), one
+// 512-channel slice per wave and pass, all slices of K inside one block (a wave takes SPW slices when
+// there are more than 12), partial tiles summed through LDS; no exchange between blocks.  More tokens:
+// a tiled GEMM whose operands go through LDS (see below).
+#include "paro_internal.h"
+#include <type_traits>
+
+namespace paro {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kOobM = 0x80000000u;
+__device__ inline __amdgpu_buffer_rsrc_t mx_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ inline v8i as_operand(u32x4 v) { return v8i{(int)v[0], (int)v[1], (int)v[2], (int)v[3], 0, 0, 0, 0}; }
+
+template <int N, class F, int I = 0>
+__device__ __forceinline__ void mx_static_while(F &&f)
+{
+    if constexpr (I < N) {
+        if (f(std::integral_constant<int, I>{})) mx_static_while<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Layout: plain [N][C/8] words + [N][C/32] bytes  <->  blob = tiles | scale dwords
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mxfp4_repack_kernel(const uint32_t *__restrict__ codes,
+                                                           const uint8_t *__restrict__ scales, int N, int C,
+                                                           u32x4 *__restrict__ tiles, uint32_t *__restrict__ sdw)
+{
+    const int K128 = C / 128, KS = C / 512;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t n_tiles16 = (size_t)(N / 16) * K128 * 64;
+    if (idx < n_tiles16) {
+        const int lane = (int)(idx & 63);
+        const size_t tk = idx >> 6;
+        const int k128 = (int)(tk % K128);
+        const size_t nt = tk / K128;
+        const size_t row = nt * 16 + (lane & 15);
+        tiles[idx] = *(const u32x4 *)(codes + row * (C / 8) + (size_t)k128 * 16 + (lane >> 4) * 4);
+    }
+    const size_t n_sdw = (size_t)(N / 16) * KS * 64;
+    if (idx < n_sdw) {
+        const int lane = (int)(idx & 63);
+        const size_t ts = idx >> 6;
+        const int ks = (int)(ts % KS);
+        const size_t nt = ts / KS;
+        const uint8_t *sr = scales + (nt * 16 + (lane & 15)) * (size_t)(C / 32) + (size_t)ks * 16 + (lane >> 4);
+        sdw[idx] = (uint32_t)sr[0] | ((uint32_t)sr[4] << 8) | ((uint32_t)sr[8] << 16) | ((uint32_t)sr[12] << 24);
+    }
+}
+
+// one thread per (row, 32-channel block): 32 code bytes and the scale byte, from either layout
+__global__ __launch_bounds__(256) void mxfp4_unpack_kernel(const uint32_t *__restrict__ codes,
+                                                           const uint8_t *__restrict__ scales,
+                                                           const u32x4 *__restrict__ tiles,
+                                                           const uint32_t *__restrict__ sdw, int N, int C,
+                                                           uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_scales)
+{
+    const int B = C / 32;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)N * B) return;
+    const size_t row = idx / B;
+    const int b = (int)(idx % B);
+    u32x4 v;
+    uint32_t sc;
+    if (tiles) {
+        const int lane = (int)(row & 15) + 16 * (b & 3);
+        v = tiles[((row / 16) * (C / 128) + b / 4) * 64 + lane];
+        sc = (sdw[((row / 16) * (C / 512) + b / 16) * 64 + lane] >> (8 * ((b / 4) & 3))) & 0xffu;
+    } else {
+        v = *(const u32x4 *)(codes + row * (C / 8) + (size_t)b * 4);
+        sc = scales[row * B + b];
+    }
+    uint8_t *o = out_codes + row * C + (size_t)b * 32;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) o[j] = (uint8_t)((v[j / 8] >> (4 * (j % 8))) & 15u);
+    out_scales[idx] = (uint8_t)sc;
+}
+
+hipError_t launch_mxfp4_repack(const paro_mxfp4_weight &w, void *packed_out, hipStream_t s)
+{
+    const size_t n = (size_t)w.c_out * w.c_in / 32;                   // 16-byte chunks of codes
+    hipLaunchKernelGGL(mxfp4_repack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w.codes, w.scales,
+                       w.c_out, w.c_in, (u32x4 *)packed_out,
+                       (uint32_t *)((char *)packed_out + (size_t)w.c_out * w.c_in / 2));
+    return hipGetLastError();
+}
+
+hipError_t launch_mxfp4_unpack(const paro_mxfp4_weight &w, uint8_t *codes, uint8_t *scales, hipStream_t s)
+{
+    const size_t n = (size_t)w.c_out * w.c_in / 32;
+    const u32x4 *tiles = (const u32x4 *)w.packed;
+    const uint32_t *sdw = w.packed ? (const uint32_t *)((const char *)w.packed + (size_t)w.c_out * w.c_in / 2) : nullptr;
+    hipLaunchKernelGGL(mxfp4_unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w.codes, w.scales, tiles,
+                       sdw, w.c_out, w.c_in, codes, scales);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Up to 16 tokens
+// ------------------------------------------------------------------------------------------
+struct MxArgs {
+    const void *blob; uint32_t blob_bytes, scales_off;
+    const uint32_t *xc; const uint8_t *xs;          // activations of this pass: [T][C/8] words, [T][C/32] bytes
+    _Float16 *Y; int64_t ldy;
+    const _Float16 *bias;
+    int T, C, N, NT, KS, tiles_per_block;
+};
+
+constexpr int kMxStages = 3;
+constexpr int kMxMaxUnits = 16;                      // (tile, slice) units per wave: the stream is unrolled
+constexpr int kMxMaxWaves = 12;                      // 3 waves per SIMD: 170 registers each
+
+struct MxStage { u32x4 w[4]; uint32_t sc; };
+
+// SPW: 512-channel slices per wave (wave w takes slices w, w + waves, ...)
+template <int SPW>
+__global__ __launch_bounds__(kMxMaxWaves * 64) void mxfp4_decode_kernel(MxArgs a)
+{
+    constexpr int NS = kMxStages;
+    extern __shared__ __attribute__((aligned(16))) float s_part[];       // [tiles per block][waves][256]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;
+    const int tile_lo = blockIdx.x * a.tiles_per_block;
+    const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
+    const int n_iter = tile_hi - tile_lo;
+    const int K128 = a.C / 128;
+    const __amdgpu_buffer_rsrc_t blob = mx_rsrc(a.blob, a.blob_bytes);
+
+    // ---- activations of the wave's slices as A operands: lane = (token l % 16, 32-channel block l / 16) ----
+    const int ft = lane & 15, fkb = lane >> 4;
+    u32x4 xf[SPW][4];
+    uint32_t xsc[SPW];
+    {
+        const __amdgpu_buffer_rsrc_t xr = mx_rsrc(a.xc, (uint32_t)((size_t)a.T * a.C / 2));
+        const __amdgpu_buffer_rsrc_t sr = mx_rsrc(a.xs, (uint32_t)((size_t)a.T * a.C / 32));
+#pragma unroll
+        for (int q = 0; q < SPW; ++q) {
+            const int ks = wave + q * nw;
+            const bool ok = ks < a.KS && ft < a.T;
+            const uint32_t xo = ok ? (uint32_t)((size_t)ft * (a.C / 2) + (size_t)ks * 256 + fkb * 16) : kOobM;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) xf[q][m] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xo + m * 64), 0, 0);
+            // the slice's 16 scale bytes: dword m = K-step m, byte kb = the lane's block
+            const u32x4 sc = __builtin_amdgcn_raw_buffer_load_b128(sr, ok ? (int)((size_t)ft * (a.C / 32) + (size_t)ks * 16) : (int)kOobM, 0, 0);
+            const int sh = 8 * fkb;
+            xsc[q] = ((sc[0] >> sh) & 0xffu) | (((sc[1] >> sh) & 0xffu) << 8) | (((sc[2] >> sh) & 0xffu) << 16) |
+                     (((sc[3] >> sh) & 0xffu) << 24);
+        }
+    }
+    // unit i = (tile tile_lo + i / SPW, slice wave + (i % SPW) waves); nothing to load beyond the range: zeros
+    MxStage st[NS];
+    auto load_unit = [&](int i, MxStage &s) {
+        const int ti = i / SPW, ks = wave + (i % SPW) * nw;
+        const bool ok = ti < n_iter && ks < a.KS;
+        const uint32_t tile = (uint32_t)(tile_lo + ti);
+        const uint32_t off = ok ? ((tile * K128 + ks * 4) * 64u + lane) * 16u : kOobM;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) s.w[m] = __builtin_amdgcn_raw_buffer_load_b128(blob, (int)(off + m * 1024u), 0, 2);
+        s.sc = __builtin_amdgcn_raw_buffer_load_b32(blob, ok ? (int)(a.scales_off + ((tile * a.KS + ks) * 64u + lane) * 4u) : (int)kOobM, 0, 0);
+    };
+#pragma unroll
+    for (int i = 0; i + 1 < NS; ++i) load_unit(i, st[i]);
+
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    mx_static_while<kMxMaxUnits>([&](auto I) {
+        constexpr int i = I;
+        constexpr int q = i % SPW;
+        if (i / SPW >= n_iter) return false;
+        load_unit(i + NS - 1, st[(i + NS - 1) % NS]);
+        const MxStage &s = st[i % NS];
+        if constexpr (q == 0) acc = float4v{0.f, 0.f, 0.f, 0.f};
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][0]), as_operand(s.w[0]), acc, 4, 4, 0, (int)xsc[q], 0, (int)s.sc);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][1]), as_operand(s.w[1]), acc, 4, 4, 1, (int)xsc[q], 1, (int)s.sc);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][2]), as_operand(s.w[2]), acc, 4, 4, 2, (int)xsc[q], 2, (int)s.sc);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][3]), as_operand(s.w[3]), acc, 4, 4, 3, (int)xsc[q], 3, (int)s.sc);
+        if constexpr (q == SPW - 1) *(float4v *)(s_part + ((size_t)(i / SPW) * nw + wave) * 256 + lane * 4) = acc;
+        return true;
+    });
+    __syncthreads();
+    // ---- sum the waves' partial tiles: element lane * 4 + r <-> token 4 (lane / 16) + r, row lane % 16 ----
+    const int per_tile = a.T * kTileN;
+    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += blockDim.x) {
+        const int i = idx / per_tile, rem = idx % per_tile;
+        const int t = rem / kTileN, nn = rem % kTileN;
+        const int e = ((t >> 2) * 16 + nn) * 4 + (t & 3);
+        float sum = 0.f;
+        for (int w = 0; w < nw; ++w) sum += s_part[((size_t)i * nw + w) * 256 + e];
+        const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
+        if (a.bias) sum += (float)a.bias[n];
+        a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
+    }
+}
+
+struct MxGeometry { int spw, waves, tiles_per_block, blocks; size_t lds; };
+static bool mx_geometry(int c_in, int c_out, MxGeometry &g)
+{
+    const int KS = c_in / 512, NT = c_out / kTileN;
+    g.spw = (KS + kMxMaxWaves - 1) / kMxMaxWaves;
+    if (g.spw > 5) return false;
+    g.waves = (KS + g.spw - 1) / g.spw;
+    int tpb = (NT + 255) / 256;                               // one block per compute unit
+    if (tpb > kMxMaxUnits / g.spw) tpb = kMxMaxUnits / g.spw;
+    if (tpb * g.waves > 144) tpb = 144 / g.waves;             // 1 KB of LDS per (tile, wave)
+    g.tiles_per_block = tpb;
+    g.blocks = (NT + tpb - 1) / tpb;
+    g.lds = (size_t)tpb * g.waves * 1024;
+    return true;
+}
+
+bool mxfp4_linear_supported(const paro_mxfp4_weight &w)
+{
+    MxGeometry g;
+    return w.packed && w.c_in % 512 == 0 && w.c_out % 16 == 0 && mx_geometry(w.c_in, w.c_out, g) &&
+           (size_t)w.c_out * w.c_in / 2 + (size_t)w.c_out * w.c_in / 32 < (1ull << 31);
+}
+
+// one pass of up to 16 tokens
+static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t *xc, const uint8_t *xs, int T,
+                                      paro_half_t *Y, int64_t ldy, hipStream_t s)
+{
+    MxGeometry g;
+    if (!mx_geometry(w.c_in, w.c_out, g)) return hipErrorInvalidValue;
+    MxArgs a;
+    a.blob = w.packed;
+    a.scales_off = (uint32_t)((size_t)w.c_out * w.c_in / 2);
+    a.blob_bytes = a.scales_off + (uint32_t)((size_t)w.c_out * w.c_in / 32);
+    a.xc = xc; a.xs = xs; a.Y = (_Float16 *)Y; a.ldy = ldy; a.bias = (const _Float16 *)w.bias;
+    a.T = T; a.C = w.c_in; a.N = w.c_out; a.NT = w.c_out / kTileN; a.KS = w.c_in / 512;
+    a.tiles_per_block = g.tiles_per_block;
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
+        const void *fns[5] = {(const void *)mxfp4_decode_kernel<1>, (const void *)mxfp4_decode_kernel<2>,
+                              (const void *)mxfp4_decode_kernel<3>, (const void *)mxfp4_decode_kernel<4>,
+                              (const void *)mxfp4_decode_kernel<5>};
+        for (const void *f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+        }
+        once_done(attr_done, dev);
+    }
+    const dim3 grid(g.blocks), block(g.waves * 64);
+    switch (g.spw) {
+    case 1: hipLaunchKernelGGL(mxfp4_decode_kernel<1>, grid, block, g.lds, s, a); break;
+    case 2: hipLaunchKernelGGL(mxfp4_decode_kernel<2>, grid, block, g.lds, s, a); break;
+    case 3: hipLaunchKernelGGL(mxfp4_decode_kernel<3>, grid, block, g.lds, s, a); break;
+    case 4: hipLaunchKernelGGL(mxfp4_decode_kernel<4>, grid, block, g.lds, s, a); break;
+    default: hipLaunchKernelGGL(mxfp4_decode_kernel<5>, grid, block, g.lds, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_codes, const uint8_t *x_scales, int T,
+                               paro_half_t *Y, int64_t ldy, hipStream_t s)
+{
+    for (int t0 = 0; t0 < T; t0 += 16) {
+        const int tp = T - t0 < 16 ? T - t0 : 16;
+        hipError_t e = launch_mxfp4_decode(w, x_codes + (size_t)t0 * (w.c_in / 8), x_scales + (size_t)t0 * (w.c_in / 32), tp,
+                                           Y + (size_t)t0 * ldy, ldy, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace paro

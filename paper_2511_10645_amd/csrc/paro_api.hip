@@ -535,4 +535,97 @@ paro_status paro_rotate_scale_quantize_mxfp4(const paro_rotation *rot, const par
     return from_hip(paro::launch_quantize_act_mxfp4(*rot, X, ldx, T, codes, scales, (hipStream_t)stream));
 }
 
+static paro_status check_mxfp4_weight(const paro_mxfp4_weight *w, bool for_linear)
+{
+    if (!w) return PARO_ERR_NULL;
+    if (w->c_in <= 0 || w->c_out <= 0 || w->c_in % paro::kGroup) return PARO_ERR_SHAPE;
+    if (for_linear && (w->c_in % 512 || w->c_out % 16)) return PARO_ERR_SHAPE;
+    if (!w->packed && (!w->codes || !w->scales)) return PARO_ERR_NULL;
+    if ((w->codes && !aligned(w->codes, 16)) || (w->packed && !aligned(w->packed, 256)) || (w->bias && !aligned(w->bias, 2)))
+        return PARO_ERR_ALIGN;
+    return PARO_OK;
+}
+
+paro_status paro_mxfp4_quantize_weight(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int32_t c_in,
+                                       int32_t c_out, uint32_t *codes, uint8_t *scales, void *stream)
+{
+    if (!W || !codes || !scales) return PARO_ERR_NULL;
+    if (c_in <= 0 || c_out <= 0 || c_in % paro::kGroup || ldw < c_in) return PARO_ERR_SHAPE;
+    if (ldw % 2 || !aligned(W, 4) || !aligned(codes, 4)) return PARO_ERR_ALIGN;
+    if (rot) {
+        paro_status st = check_rotation(rot);
+        if (st != PARO_OK) return st;
+        if (rot->c_in != c_in) return PARO_ERR_SHAPE;
+        if (!rot->plan) return PARO_ERR_UNSUPPORTED;
+    }
+    return from_hip(paro::launch_quantize_weight_mxfp4(rot, W, ldw, c_out, c_in, codes, scales, (hipStream_t)stream));
+}
+
+size_t paro_mxfp4_packed_bytes(const paro_mxfp4_weight *w)
+{
+    if (!w || w->c_in <= 0 || w->c_out <= 0 || w->c_in % 512 || w->c_out % 16) return 0;
+    return (size_t)w->c_out * w->c_in / 2 + (size_t)w->c_out * w->c_in / 32;
+}
+
+paro_status paro_mxfp4_repack(const paro_mxfp4_weight *w, void *packed_out, void *stream)
+{
+    paro_status st = check_mxfp4_weight(w, true);
+    if (st != PARO_OK) return st;
+    if (!w->codes || !w->scales || !packed_out) return PARO_ERR_NULL;
+    if (!aligned(packed_out, 256)) return PARO_ERR_ALIGN;
+    return from_hip(paro::launch_mxfp4_repack(*w, packed_out, (hipStream_t)stream));
+}
+
+paro_status paro_mxfp4_unpack(const paro_mxfp4_weight *w, uint8_t *codes, uint8_t *scales, void *stream)
+{
+    paro_status st = check_mxfp4_weight(w, w && w->packed);
+    if (st != PARO_OK) return st;
+    if (!codes || !scales) return PARO_ERR_NULL;
+    return from_hip(paro::launch_mxfp4_unpack(*w, codes, scales, (hipStream_t)stream));
+}
+
+paro_status paro_mxfp4_linear(const paro_mxfp4_weight *w, const uint32_t *x_codes, const uint8_t *x_scales, int32_t T,
+                              paro_half_t *Y, int64_t ldy, void *stream)
+{
+    paro_status st = check_mxfp4_weight(w, true);
+    if (st != PARO_OK) return st;
+    if (!x_codes || !x_scales || !Y) return PARO_ERR_NULL;
+    if (T <= 0 || ldy < w->c_out) return PARO_ERR_SHAPE;
+    if (ldy >= kMaxRowStride) return PARO_ERR_UNSUPPORTED;
+    if (!aligned(x_codes, 16) || !aligned(x_scales, 16) || !aligned(Y, 2)) return PARO_ERR_ALIGN;
+    if (!paro::mxfp4_linear_supported(*w)) return PARO_ERR_UNSUPPORTED;
+    return from_hip(paro::launch_mxfp4_linear(*w, x_codes, x_scales, T, Y, ldy, (hipStream_t)stream));
+}
+
+size_t paro_workspace_bytes_mxfp4(int32_t c_in, int32_t T)
+{
+    if (c_in <= 0 || T <= 0 || c_in % 512) return 0;
+    return round_up((size_t)T * c_in / 2, 256) + round_up((size_t)T * c_in / 32, 256);
+}
+
+paro_status paro_rotated_linear_mxfp4(const paro_rotation *rot, const paro_mxfp4_weight *w, const paro_half_t *X,
+                                      int64_t ldx, paro_half_t *Y, int64_t ldy, int32_t T, void *ws, size_t ws_bytes,
+                                      void *stream)
+{
+    paro_status st = check_rotation(rot);
+    if (st != PARO_OK) return st;
+    st = check_mxfp4_weight(w, true);
+    if (st != PARO_OK) return st;
+    if (rot->c_in != w->c_in) return PARO_ERR_SHAPE;
+    if (!X || !Y) return PARO_ERR_NULL;
+    if (T <= 0 || ldx < w->c_in || ldy < w->c_out) return PARO_ERR_SHAPE;
+    if (ldx >= kMaxRowStride || ldy >= kMaxRowStride) return PARO_ERR_UNSUPPORTED;
+    if (ldx % 2 || !aligned(X, 4) || !aligned(Y, 2)) return PARO_ERR_ALIGN;
+    if (!rot->plan || !paro::mxfp4_linear_supported(*w)) return PARO_ERR_UNSUPPORTED;
+    const size_t need = paro_workspace_bytes_mxfp4(w->c_in, T);
+    if (!ws || ws_bytes < need) return PARO_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return PARO_ERR_ALIGN;
+    uint32_t *xc = (uint32_t *)ws;
+    uint8_t *xs = (uint8_t *)ws + round_up((size_t)T * w->c_in / 2, 256);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = paro::launch_quantize_act_mxfp4(*rot, X, ldx, T, xc, xs, s);
+    if (e != hipSuccess) return PARO_ERR_HIP;
+    return from_hip(paro::launch_mxfp4_linear(*w, xc, xs, T, Y, ldy, s));
+}
+
 }  // extern "C"

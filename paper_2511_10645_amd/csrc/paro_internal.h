@@ -153,6 +153,14 @@ hipError_t launch_quantize_act(const paro_rotation &rot, const paro_half_t *X, i
                                paro_half_t *scales, uint8_t *zeros, hipStream_t s);
 
 // The same with the MXFP4 quantiser: E2M1 codes, one E8M0 scale byte per 32 channels.
+hipError_t launch_quantize_weight_mxfp4(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int N, int C,
+                                        uint32_t *codes, uint8_t *scales, hipStream_t s);
+// MXFP4 x MXFP4 linear (App. A.3) on the block-scaled FP4 matrix instruction
+hipError_t launch_mxfp4_repack(const paro_mxfp4_weight &w, void *packed_out, hipStream_t s);
+hipError_t launch_mxfp4_unpack(const paro_mxfp4_weight &w, uint8_t *codes, uint8_t *scales, hipStream_t s);
+bool mxfp4_linear_supported(const paro_mxfp4_weight &w);
+hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_codes, const uint8_t *x_scales, int T,
+                               paro_half_t *Y, int64_t ldy, hipStream_t s);
 hipError_t launch_quantize_act_mxfp4(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
                                      uint8_t *scales, hipStream_t s);
 

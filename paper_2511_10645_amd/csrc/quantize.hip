@@ -217,7 +217,10 @@ __device__ __forceinline__ uint32_t e2m1_code(float r)
     return c | ((__float_as_uint(r) >> 28) & 8u);
 }
 
-template <int K>
+// WSIDE: the rows are output rows of a dense weight and take the weight side of the transform
+// (the reciprocals of the activation-side multipliers, as in quantize_rows_kernel): Q(T W) of
+// App. A.3.  K < 0: no transform at all (rows quantised as they are).
+template <int K, bool WSIDE>
 __global__ __launch_bounds__(kActWaves * 64) void quantize_act_mxfp4_kernel(const uint32_t *__restrict__ plan,
                                                                              const _Float16 *__restrict__ X, int64_t ldx,
                                                                              int T, int C, uint32_t *__restrict__ codes,
@@ -231,19 +234,27 @@ __global__ __launch_bounds__(kActWaves * 64) void quantize_act_mxfp4_kernel(cons
     const int t = blockIdx.y * kActWaves + wave;
     if (t >= T) return;
 
-    LanePlan<K> P;
-    load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
-    *(uint32_t *)&s_stage[wave][2 * lane] = *((const uint32_t *)(X + (size_t)t * ldx + (size_t)g * kGroup) + lane);
-    __builtin_amdgcn_wave_barrier();
-    float a[1] = {(float)s_stage[wave][P.in_a] * P.sia};
-    float b[1] = {(float)s_stage[wave][P.in_b] * P.sib};
-    rotate_layers<K, 1>(P, a, b);
-    s_val[wave][P.out_a] = a[0] * P.soa;
-    s_val[wave][P.out_b] = b[0] * P.sob;
-    __builtin_amdgcn_wave_barrier();
-
-    // channel order from here: lane l holds channels 2l, 2l+1; 16 lanes = one 32-channel block
-    const float2 v = *(const float2 *)&s_val[wave][2 * lane];
+    const uint32_t raw = *((const uint32_t *)(X + (size_t)t * ldx + (size_t)g * kGroup) + lane);
+    float2 v;
+    if constexpr (K >= 0) {
+        LanePlan<K> P;
+        load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
+        *(uint32_t *)&s_stage[wave][2 * lane] = raw;
+        __builtin_amdgcn_wave_barrier();
+        const float ia = WSIDE ? 1.0f / P.sia : P.sia, ib = WSIDE ? 1.0f / P.sib : P.sib;
+        const float oa = WSIDE ? 1.0f / P.soa : P.soa, ob = WSIDE ? 1.0f / P.sob : P.sob;
+        float a[1] = {(float)s_stage[wave][P.in_a] * ia};
+        float b[1] = {(float)s_stage[wave][P.in_b] * ib};
+        rotate_layers<K, 1>(P, a, b);
+        s_val[wave][P.out_a] = a[0] * oa;
+        s_val[wave][P.out_b] = b[0] * ob;
+        __builtin_amdgcn_wave_barrier();
+        // channel order from here: lane l holds channels 2l, 2l+1; 16 lanes = one 32-channel block
+        v = *(const float2 *)&s_val[wave][2 * lane];
+    } else {
+        union { uint32_t u; _Float16 h[2]; } c; c.u = raw;
+        v = make_float2((float)c.h[0], (float)c.h[1]);
+    }
     float amax = fmaxf(fabsf(v.x), fabsf(v.y));
 #pragma unroll
     for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
@@ -256,30 +267,45 @@ __global__ __launch_bounds__(kActWaves * 64) void quantize_act_mxfp4_kernel(cons
     if ((lane & 15) == 0) scales[(size_t)t * (C / 32) + (size_t)g * (kGroup / 32) + (lane >> 4)] = (uint8_t)(e + 127);
 }
 
-template <int K>
-static hipError_t launch_quantize_act_mxfp4_k(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T,
-                                              uint32_t *codes, uint8_t *scales, hipStream_t s)
+template <int K, bool WSIDE>
+static hipError_t launch_quantize_mxfp4_k(const uint32_t *plan, int C, const paro_half_t *X, int64_t ldx, int T,
+                                          uint32_t *codes, uint8_t *scales, hipStream_t s)
 {
-    hipLaunchKernelGGL(quantize_act_mxfp4_kernel<K>, dim3(rot.c_in / kGroup, (T + kActWaves - 1) / kActWaves),
-                       dim3(kActWaves * 64), 0, s, (const uint32_t *)rot.plan, (const _Float16 *)X, ldx, T, rot.c_in, codes,
-                       scales);
+    hipLaunchKernelGGL((quantize_act_mxfp4_kernel<K, WSIDE>), dim3(C / kGroup, (T + kActWaves - 1) / kActWaves),
+                       dim3(kActWaves * 64), 0, s, plan, (const _Float16 *)X, ldx, T, C, codes, scales);
     return hipGetLastError();
+}
+
+template <bool WSIDE>
+static hipError_t launch_quantize_mxfp4_side(const paro_rotation *rot, int C, const paro_half_t *X, int64_t ldx, int T,
+                                             uint32_t *codes, uint8_t *scales, hipStream_t s)
+{
+    if (!rot) return launch_quantize_mxfp4_k<-1, WSIDE>(nullptr, C, X, ldx, T, codes, scales, s);
+    const uint32_t *plan = (const uint32_t *)rot->plan;
+    switch (rot->n_layers) {
+    case 0: return launch_quantize_mxfp4_k<0, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 1: return launch_quantize_mxfp4_k<1, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 2: return launch_quantize_mxfp4_k<2, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 3: return launch_quantize_mxfp4_k<3, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 4: return launch_quantize_mxfp4_k<4, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 5: return launch_quantize_mxfp4_k<5, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 6: return launch_quantize_mxfp4_k<6, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    case 7: return launch_quantize_mxfp4_k<7, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    default: return launch_quantize_mxfp4_k<8, WSIDE>(plan, C, X, ldx, T, codes, scales, s);
+    }
 }
 
 hipError_t launch_quantize_act_mxfp4(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T, uint32_t *codes,
                                      uint8_t *scales, hipStream_t s)
 {
-    switch (rot.n_layers) {
-    case 0: return launch_quantize_act_mxfp4_k<0>(rot, X, ldx, T, codes, scales, s);
-    case 1: return launch_quantize_act_mxfp4_k<1>(rot, X, ldx, T, codes, scales, s);
-    case 2: return launch_quantize_act_mxfp4_k<2>(rot, X, ldx, T, codes, scales, s);
-    case 3: return launch_quantize_act_mxfp4_k<3>(rot, X, ldx, T, codes, scales, s);
-    case 4: return launch_quantize_act_mxfp4_k<4>(rot, X, ldx, T, codes, scales, s);
-    case 5: return launch_quantize_act_mxfp4_k<5>(rot, X, ldx, T, codes, scales, s);
-    case 6: return launch_quantize_act_mxfp4_k<6>(rot, X, ldx, T, codes, scales, s);
-    case 7: return launch_quantize_act_mxfp4_k<7>(rot, X, ldx, T, codes, scales, s);
-    default: return launch_quantize_act_mxfp4_k<8>(rot, X, ldx, T, codes, scales, s);
-    }
+    return launch_quantize_mxfp4_side<false>(&rot, rot.c_in, X, ldx, T, codes, scales, s);
+}
+
+// rows of a dense weight [N][ldw]; rot == nullptr: no transform
+hipError_t launch_quantize_weight_mxfp4(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int N, int C,
+                                        uint32_t *codes, uint8_t *scales, hipStream_t s)
+{
+    return launch_quantize_mxfp4_side<true>(rot, C, W, ldw, N, codes, scales, s);
 }
 
 }  // namespace paro

@@ -241,6 +241,38 @@ def test_fused_or_two_launches_by_shape():
     assert scratch(4096, 28672, 2) == 2 * 4096 * 2
 
 
+def test_mxfp4_linear_argument_errors():
+    L = paro.lib()
+    M = B._CMxfp4Weight
+    ok = M(1024, 64, FAKE, FAKE, None, FAKE)
+    lin = lambda w, xc=FAKE, xs=FAKE, T=1, Y=FAKE, ldy=64: L.paro_mxfp4_linear(ctypes.byref(w) if w else None, xc, xs, T, Y, ldy, None)
+    assert lin(None) == E_NULL
+    assert lin(ok, xc=None) == E_NULL and lin(ok, Y=None) == E_NULL
+    assert lin(M(1024 + 128, 64, FAKE, FAKE, None, FAKE)) == E_SHAPE          # c_in not a multiple of 512
+    assert lin(M(1024, 72, FAKE, FAKE, None, FAKE), ldy=72) == E_SHAPE        # c_out not a multiple of 16
+    assert lin(ok, T=0) == E_SHAPE and lin(ok, ldy=32) == E_SHAPE
+    assert lin(ok, xc=FAKE + 4) == E_ALIGN and lin(ok, xs=FAKE + 8) == E_ALIGN
+    assert lin(M(1024, 64, FAKE, FAKE, None, None)) == E_UNSUP                # not repacked
+    assert lin(M(32768, 64, FAKE, FAKE, None, FAKE)) == E_UNSUP               # more than 60 K-slices
+    L.paro_mxfp4_packed_bytes.restype = ctypes.c_size_t
+    assert L.paro_mxfp4_packed_bytes(ctypes.byref(ok)) == 1024 * 64 // 2 + 1024 * 64 // 32
+    assert L.paro_mxfp4_packed_bytes(ctypes.byref(M(640, 64, FAKE, FAKE, None, None))) == 0
+    assert L.paro_mxfp4_repack(ctypes.byref(M(1024, 64, None, FAKE, None, None)), FAKE, None) == E_NULL
+    assert L.paro_mxfp4_repack(ctypes.byref(ok), FAKE + 16, None) == E_ALIGN
+    q = lambda r, W=FAKE, ldw=1024, c_in=1024, c_out=64, c=FAKE, s=FAKE: L.paro_mxfp4_quantize_weight(
+        ctypes.byref(r) if r else None, W, ldw, c_in, c_out, c, s, None)
+    assert q(None, W=None) == E_NULL and q(None, c_in=1000) == E_SHAPE and q(None, ldw=512) == E_SHAPE
+    assert q(_rot(c_in=512, plan=FAKE)) == E_SHAPE and q(_rot(c_in=1024)) == E_UNSUP
+    L.paro_workspace_bytes_mxfp4.restype = ctypes.c_size_t
+    assert L.paro_workspace_bytes_mxfp4(4096, 16) == 16 * 4096 // 2 + 16 * 4096 // 32
+    assert L.paro_workspace_bytes_mxfp4(4096, 1) == 2048 + 256 and L.paro_workspace_bytes_mxfp4(640, 1) == 0
+    full = lambda r, w, T=1, ws=FAKE, n=1 << 20: L.paro_rotated_linear_mxfp4(ctypes.byref(r), ctypes.byref(w), FAKE, 1024, FAKE, 64, T, ws, n, None)
+    assert full(_rot(c_in=512, plan=FAKE), ok) == E_SHAPE
+    assert full(_rot(c_in=1024), ok) == E_UNSUP
+    assert full(_rot(c_in=1024, plan=FAKE), ok, n=100) == E_WS
+    assert full(_rot(c_in=1024, plan=FAKE), ok, ws=FAKE + 64) == E_ALIGN
+
+
 def test_fwht_argument_errors():
     L = paro.lib()
     assert L.paro_fwht(None, 64, FAKE, 64, 1, 64, None) == 1
