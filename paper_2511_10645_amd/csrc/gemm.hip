@@ -368,7 +368,7 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float *__
 
 // Block slots of a launch over m_tiles x n_tiles tiles: the XCD patches are rounded up to whole
 // rounds of 8 (see the kernel's block numbering); slots without a tile exit at once.
-static void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, int &blocks)
+void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, int &blocks)
 {
     int pb = kPatchBlocks;
     while (pb > 1 && (long)m_tiles * n_tiles < 8L * pb) pb >>= 1;

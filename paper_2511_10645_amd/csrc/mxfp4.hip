@@ -274,9 +274,200 @@ static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t
     return hipGetLastError();
 }
 
+
+// ------------------------------------------------------------------------------------------
+// More than 16 tokens: tiled GEMM.  Block tile 256 tokens x 256 outputs x 128 channels (one K-step of
+// the matrix instruction: 64 bytes per row of either operand), 8 waves as 2 x 4, wave tile 128 x 64 =
+// 8 x 4 MFMA tiles of 16 x 16 (128 accumulator registers).  Per K-step a block fetches 16 KB of
+// activation codes and 16 KB of weight codes into registers (4 x 16 B per thread), one K-step ahead,
+// and writes them into the other half of a double-buffered LDS tile; one barrier per K-step.  LDS rows
+// are 64 bytes; the 16-byte chunk index is XOR-ed with bits 1..2 of the row so that the 16-byte
+// fragment reads of 8 consecutive rows fall into 8 different bank groups.  The scales do not go through
+// LDS: a lane needs one byte per (MFMA tile, K-step) and fetches it straight from memory one K-step
+// ahead - the activation side as the dword of its row's four blocks of that K-step, the weight side as
+// the repacked dword that covers four K-steps, each shifted so that the byte wanted is byte 0.
+// Blocks are numbered in XCD patches as in the fp16 GEMM.
+// ------------------------------------------------------------------------------------------
+struct MxGemmArgs {
+    const void *blob; uint32_t blob_bytes, scales_off;
+    const uint32_t *xc; const uint8_t *xs;
+    _Float16 *Y; int64_t ldy;
+    const _Float16 *bias;
+    int T, C, N, K128, KS;
+    int m_tiles, n_tiles, patch_m, patch_n;
+};
+
+constexpr int kMxBM = 256, kMxBN = 256;
+constexpr int kMxRowBytes = 64;                          // one K-step of one row
+
+__device__ __forceinline__ int mx_lds_off(int row, int chunk) { return row * kMxRowBytes + ((chunk ^ ((row >> 1) & 3)) << 4); }
+
+__global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [2][A 16 KB | B 16 KB]
+    constexpr int kStageBytes = (kMxBM + kMxBN) * kMxRowBytes;
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, j = bid >> 3;
+    const int pb = a.patch_m * a.patch_n;
+    const int patch = j / pb, q = j % pb;
+    const int m_patches = (a.m_tiles + a.patch_m - 1) / a.patch_m;
+    const int gp = patch * 8 + xcd;
+    const int pm = gp % m_patches, pn = gp / m_patches;
+    const int mt = pm * a.patch_m + q % a.patch_m, ntile = pn * a.patch_n + q / a.patch_m;
+    if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
+    const int m0 = mt * kMxBM, n0 = ntile * kMxBN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const __amdgpu_buffer_rsrc_t xr = mx_rsrc(a.xc, (uint32_t)((size_t)a.T * a.C / 2));
+    const __amdgpu_buffer_rsrc_t sr = mx_rsrc(a.xs, (uint32_t)((size_t)a.T * a.C / 32));
+    const __amdgpu_buffer_rsrc_t br = mx_rsrc(a.blob, a.blob_bytes);
+
+    // staging: thread -> 2 activation chunks (rows tid / 4 and tid / 4 + 128, chunk tid % 4) and 2 weight
+    // chunks (16-row tiles tid / 64 and tid / 64 + 8, lane of the repacked tile = tid % 64)
+    // (rows beyond T start beyond the end of the activation buffer: they read as zero)
+    uint32_t ga[2], gb[2];
+    int la[2], lb[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int row = (tid >> 2) + 128 * r, chunk = tid & 3;
+        ga[r] = (uint32_t)((size_t)(m0 + row) * (a.C / 2) + chunk * 16);
+        la[r] = mx_lds_off(row, chunk);
+        const int t16 = (tid >> 6) + 8 * r, n = lane & 15, kb = lane >> 4;
+        const int nt16 = n0 / 16 + t16;
+        gb[r] = nt16 * 16 < a.N ? ((uint32_t)nt16 * a.K128 * 64u + lane) * 16u : kOobM;
+        lb[r] = kMxBM * kMxRowBytes + mx_lds_off(t16 * 16 + n, kb);
+    }
+    u32x4 sa[2], sb[2];
+    auto load_stage = [&](int ks) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            sa[r] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)ga[r], ks * kMxRowBytes, 0);
+            sb[r] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)gb[r], ks * 1024, 0);
+        }
+    };
+    auto store_stage = [&](char *buf) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            *(u32x4 *)(buf + la[r]) = sa[r];
+            *(u32x4 *)(buf + lb[r]) = sb[r];
+        }
+    };
+    // scales: activation rows of the wave's 8 MFMA tiles, weight tiles of its 4.  Rows beyond T and tiles
+    // beyond N lie beyond the end of their buffers: the range check of the buffer resource returns 0 for them.
+    const int fr = lane & 15, fkb = lane >> 4;
+    const uint32_t xs_off0 = (uint32_t)((size_t)(m0 + wm * 128 + fr) * (a.C / 32));
+    const uint32_t xs_step = (uint32_t)(16 * (a.C / 32));
+    const uint32_t ws_off0 = a.scales_off + ((uint32_t)(n0 / 16 + wn * 4) * a.KS * 64u + lane) * 4u;
+    const uint32_t ws_step = (uint32_t)a.KS * 256u;
+    uint32_t xsc[8], xsc_n[8], wsc[4], wsc_n[4];
+    auto load_scales = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xsc_n[i] = __builtin_amdgcn_raw_buffer_load_b32(sr, (int)(xs_off0 + i * xs_step), ks * 4, 0);
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) wsc_n[jn] = __builtin_amdgcn_raw_buffer_load_b32(br, (int)(ws_off0 + jn * ws_step), (ks >> 2) * 256, 0);
+    };
+    // the lane's own byte becomes byte 0 (the instruction reads the byte its immediate selects, here always 0)
+    auto take_scales = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xsc[i] = xsc_n[i] >> (8 * fkb);
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) wsc[jn] = wsc_n[jn] >> (8 * (ks & 3));
+    };
+
+    float4v acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) acc[i][jn] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    const int n_ks = a.K128;
+    load_stage(0);
+    load_scales(0);
+    store_stage(smem_mx);
+    take_scales(0);
+    if (n_ks > 1) { load_stage(1); load_scales(1); }
+    __syncthreads();
+
+    const int fa_off = mx_lds_off(wm * 128 + fr, fkb);                              // + 1024 per MFMA tile (16 rows)
+    const int fb_off = kMxBM * kMxRowBytes + mx_lds_off(wn * 64 + fr, fkb);
+
+    for (int ks = 0; ks < n_ks; ++ks) {
+        const char *cur = smem_mx + (ks & 1) * kStageBytes;
+        char *nxt = smem_mx + ((ks & 1) ^ 1) * kStageBytes;
+        u32x4 fb[4];
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) fb[jn] = *(const u32x4 *)(cur + fb_off + jn * 1024);
+        u32x4 fa = *(const u32x4 *)(cur + fa_off);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const u32x4 fa_cur = fa;
+            if (i + 1 < 8) fa = *(const u32x4 *)(cur + fa_off + (i + 1) * 1024);
+            if (i == 2 && ks + 1 < n_ks) store_stage(nxt);                       // K-step ks + 1 has arrived by now
+            if (i == 3 && ks + 2 < n_ks) load_stage(ks + 2);
+#pragma unroll
+            for (int jn = 0; jn < 4; ++jn)
+                acc[i][jn] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(fa_cur), as_operand(fb[jn]), acc[i][jn], 4, 4, 0,
+                                                                              (int)xsc[i], 0, (int)wsc[jn]);
+        }
+        // scales of the next K-step (requested one K-step ago), then the request for the one after
+        take_scales(ks + 1);
+        if (ks + 2 < n_ks) load_scales(ks + 2);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds column fr, tokens 4 fkb + r of every 16 x 16 tile ----
+    const __amdgpu_buffer_rsrc_t yr = mx_rsrc(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn) {
+        const int n = n0 + wn * 64 + jn * 16 + fr;
+        const float bv = (a.bias && n < a.N) ? (float)a.bias[n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = m0 + wm * 128 + i * 16 + fkb * 4 + r;
+                union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(acc[i][jn][r] + bv);
+                const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.ldy + n) * 2) : kOobM;
+                __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
+            }
+    }
+}
+
+static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *xc, const uint8_t *xs, int T, paro_half_t *Y,
+                                    int64_t ldy, hipStream_t s)
+{
+    MxGemmArgs a;
+    a.blob = w.packed;
+    a.scales_off = (uint32_t)((size_t)w.c_out * w.c_in / 2);
+    a.blob_bytes = a.scales_off + (uint32_t)((size_t)w.c_out * w.c_in / 32);
+    a.xc = xc; a.xs = xs; a.Y = (_Float16 *)Y; a.ldy = ldy; a.bias = (const _Float16 *)w.bias;
+    a.T = T; a.C = w.c_in; a.N = w.c_out; a.K128 = w.c_in / 128; a.KS = w.c_in / 512;
+    a.m_tiles = (T + kMxBM - 1) / kMxBM; a.n_tiles = (w.c_out + kMxBN - 1) / kMxBN;
+    int blocks;
+    gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
+    constexpr int lds = 2 * (kMxBM + kMxBN) * kMxRowBytes;
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
+        hipError_t e = hipFuncSetAttribute((const void *)mxfp4_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        once_done(attr_done, dev);
+    }
+    hipLaunchKernelGGL(mxfp4_gemm_kernel, dim3(blocks), dim3(512), lds, s, a);
+    return hipGetLastError();
+}
+
+// Which kernel: the streaming kernel reads the whole weight once per 16 tokens, the GEMM once per 256 but
+// works on 256 x 256 tiles whatever T is.
+constexpr int kMxGemmMinTokens = 64;
+
 hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_codes, const uint8_t *x_scales, int T,
                                paro_half_t *Y, int64_t ldy, hipStream_t s)
 {
+    // the GEMM addresses the activations with 32-bit offsets
+    if (T >= kMxGemmMinTokens && (size_t)T * w.c_in / 2 < (1ull << 31) && ((size_t)(T - 1) * ldy + w.c_out) * 2 < (1ull << 31))
+        return launch_mxfp4_gemm(w, x_codes, x_scales, T, Y, ldy, s);
     for (int t0 = 0; t0 < T; t0 += 16) {
         const int tp = T - t0 < 16 ? T - t0 : 16;
         hipError_t e = launch_mxfp4_decode(w, x_codes + (size_t)t0 * (w.c_in / 8), x_scales + (size_t)t0 * (w.c_in / 32), tp,

@@ -155,6 +155,8 @@ hipError_t launch_quantize_act(const paro_rotation &rot, const paro_half_t *X, i
 // The same with the MXFP4 quantiser: E2M1 codes, one E8M0 scale byte per 32 channels.
 hipError_t launch_quantize_weight_mxfp4(const paro_rotation *rot, const paro_half_t *W, int64_t ldw, int N, int C,
                                         uint32_t *codes, uint8_t *scales, hipStream_t s);
+// XCD patches of a tiled launch (gemm.hip): tiles of one patch share panels through one XCD's L2
+void gemm_patches(int m_tiles, int n_tiles, int &patch_m, int &patch_n, int &blocks);
 // MXFP4 x MXFP4 linear (App. A.3) on the block-scaled FP4 matrix instruction
 hipError_t launch_mxfp4_repack(const paro_mxfp4_weight &w, void *packed_out, hipStream_t s);
 hipError_t launch_mxfp4_unpack(const paro_mxfp4_weight &w, uint8_t *codes, uint8_t *scales, hipStream_t s);

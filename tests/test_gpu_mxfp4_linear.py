@@ -84,6 +84,10 @@ def test_repack_and_unpack_are_bit_exact(P, shape):
     dict(seed=9206, T=37, C=1024, N=80, bias=True),           # three passes of up to 16 tokens
     dict(seed=9207, T=1, C=4096, N=6144, bias=False),         # more tiles than blocks
     dict(seed=9208, T=16, C=6144, N=4112, bias=False),        # 12 slices, 257 tiles
+    dict(seed=9209, T=64, C=512, N=256, bias=True),           # tiled kernel from 64 tokens: one tile, 4 K-steps
+    dict(seed=9210, T=300, C=1024, N=272, bias=True),         # ragged in tokens and in outputs
+    dict(seed=9211, T=257, C=2048, N=528, bias=False),        # a second token tile of one row
+    dict(seed=9212, T=1024, C=4096, N=1536, bias=True),       # 4 x 6 tiles, 32 K-steps
 ])
 def test_mxfp4_linear_against_oracle(P, case):
     import torch
@@ -139,6 +143,7 @@ def test_weight_quantiser_without_rotation_is_bit_exact(P):
     dict(seed=9501, T=1, c_in=512, c_out=64),
     dict(seed=9502, T=9, c_in=1024, c_out=144),
     dict(seed=9503, T=20, c_in=4096, c_out=96),
+    dict(seed=9504, T=150, c_in=1024, c_out=304),             # tiled kernel
 ])
 def test_whole_equation_from_dense_weight_and_fp16_activations(P, case):
     """Q(T W) on the GPU, Q(X T^-1) on the GPU inside paro_rotated_linear_mxfp4, then the contraction: the output must
