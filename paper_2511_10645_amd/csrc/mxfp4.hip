@@ -277,15 +277,17 @@ static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t
 
 // ------------------------------------------------------------------------------------------
 // More than 16 tokens: tiled GEMM.  Block tile 256 tokens x 256 outputs x 128 channels (one K-step of
-// the matrix instruction: 64 bytes per row of either operand), 8 waves as 2 x 4, wave tile 128 x 64 =
-// 8 x 4 MFMA tiles of 16 x 16 (128 accumulator registers).  Per K-step a block fetches 16 KB of
-// activation codes and 16 KB of weight codes into registers (4 x 16 B per thread), one K-step ahead,
-// and writes them into the other half of a double-buffered LDS tile; one barrier per K-step.  LDS rows
-// are 64 bytes; the 16-byte chunk index is XOR-ed with bits 1..2 of the row so that the 16-byte
-// fragment reads of 8 consecutive rows fall into 8 different bank groups.  The scales do not go through
-// LDS: a lane needs one byte per (MFMA tile, K-step) and fetches it straight from memory one K-step
-// ahead - the activation side as the dword of its row's four blocks of that K-step, the weight side as
-// the repacked dword that covers four K-steps, each shifted so that the byte wanted is byte 0.
+// the matrix instruction: 64 bytes per row of either operand), 8 waves side by side along the outputs:
+// wave tile 256 tokens x 32 outputs = 16 x 2 MFMA tiles of 16 x 16 (128 accumulator registers).
+//   - Weights never touch LDS: the repacked blob IS the operand order, every 16-row tile of a K-step
+//     is needed by exactly one wave, which fetches it straight into registers, 3 K-steps ahead.
+//   - Activations (16 KB of codes + 1 KB of scale bytes per K-step) are shared by all 8 waves: fetched
+//     into registers two K-steps ahead (2 x 16 B + 4 B per thread and stage), written one K-step ahead
+//     into the other half of a double-buffered LDS tile; one barrier per K-step.  LDS rows are 64
+//     bytes; the 16-byte chunk index is XOR-ed with bits 1..2 of the row so that the 16-byte fragment
+//     reads of 8 consecutive rows fall into 8 different bank groups.
+// What bounds the loop is the data in flight per compute unit (measured: with a single K-step in
+// flight a K-step takes 3 us, 7 x the time of its 32 MFMAs per wave), hence the deep register queues.
 // Blocks are numbered in XCD patches as in the fp16 GEMM.
 // ------------------------------------------------------------------------------------------
 struct MxGemmArgs {
@@ -299,13 +301,13 @@ struct MxGemmArgs {
 
 constexpr int kMxBM = 256, kMxBN = 256;
 constexpr int kMxRowBytes = 64;                          // one K-step of one row
+constexpr int kMxStageBytes = kMxBM * kMxRowBytes + kMxBM * 4;   // codes | scale dwords (4 blocks per row)
 
 __device__ __forceinline__ int mx_lds_off(int row, int chunk) { return row * kMxRowBytes + ((chunk ^ ((row >> 1) & 3)) << 4); }
 
 __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [2][A 16 KB | B 16 KB]
-    constexpr int kStageBytes = (kMxBM + kMxBN) * kMxRowBytes;
+    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [2][kMxStageBytes]
     const int bid = blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
     const int pb = a.patch_m * a.patch_n;
@@ -319,115 +321,124 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
     const __amdgpu_buffer_rsrc_t xr = mx_rsrc(a.xc, (uint32_t)((size_t)a.T * a.C / 2));
     const __amdgpu_buffer_rsrc_t sr = mx_rsrc(a.xs, (uint32_t)((size_t)a.T * a.C / 32));
     const __amdgpu_buffer_rsrc_t br = mx_rsrc(a.blob, a.blob_bytes);
-
-    // staging: thread -> 2 activation chunks (rows tid / 4 and tid / 4 + 128, chunk tid % 4) and 2 weight
-    // chunks (16-row tiles tid / 64 and tid / 64 + 8, lane of the repacked tile = tid % 64)
-    // (rows beyond T start beyond the end of the activation buffer: they read as zero)
-    uint32_t ga[2], gb[2];
-    int la[2], lb[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const int row = (tid >> 2) + 128 * r, chunk = tid & 3;
-        ga[r] = (uint32_t)((size_t)(m0 + row) * (a.C / 2) + chunk * 16);
-        la[r] = mx_lds_off(row, chunk);
-        const int t16 = (tid >> 6) + 8 * r, n = lane & 15, kb = lane >> 4;
-        const int nt16 = n0 / 16 + t16;
-        gb[r] = nt16 * 16 < a.N ? ((uint32_t)nt16 * a.K128 * 64u + lane) * 16u : kOobM;
-        lb[r] = kMxBM * kMxRowBytes + mx_lds_off(t16 * 16 + n, kb);
-    }
-    u32x4 sa[2], sb[2];
-    auto load_stage = [&](int ks) {
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            sa[r] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)ga[r], ks * kMxRowBytes, 0);
-            sb[r] = __builtin_amdgcn_raw_buffer_load_b128(br, (int)gb[r], ks * 1024, 0);
-        }
-    };
-    auto store_stage = [&](char *buf) {
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            *(u32x4 *)(buf + la[r]) = sa[r];
-            *(u32x4 *)(buf + lb[r]) = sb[r];
-        }
-    };
-    // scales: activation rows of the wave's 8 MFMA tiles, weight tiles of its 4.  Rows beyond T and tiles
-    // beyond N lie beyond the end of their buffers: the range check of the buffer resource returns 0 for them.
-    const int fr = lane & 15, fkb = lane >> 4;
-    const uint32_t xs_off0 = (uint32_t)((size_t)(m0 + wm * 128 + fr) * (a.C / 32));
-    const uint32_t xs_step = (uint32_t)(16 * (a.C / 32));
-    const uint32_t ws_off0 = a.scales_off + ((uint32_t)(n0 / 16 + wn * 4) * a.KS * 64u + lane) * 4u;
-    const uint32_t ws_step = (uint32_t)a.KS * 256u;
-    uint32_t xsc[8], xsc_n[8], wsc[4], wsc_n[4];
-    auto load_scales = [&](int ks) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) xsc_n[i] = __builtin_amdgcn_raw_buffer_load_b32(sr, (int)(xs_off0 + i * xs_step), ks * 4, 0);
-#pragma unroll
-        for (int jn = 0; jn < 4; ++jn) wsc_n[jn] = __builtin_amdgcn_raw_buffer_load_b32(br, (int)(ws_off0 + jn * ws_step), (ks >> 2) * 256, 0);
-    };
-    // the lane's own byte becomes byte 0 (the instruction reads the byte its immediate selects, here always 0)
-    auto take_scales = [&](int ks) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) xsc[i] = xsc_n[i] >> (8 * fkb);
-#pragma unroll
-        for (int jn = 0; jn < 4; ++jn) wsc[jn] = wsc_n[jn] >> (8 * (ks & 3));
-    };
-
-    float4v acc[8][4];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int jn = 0; jn < 4; ++jn) acc[i][jn] = float4v{0.f, 0.f, 0.f, 0.f};
-
     const int n_ks = a.K128;
-    load_stage(0);
-    load_scales(0);
-    store_stage(smem_mx);
-    take_scales(0);
-    if (n_ks > 1) { load_stage(1); load_scales(1); }
+
+    // ---- activations: thread -> chunks (row tid / 4 [+ 128], chunk tid % 4); threads 0..255 also the scale
+    // dword of row tid.  Rows beyond T start beyond the end of their buffers: they read as zero. ----
+    const uint32_t ga = (uint32_t)((size_t)(m0 + (tid >> 2)) * (a.C / 2) + (tid & 3) * 16);
+    const uint32_t ga_step = (uint32_t)(128 * (a.C / 2));
+    const int la0 = mx_lds_off(tid >> 2, tid & 3), la1 = mx_lds_off((tid >> 2) + 128, tid & 3);
+    const uint32_t gs = tid < kMxBM ? (uint32_t)((size_t)(m0 + tid) * (a.C / 32)) : kOobM;
+    const int ls = kMxBM * kMxRowBytes + (tid & (kMxBM - 1)) * 4;
+    struct AStage { u32x4 c0, c1; uint32_t sc; };
+    auto load_a = [&](int ks, AStage &st) {
+        const bool ok = ks < n_ks;
+        st.c0 = __builtin_amdgcn_raw_buffer_load_b128(xr, ok ? (int)ga : (int)kOobM, ks * kMxRowBytes, 0);
+        st.c1 = __builtin_amdgcn_raw_buffer_load_b128(xr, ok ? (int)(ga + ga_step) : (int)kOobM, ks * kMxRowBytes, 0);
+        st.sc = __builtin_amdgcn_raw_buffer_load_b32(sr, ok ? (int)gs : (int)kOobM, ks * 4, 0);
+    };
+    auto store_a = [&](char *buf, const AStage &st) {
+        *(u32x4 *)(buf + la0) = st.c0;
+        *(u32x4 *)(buf + la1) = st.c1;
+        if (tid < kMxBM) *(uint32_t *)(buf + ls) = st.sc;
+    };
+    // ---- weights: the wave's two 16-row tiles, as they lie in the blob ----
+    const int nt16 = n0 / 16 + wave * 2;
+    const bool n_ok0 = nt16 * 16 < a.N, n_ok1 = (nt16 + 1) * 16 < a.N;
+    const uint32_t gb0 = ((uint32_t)nt16 * a.K128 * 64u + lane) * 16u;
+    const uint32_t gb_step = (uint32_t)a.K128 * 1024u;
+    const uint32_t gw0 = a.scales_off + ((uint32_t)nt16 * a.KS * 64u + lane) * 4u;
+    const uint32_t gw_step = (uint32_t)a.KS * 256u;
+    struct BStage { u32x4 t0, t1; };
+    auto load_b = [&](int ks, BStage &st) {
+        const bool ok = ks < n_ks;
+        st.t0 = __builtin_amdgcn_raw_buffer_load_b128(br, ok && n_ok0 ? (int)gb0 : (int)kOobM, ks * 1024, 0);
+        st.t1 = __builtin_amdgcn_raw_buffer_load_b128(br, ok && n_ok1 ? (int)(gb0 + gb_step) : (int)kOobM, ks * 1024, 0);
+    };
+    uint32_t wq0 = 0, wq1 = 0, wq0_n, wq1_n;                 // scale dwords of the current / the next 512-channel slice
+    auto load_wscales = [&](int slice, uint32_t &d0, uint32_t &d1) {
+        const bool ok = slice < a.KS;
+        d0 = __builtin_amdgcn_raw_buffer_load_b32(br, ok && n_ok0 ? (int)gw0 : (int)kOobM, slice * 256, 0);
+        d1 = __builtin_amdgcn_raw_buffer_load_b32(br, ok && n_ok1 ? (int)(gw0 + gw_step) : (int)kOobM, slice * 256, 0);
+    };
+
+    float4v acc[16][2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[i][0] = float4v{0.f, 0.f, 0.f, 0.f}; acc[i][1] = float4v{0.f, 0.f, 0.f, 0.f}; }
+
+    // ---- prologue: A of K-step 0 into LDS, A of 1 and 2 in registers; B of 0, 1, 2 in registers ----
+    // Register queues are rings indexed by the K-step (A: 2 deep, B: 3 deep); a ring must be indexed at compile
+    // time and a value still in flight must never be copied (a copy waits for it), hence the loop body is
+    // written out for 12 consecutive K-steps (the rings' periods and the 4 K-steps of a scale dword) with one
+    // early exit.
+    AStage ar[2];
+    BStage bq[3];
+    load_a(0, ar[0]);
+    load_b(0, bq[0]);
+    load_wscales(0, wq0, wq1);
+    load_wscales(1, wq0_n, wq1_n);
+    store_a(smem_mx, ar[0]);
+    load_a(1, ar[1]);
+    load_a(2, ar[0]);
+    load_b(1, bq[1]);
+    load_b(2, bq[2]);
     __syncthreads();
 
-    const int fa_off = mx_lds_off(wm * 128 + fr, fkb);                              // + 1024 per MFMA tile (16 rows)
-    const int fb_off = kMxBM * kMxRowBytes + mx_lds_off(wn * 64 + fr, fkb);
+    const int fr = lane & 15, fkb = lane >> 4;
+    const int fa_off = mx_lds_off(fr, fkb);                                          // + 1024 per MFMA tile (16 rows)
+    const int fs_off = kMxBM * kMxRowBytes + fr * 4 + fkb;                           // + 64 per MFMA tile
 
-    for (int ks = 0; ks < n_ks; ++ks) {
-        const char *cur = smem_mx + (ks & 1) * kStageBytes;
-        char *nxt = smem_mx + ((ks & 1) ^ 1) * kStageBytes;
-        u32x4 fb[4];
+    for (int ks0 = 0; ks0 < n_ks; ks0 += 12) {
+        mx_static_while<12>([&](auto I) {
+            constexpr int u = I;
+            const int ks = ks0 + u;
+            if (ks >= n_ks) return false;
+            const char *cur = smem_mx + (u & 1) * kMxStageBytes;
+            char *nxt = smem_mx + ((u & 1) ^ 1) * kMxStageBytes;
+            AStage &an = ar[(u + 1) & 1];                                           // holds K-step ks + 1
+            BStage &bc = bq[u % 3];
+            const uint32_t ws0 = wq0 >> (8 * (u & 3)), ws1 = wq1 >> (8 * (u & 3));
+            u32x4 fa = *(const u32x4 *)(cur + fa_off);
+            uint32_t xsb = *(const uint8_t *)(cur + fs_off);
 #pragma unroll
-        for (int jn = 0; jn < 4; ++jn) fb[jn] = *(const u32x4 *)(cur + fb_off + jn * 1024);
-        u32x4 fa = *(const u32x4 *)(cur + fa_off);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const u32x4 fa_cur = fa;
-            if (i + 1 < 8) fa = *(const u32x4 *)(cur + fa_off + (i + 1) * 1024);
-            if (i == 2 && ks + 1 < n_ks) store_stage(nxt);                       // K-step ks + 1 has arrived by now
-            if (i == 3 && ks + 2 < n_ks) load_stage(ks + 2);
-#pragma unroll
-            for (int jn = 0; jn < 4; ++jn)
-                acc[i][jn] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(fa_cur), as_operand(fb[jn]), acc[i][jn], 4, 4, 0,
-                                                                              (int)xsc[i], 0, (int)wsc[jn]);
-        }
-        // scales of the next K-step (requested one K-step ago), then the request for the one after
-        take_scales(ks + 1);
-        if (ks + 2 < n_ks) load_scales(ks + 2);
-        __syncthreads();
+            for (int i = 0; i < 16; ++i) {
+                const u32x4 fa_cur = fa;
+                const uint32_t xs_cur = xsb;
+                if (i + 1 < 16) {
+                    fa = *(const u32x4 *)(cur + fa_off + (i + 1) * 1024);
+                    xsb = *(const uint8_t *)(cur + fs_off + (i + 1) * 64);
+                }
+                if (i == 4) {                                                       // K-step ks + 1 (requested two K-steps ago)
+                    store_a(nxt, an);
+                    load_a(ks + 3, an);
+                }
+                acc[i][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(fa_cur), as_operand(bc.t0), acc[i][0], 4, 4, 0, (int)xs_cur, 0, (int)ws0);
+                acc[i][1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(fa_cur), as_operand(bc.t1), acc[i][1], 4, 4, 0, (int)xs_cur, 0, (int)ws1);
+            }
+            load_b(ks + 3, bc);
+            if constexpr ((u & 3) == 3) {
+                wq0 = wq0_n; wq1 = wq1_n;                                          // requested 4 K-steps ago
+                load_wscales((ks >> 2) + 2, wq0_n, wq1_n);
+            }
+            __syncthreads();
+            return true;
+        });
     }
 
     // ---- epilogue: lane holds column fr, tokens 4 fkb + r of every 16 x 16 tile ----
     const __amdgpu_buffer_rsrc_t yr = mx_rsrc(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
 #pragma unroll
-    for (int jn = 0; jn < 4; ++jn) {
-        const int n = n0 + wn * 64 + jn * 16 + fr;
+    for (int jn = 0; jn < 2; ++jn) {
+        const int n = n0 + wave * 32 + jn * 16 + fr;
         const float bv = (a.bias && n < a.N) ? (float)a.bias[n] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 16; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int m = m0 + wm * 128 + i * 16 + fkb * 4 + r;
+                const int m = m0 + i * 16 + fkb * 4 + r;
                 union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(acc[i][jn][r] + bv);
                 const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.ldy + n) * 2) : kOobM;
                 __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
@@ -447,7 +458,7 @@ static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *
     a.m_tiles = (T + kMxBM - 1) / kMxBM; a.n_tiles = (w.c_out + kMxBN - 1) / kMxBN;
     int blocks;
     gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
-    constexpr int lds = 2 * (kMxBM + kMxBN) * kMxRowBytes;
+    constexpr int lds = 2 * kMxStageBytes;
     static std::atomic<uint64_t> attr_done{0};
     if (const int dev = once_pending(attr_done); dev >= 0) {
         hipError_t e = hipFuncSetAttribute((const void *)mxfp4_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
