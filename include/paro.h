@@ -350,6 +350,12 @@ paro_status paro_diag_mfma_f16(void *out, size_t out_bytes, int32_t blocks, int3
                                int32_t random_operands, void *stream);
 double paro_diag_mfma_f16_flops(int32_t blocks, int32_t iters);
 
+/* The same for the block-scaled FP4 instruction of paro_mxfp4_linear: every wave (8 per block of 512
+ * threads) runs iters x 32 independent 16x16x128 FP4 MFMAs.  out: device floats, blocks * 512. */
+paro_status paro_diag_mfma_fp4(void *out, size_t out_bytes, int32_t blocks, int32_t iters,
+                               int32_t random_operands, void *stream);
+double paro_diag_mfma_fp4_flops(int32_t blocks, int32_t iters);
+
 #ifdef __cplusplus
 }
 #endif

@@ -105,6 +105,10 @@ def lib():
         L.paro_diag_mfma_f16.argtypes = [vp, sz, i32, i32, i32, vp]
         L.paro_diag_mfma_f16_flops.argtypes = [i32, i32]
         L.paro_diag_mfma_f16_flops.restype = ctypes.c_double
+        L.paro_diag_mfma_fp4.argtypes = [vp, sz, i32, i32, i32, vp]
+        L.paro_diag_mfma_fp4.restype = ctypes.c_int
+        L.paro_diag_mfma_fp4_flops.argtypes = [i32, i32]
+        L.paro_diag_mfma_fp4_flops.restype = ctypes.c_double
         for name in ("paro_validate_pairs_host", "paro_select_pairs_host", "paro_rotation_plan_build", "paro_w4_repack", "paro_rotate_scale",
                      "paro_w4a16_linear", "paro_rotated_linear", "paro_rotated_linear_noalloc", "paro_w4_unpack_codes", "paro_w4_unpack_zeros",
                      "paro_w4_dequant", "paro_w4_quantize", "paro_rotated_linear_multi",
@@ -168,6 +172,13 @@ def paro_diag_mfma_f16(out: torch.Tensor, blocks: int, iters: int, random_operan
     _check(lib().paro_diag_mfma_f16(out.data_ptr(), out.numel() * 4, blocks, iters, int(random_operands), _stream()),
            "paro_diag_mfma_f16")
     return lib().paro_diag_mfma_f16_flops(blocks, iters)
+
+
+def paro_diag_mfma_fp4(out: torch.Tensor, blocks: int, iters: int, random_operands: bool) -> float:
+    """Launch the FP4 MFMA issue probe; returns the floating-point operations of the launch."""
+    _check(lib().paro_diag_mfma_fp4(out.data_ptr(), out.numel() * out.element_size(), blocks, iters, int(random_operands),
+                                    _stream()), "paro_diag_mfma_fp4")
+    return lib().paro_diag_mfma_fp4_flops(blocks, iters)
 
 
 def paro_select_pairs_host(order: np.ndarray, group: int, n_rotations: int, pairs_per_rotation: int):

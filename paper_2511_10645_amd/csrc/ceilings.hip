@@ -56,6 +56,32 @@ __global__ __launch_bounds__(256) void mfma_f16_kernel(float *out, int iters, in
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The block-scaled FP4 instruction of the MXFP4 linear, on register operands: 32 independent 16x16x128 MFMAs per
+// iteration and wave (as many accumulators as one K-step of that kernel's wave tile).
+typedef int v8ic __attribute__((ext_vector_type(8)));
+typedef float float4c __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512) void mfma_fp4_kernel(float *out, int iters, int random_operands)
+{
+    v8ic a = {0x22222222, 0x22222222, 0x22222222, 0x22222222, 0, 0, 0, 0}, b = a;      // all 1.0
+    int sa = 127, sb = 127;
+    if (random_operands) {
+        uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u;
+        for (int e = 0; e < 4; ++e) {
+            h = h * 1664525u + 1013904223u; a[e] = (int)(h ^ (h >> 13));
+            h = h * 1664525u + 1013904223u; b[e] = (int)(h ^ (h >> 11));
+        }
+        sa = 120 + (int)(h & 7); sb = 118 + (int)((h >> 8) & 7);
+    }
+    float4c acc[32];
+    for (int i = 0; i < 32; ++i) acc[i] = float4c{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int i = 0; i < 32; ++i) acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[i], 4, 4, 0, sa, 0, sb);
+    float s = 0;
+    for (int i = 0; i < 32; ++i) s += acc[i][0];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 }  // namespace paro
 
 extern "C" {
@@ -83,6 +109,23 @@ paro_status paro_diag_mfma_f16(void *out, size_t out_bytes, int32_t blocks, int3
     if (blocks < 1 || blocks > 65536 || iters < 1 || out_bytes < (size_t)blocks * 256 * sizeof(float)) return PARO_ERR_SHAPE;
     if ((uintptr_t)out % 4) return PARO_ERR_ALIGN;
     hipLaunchKernelGGL(paro::mfma_f16_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (float *)out, iters,
+                       random_operands);
+    return hipGetLastError() == hipSuccess ? PARO_OK : PARO_ERR_HIP;
+}
+
+double paro_diag_mfma_fp4_flops(int32_t blocks, int32_t iters)
+{
+    // 8 waves per block, 32 MFMAs per iteration, 2 * 16 * 16 * 128 flop each
+    return (double)blocks * 8.0 * (double)iters * 32.0 * 65536.0;
+}
+
+paro_status paro_diag_mfma_fp4(void *out, size_t out_bytes, int32_t blocks, int32_t iters, int32_t random_operands,
+                               void *stream)
+{
+    if (!out) return PARO_ERR_NULL;
+    if (blocks < 1 || blocks > 65536 || iters < 1 || out_bytes < (size_t)blocks * 512 * sizeof(float)) return PARO_ERR_SHAPE;
+    if ((uintptr_t)out % 4) return PARO_ERR_ALIGN;
+    hipLaunchKernelGGL(paro::mfma_fp4_kernel, dim3(blocks), dim3(512), 0, (hipStream_t)stream, (float *)out, iters,
                        random_operands);
     return hipGetLastError() == hipSuccess ? PARO_OK : PARO_ERR_HIP;
 }

@@ -282,8 +282,8 @@ static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t
 //   - Weights never touch LDS: the repacked blob IS the operand order, every 16-row tile of a K-step
 //     is needed by exactly one wave, which fetches it straight into registers, 3 K-steps ahead.
 //   - Activations (16 KB of codes + 1 KB of scale bytes per K-step) are shared by all 8 waves: fetched
-//     into registers two K-steps ahead (2 x 16 B + 4 B per thread and stage), written one K-step ahead
-//     into the other half of a double-buffered LDS tile; one barrier per K-step.  LDS rows are 64
+//     into registers five K-steps ahead (2 x 16 B + 4 B per thread and stage), written two K-steps ahead
+//     into a ring of three LDS tiles; one barrier per K-step.  LDS rows are 64
 //     bytes; the 16-byte chunk index is XOR-ed with bits 1..2 of the row so that the 16-byte fragment
 //     reads of 8 consecutive rows fall into 8 different bank groups.
 // What bounds the loop is the data in flight per compute unit (measured: with a single K-step in
@@ -302,12 +302,13 @@ struct MxGemmArgs {
 constexpr int kMxBM = 256, kMxBN = 256;
 constexpr int kMxRowBytes = 64;                          // one K-step of one row
 constexpr int kMxStageBytes = kMxBM * kMxRowBytes + kMxBM * 4;   // codes | scale dwords (4 blocks per row)
+constexpr int kMxChunk = 12;                             // K-steps written out in the loop body (24: no faster)
 
 __device__ __forceinline__ int mx_lds_off(int row, int chunk) { return row * kMxRowBytes + ((chunk ^ ((row >> 1) & 3)) << 4); }
 
 __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [2][kMxStageBytes]
+    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [3][kMxStageBytes]
     const int bid = blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
     const int pb = a.patch_m * a.patch_n;
@@ -369,20 +370,27 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) { acc[i][0] = float4v{0.f, 0.f, 0.f, 0.f}; acc[i][1] = float4v{0.f, 0.f, 0.f, 0.f}; }
 
-    // ---- prologue: A of K-step 0 into LDS, A of 1 and 2 in registers; B of 0, 1, 2 in registers ----
-    // Register queues are rings indexed by the K-step (A: 2 deep, B: 3 deep); a ring must be indexed at compile
-    // time and a value still in flight must never be copied (a copy waits for it), hence the loop body is
-    // written out for 12 consecutive K-steps (the rings' periods and the 4 K-steps of a scale dword) with one
-    // early exit.
-    AStage ar[2];
+    // ---- prologue ----
+    // LDS holds three K-steps of activations: step k is multiplied from buffer k % 3 while step k + 2 is written
+    // into buffer (k + 2) % 3 (last read during step k - 1, i.e. before the previous barrier), so the first
+    // fragments of step k + 1 (written during step k - 1) can be requested BEFORE the barrier that ends step k and
+    // the matrix pipe does not wait for an LDS round trip after every barrier.
+    // Register queues are rings indexed by the K-step (A: 3 deep, holding steps k + 2 .. k + 4; B: 3 deep,
+    // k .. k + 2); a ring must be indexed at compile time and a value still in flight must never be copied (a copy
+    // waits for it), hence the loop body is written out for kMxChunk consecutive K-steps (a multiple of the
+    // rings' periods and of the 4 K-steps of a scale dword) with one early exit.
+    AStage ar[3];
     BStage bq[3];
     load_a(0, ar[0]);
+    load_a(1, ar[1]);
     load_b(0, bq[0]);
     load_wscales(0, wq0, wq1);
     load_wscales(1, wq0_n, wq1_n);
     store_a(smem_mx, ar[0]);
-    load_a(1, ar[1]);
-    load_a(2, ar[0]);
+    store_a(smem_mx + kMxStageBytes, ar[1]);
+    load_a(2, ar[2]);
+    load_a(3, ar[0]);
+    load_a(4, ar[1]);
     load_b(1, bq[1]);
     load_b(2, bq[2]);
     __syncthreads();
@@ -390,33 +398,48 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     const int fr = lane & 15, fkb = lane >> 4;
     const int fa_off = mx_lds_off(fr, fkb);                                          // + 1024 per MFMA tile (16 rows)
     const int fs_off = kMxBM * kMxRowBytes + fr * 4 + fkb;                           // + 64 per MFMA tile
+    // fragments are requested kFragAhead tiles before their MFMAs (an LDS read takes several times as long as the
+    // two MFMAs of a tile), across the end of a K-step as well
+    constexpr int kFragAhead = 3;
+    u32x4 fa[kFragAhead + 1];
+    uint32_t xsb[kFragAhead + 1];
+#pragma unroll
+    for (int i = 0; i < kFragAhead; ++i) {
+        fa[i] = *(const u32x4 *)(smem_mx + fa_off + i * 1024);
+        xsb[i] = *(const uint8_t *)(smem_mx + fs_off + i * 64);
+    }
 
-    for (int ks0 = 0; ks0 < n_ks; ks0 += 12) {
-        mx_static_while<12>([&](auto I) {
+    for (int ks0 = 0; ks0 < n_ks; ks0 += kMxChunk) {
+        mx_static_while<kMxChunk>([&](auto I) {
             constexpr int u = I;
             const int ks = ks0 + u;
             if (ks >= n_ks) return false;
-            const char *cur = smem_mx + (u & 1) * kMxStageBytes;
-            char *nxt = smem_mx + ((u & 1) ^ 1) * kMxStageBytes;
-            AStage &an = ar[(u + 1) & 1];                                           // holds K-step ks + 1
+            const char *cur = smem_mx + (u % 3) * kMxStageBytes;
+            const char *nxt = smem_mx + ((u + 1) % 3) * kMxStageBytes;
+            char *fill = smem_mx + ((u + 2) % 3) * kMxStageBytes;
+            AStage &an = ar[(u + 2) % 3];                                           // holds K-step ks + 2
             BStage &bc = bq[u % 3];
             const uint32_t ws0 = wq0 >> (8 * (u & 3)), ws1 = wq1 >> (8 * (u & 3));
-            u32x4 fa = *(const u32x4 *)(cur + fa_off);
-            uint32_t xsb = *(const uint8_t *)(cur + fs_off);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const u32x4 fa_cur = fa;
-                const uint32_t xs_cur = xsb;
-                if (i + 1 < 16) {
-                    fa = *(const u32x4 *)(cur + fa_off + (i + 1) * 1024);
-                    xsb = *(const uint8_t *)(cur + fs_off + (i + 1) * 64);
+                constexpr int kRing = kFragAhead + 1;
+                const int ip = i + kFragAhead;
+                if (ip < 16) {
+                    fa[ip % kRing] = *(const u32x4 *)(cur + fa_off + ip * 1024);
+                    xsb[ip % kRing] = *(const uint8_t *)(cur + fs_off + ip * 64);
+                } else {
+                    fa[ip % kRing] = *(const u32x4 *)(nxt + fa_off + (ip - 16) * 1024);
+                    xsb[ip % kRing] = *(const uint8_t *)(nxt + fs_off + (ip - 16) * 64);
                 }
-                if (i == 4) {                                                       // K-step ks + 1 (requested two K-steps ago)
-                    store_a(nxt, an);
-                    load_a(ks + 3, an);
+                if (i == 4) {                                                       // requested three K-steps ago
+                    store_a(fill, an);
+                    load_a(ks + 5, an);
                 }
+                const u32x4 fa_cur = fa[i % kRing];
+                const uint32_t xs_cur = xsb[i % kRing];
                 acc[i][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(fa_cur), as_operand(bc.t0), acc[i][0], 4, 4, 0, (int)xs_cur, 0, (int)ws0);
                 acc[i][1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(fa_cur), as_operand(bc.t1), acc[i][1], 4, 4, 0, (int)xs_cur, 0, (int)ws1);
+                __builtin_amdgcn_sched_barrier(0);                                  // keep the reads this far ahead of their use
             }
             load_b(ks + 3, bc);
             if constexpr ((u & 3) == 3) {
@@ -428,21 +451,43 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
         });
     }
 
-    // ---- epilogue: lane holds column fr, tokens 4 fkb + r of every 16 x 16 tile ----
+    // ---- epilogue.  Lane holds column fr, tokens 4 fkb + r of every 16 x 16 tile; a 16 x 32 strip of the wave's
+    // tile goes through a wave-private 1 KB of LDS (the K loop's buffers are free now) and leaves as one 16-byte
+    // store per lane: 64 contiguous bytes per token row instead of 2-byte stores. ----
+    __syncthreads();
+    _Float16 *strip = (_Float16 *)(smem_mx + wave * 1024);                          // [16 tokens][32 outputs]
     const __amdgpu_buffer_rsrc_t yr = mx_rsrc(a.Y, (uint32_t)(((size_t)(a.T - 1) * a.ldy + a.N) * 2));
+    const int nw0 = n0 + wave * 32;
+    float bv[2];
 #pragma unroll
     for (int jn = 0; jn < 2; ++jn) {
-        const int n = n0 + wave * 32 + jn * 16 + fr;
-        const float bv = (a.bias && n < a.N) ? (float)a.bias[n] : 0.f;
+        const int n = nw0 + jn * 16 + fr;
+        bv[jn] = (a.bias && n < a.N) ? (float)a.bias[n] : 0.f;
+    }
+    const int orow = lane >> 2, ocol = (lane & 3) * 8;                               // this lane's 8 outputs of the strip
+    const bool row_wide = a.ldy % 8 == 0 && ((uintptr_t)a.Y % 16) == 0 && nw0 + 32 <= a.N;
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < 16; ++i) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = m0 + i * 16 + fkb * 4 + r;
-                union { _Float16 h; uint16_t u; } o; o.h = (_Float16)(acc[i][jn][r] + bv);
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) strip[(fkb * 4 + r) * 32 + jn * 16 + fr] = (_Float16)(acc[i][jn][r] + bv[jn]);
+        __builtin_amdgcn_wave_barrier();
+        const int m = m0 + i * 16 + orow;
+        if (row_wide) {
+            const u32x4 v = *(const u32x4 *)(strip + orow * 32 + ocol);
+            const uint32_t off = m < a.T ? (uint32_t)(((size_t)m * a.ldy + nw0 + ocol) * 2) : kOobM;
+            __builtin_amdgcn_raw_buffer_store_b128(v, yr, (int)off, 0, 0);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                union { _Float16 h; uint16_t u; } o; o.h = strip[orow * 32 + ocol + e];
+                const int n = nw0 + ocol + e;
                 const uint32_t off = (m < a.T && n < a.N) ? (uint32_t)(((size_t)m * a.ldy + n) * 2) : kOobM;
                 __builtin_amdgcn_raw_buffer_store_b16(o.u, yr, (int)off, 0, 0);
             }
+        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -458,7 +503,7 @@ static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *
     a.m_tiles = (T + kMxBM - 1) / kMxBM; a.n_tiles = (w.c_out + kMxBN - 1) / kMxBN;
     int blocks;
     gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
-    constexpr int lds = 2 * kMxStageBytes;
+    constexpr int lds = 3 * kMxStageBytes;
     static std::atomic<uint64_t> attr_done{0};
     if (const int dev = once_pending(attr_done); dev >= 0) {
         hipError_t e = hipFuncSetAttribute((const void *)mxfp4_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
