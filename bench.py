@@ -31,6 +31,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
+MFMA_FP4_PEAK_TFLOPS = 10100.0 # dense fp4
 # HBM bytes per launch of the dominant fused kernel (gate/up) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --pmc-probe [--config 4]`, scaled by the same counters on a 256 MiB copy
 # (profiles/decode_stream_pmc.md).  Config 2 runs the transform as a launch of its own: no single dominant launch.
@@ -356,6 +357,67 @@ def main() -> int:
         if prefill:
             prefill["frac_of_measured_mfma_random"] = round(prefill["layer_tflops"] / mf["random_operands"], 4)
 
+    # ---- the weight-activation form with MXFP4 operands (App. A.3) on the same shapes -----------------
+    w4a4 = None
+    if extras and not args.no_prefill and args.config == 1:
+        w4a4 = {"decode_tokens": T, "prefill_tokens": 2048, "per_linear": {}}
+        tot = {"dec": 0.0, "dec_whole": 0.0, "pre": 0.0, "pre_whole": 0.0, "bytes": 0, "flop": 0.0}
+        for L in lin:
+            shp = L["shape"]
+            N, C = shp.c_out, shp.c_in
+            nbytes = N * C // 2 + N * C // 32
+            w0 = paro.Mxfp4Weight(torch.randint(-2 ** 31, 2 ** 31 - 1, (N, C // 8), dtype=torch.int32, device=dev),
+                                  torch.randint(112, 122, (N, C // 32), dtype=torch.uint8, device=dev))
+            paro.paro_mxfp4_repack(w0)
+            n_cp = max(2, -(-args.pool_mb * (1 << 20) // nbytes))
+            pool = [w0]
+            for _ in range(n_cp - 1):
+                wc = paro.Mxfp4Weight(w0.codes, w0.scales)
+                wc.packed = w0.packed.clone()
+                wc.c.packed = wc.packed.data_ptr()
+                pool.append(wc)
+            rec = {}
+            for label, Tq in (("decode", T), ("prefill", 2048)):
+                xq = torch.as_tensor(pin.make_x(1, 0, Tq, C, pin.CONFIGS[1].n_outlier(C))[0]).to(dev)
+                xc, xs = paro.paro_rotate_scale_quantize_mxfp4(L["rot"], xq)
+                yq = torch.empty((Tq, N), dtype=torch.float16, device=dev)
+                wsq = torch.empty(paro.paro_workspace_bytes_mxfp4(C, Tq), dtype=torch.uint8, device=dev)
+                n_it = max(args.steps, n_cp) if label == "decode" else 10
+                us_c = graph_ms(lambda i: paro.paro_mxfp4_linear(pool[i % n_cp], xc, xs, yq), n_it, 2) * 1e3
+                us_w = graph_ms(lambda i: paro.paro_rotated_linear_mxfp4(L["rot"], pool[i % n_cp], xq, wsq, yq), n_it, 2) * 1e3
+                if label == "decode":
+                    rec.update({"us_contraction": round(us_c, 3), "us_whole": round(us_w, 3), "weight_bytes": nbytes,
+                                "contraction_gbs": round(nbytes / us_c / 1e3, 1)})
+                    tot["dec"] += us_c; tot["dec_whole"] += us_w; tot["bytes"] += nbytes
+                else:
+                    fl = 2.0 * Tq * C * N
+                    rec.update({"us_contraction_prefill": round(us_c, 1), "us_whole_prefill": round(us_w, 1),
+                                "contraction_tflops": round(fl / us_c / 1e6, 1)})
+                    tot["pre"] += us_c; tot["pre_whole"] += us_w; tot["flop"] += fl
+                del xq, xc, xs, yq, wsq
+            w4a4["per_linear"][shp.name] = rec
+            del pool, w0
+        w4a4["decode_layer_us"] = round(tot["dec"], 3)
+        w4a4["decode_layer_us_whole"] = round(tot["dec_whole"], 3)
+        w4a4["decode_layer_gbs"] = round(tot["bytes"] / tot["dec"] / 1e3, 1)
+        w4a4["decode_pct_of_hbm_peak"] = round(100.0 * tot["bytes"] / tot["dec"] / 1e3 / HBM_PEAK_GBS, 2)
+        w4a4["prefill_layer_tflops"] = round(tot["flop"] / tot["pre"] / 1e6, 1)
+        w4a4["prefill_layer_tflops_whole"] = round(tot["flop"] / tot["pre_whole"] / 1e6, 1)
+        w4a4["prefill_pct_of_mfma_fp4_peak"] = round(100.0 * tot["flop"] / tot["pre"] / 1e6 / MFMA_FP4_PEAK_TFLOPS, 2)
+        out_f4 = torch.empty(1024 * 512, dtype=torch.float32, device=dev)
+        mf4 = {}
+        for label, rnd in (("constant_operands", False), ("random_operands", True)):
+            paro.paro_diag_mfma_fp4(out_f4, 1024, 1000, rnd)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = paro.paro_diag_mfma_fp4(out_f4, 1024, 1000, rnd)
+            e1.record()
+            torch.cuda.synchronize()
+            mf4[label] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        w4a4["mfma_fp4_tflops_measured"] = mf4
+        w4a4["prefill_frac_of_measured_mfma_random"] = round(w4a4["prefill_layer_tflops"] / mf4["random_operands"], 4)
+
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -402,7 +464,7 @@ def main() -> int:
         "per_linear": per,
         "config2": config2, "config4": config4,
         "prefill": prefill, "own_transform_per_projection": multi,
-        "rotate_vs_fwht": fwht, "ceiling": ceiling,
+        "rotate_vs_fwht": fwht, "ceiling": ceiling, "w4a4_mxfp4": w4a4,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

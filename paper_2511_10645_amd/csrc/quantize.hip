@@ -223,7 +223,8 @@ __device__ __forceinline__ uint32_t e2m1_code(float r)
 template <int K, bool WSIDE>
 __global__ __launch_bounds__(kActWaves * 64) void quantize_act_mxfp4_kernel(const uint32_t *__restrict__ plan,
                                                                              const _Float16 *__restrict__ X, int64_t ldx,
-                                                                             int T, int C, uint32_t *__restrict__ codes,
+                                                                             int T, int C, int rows_per_wave,
+                                                                             uint32_t *__restrict__ codes,
                                                                              uint8_t *__restrict__ scales)
 {
     __shared__ _Float16 s_stage[kActWaves][kGroup];
@@ -231,48 +232,65 @@ __global__ __launch_bounds__(kActWaves * 64) void quantize_act_mxfp4_kernel(cons
     __shared__ __attribute__((aligned(4))) uint8_t s_codes[kActWaves][kLanes];
     const int g = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = blockIdx.y * kActWaves + wave;
-    if (t >= T) return;
+    const int t0 = (blockIdx.y * kActWaves + wave) * rows_per_wave;
+    if (t0 >= T) return;
+    const int t1 = min(T, t0 + rows_per_wave);
 
-    const uint32_t raw = *((const uint32_t *)(X + (size_t)t * ldx + (size_t)g * kGroup) + lane);
-    float2 v;
+    // The group's plan once per wave, then a run of rows: the plan is 7.4 KB at K = 8, re-reading it per row would
+    // outweigh the row itself 30 times.  (Rotating four rows at a time as the activation kernel does was measured
+    // and is no faster here: the conversion, not the permute latency, is what a row costs.)
+    LanePlan<K> P;
+    float ia = 1.f, ib = 1.f, oa = 1.f, ob = 1.f;
     if constexpr (K >= 0) {
-        LanePlan<K> P;
         load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
-        *(uint32_t *)&s_stage[wave][2 * lane] = raw;
-        __builtin_amdgcn_wave_barrier();
-        const float ia = WSIDE ? 1.0f / P.sia : P.sia, ib = WSIDE ? 1.0f / P.sib : P.sib;
-        const float oa = WSIDE ? 1.0f / P.soa : P.soa, ob = WSIDE ? 1.0f / P.sob : P.sob;
-        float a[1] = {(float)s_stage[wave][P.in_a] * ia};
-        float b[1] = {(float)s_stage[wave][P.in_b] * ib};
-        rotate_layers<K, 1>(P, a, b);
-        s_val[wave][P.out_a] = a[0] * oa;
-        s_val[wave][P.out_b] = b[0] * ob;
-        __builtin_amdgcn_wave_barrier();
-        // channel order from here: lane l holds channels 2l, 2l+1; 16 lanes = one 32-channel block
-        v = *(const float2 *)&s_val[wave][2 * lane];
-    } else {
-        union { uint32_t u; _Float16 h[2]; } c; c.u = raw;
-        v = make_float2((float)c.h[0], (float)c.h[1]);
+        ia = WSIDE ? 1.0f / P.sia : P.sia; ib = WSIDE ? 1.0f / P.sib : P.sib;
+        oa = WSIDE ? 1.0f / P.soa : P.soa; ob = WSIDE ? 1.0f / P.sob : P.sob;
     }
-    float amax = fmaxf(fabsf(v.x), fabsf(v.y));
+    uint32_t raw = *((const uint32_t *)(X + (size_t)t0 * ldx + (size_t)g * kGroup) + lane);
+    for (int t = t0; t < t1; ++t) {
+        const uint32_t cur = raw;
+        if (t + 1 < t1) raw = *((const uint32_t *)(X + (size_t)(t + 1) * ldx + (size_t)g * kGroup) + lane);
+        float2 v;
+        if constexpr (K >= 0) {
+            *(uint32_t *)&s_stage[wave][2 * lane] = cur;
+            __builtin_amdgcn_wave_barrier();
+            float a[1] = {(float)s_stage[wave][P.in_a] * ia};
+            float b[1] = {(float)s_stage[wave][P.in_b] * ib};
+            rotate_layers<K, 1>(P, a, b);
+            s_val[wave][P.out_a] = a[0] * oa;
+            s_val[wave][P.out_b] = b[0] * ob;
+            __builtin_amdgcn_wave_barrier();
+            // channel order from here: lane l holds channels 2l, 2l+1; 16 lanes = one 32-channel block
+            v = *(const float2 *)&s_val[wave][2 * lane];
+        } else {
+            union { uint32_t u; _Float16 h[2]; } c; c.u = cur;
+            v = make_float2((float)c.h[0], (float)c.h[1]);
+        }
+        float amax = fmaxf(fabsf(v.x), fabsf(v.y));
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-    int e = (int)(__float_as_uint(amax) >> 23) - 127 - 2;
-    if (e < -127) e = -127;
-    const uint32_t byte = e2m1_code(ldexpf(v.x, -e)) | (e2m1_code(ldexpf(v.y, -e)) << 4);
-    s_codes[wave][lane] = (uint8_t)byte;
-    __builtin_amdgcn_wave_barrier();
-    if (lane < kGroup / 8) codes[(size_t)t * (C / 8) + (size_t)g * (kGroup / 8) + lane] = *(const uint32_t *)&s_codes[wave][4 * lane];
-    if ((lane & 15) == 0) scales[(size_t)t * (C / 32) + (size_t)g * (kGroup / 32) + (lane >> 4)] = (uint8_t)(e + 127);
+        for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        int e = (int)(__float_as_uint(amax) >> 23) - 127 - 2;
+        if (e < -127) e = -127;
+        const uint32_t byte = e2m1_code(ldexpf(v.x, -e)) | (e2m1_code(ldexpf(v.y, -e)) << 4);
+        s_codes[wave][lane] = (uint8_t)byte;
+        __builtin_amdgcn_wave_barrier();
+        if (lane < kGroup / 8) codes[(size_t)t * (C / 8) + (size_t)g * (kGroup / 8) + lane] = *(const uint32_t *)&s_codes[wave][4 * lane];
+        if ((lane & 15) == 0) scales[(size_t)t * (C / 32) + (size_t)g * (kGroup / 32) + (lane >> 4)] = (uint8_t)(e + 127);
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 template <int K, bool WSIDE>
 static hipError_t launch_quantize_mxfp4_k(const uint32_t *plan, int C, const paro_half_t *X, int64_t ldx, int T,
                                           uint32_t *codes, uint8_t *scales, hipStream_t s)
 {
-    hipLaunchKernelGGL((quantize_act_mxfp4_kernel<K, WSIDE>), dim3(C / kGroup, (T + kActWaves - 1) / kActWaves),
-                       dim3(kActWaves * 64), 0, s, plan, (const _Float16 *)X, ldx, T, C, codes, scales);
+    // runs of up to 32 rows per wave, shorter while that leaves fewer than ~4096 waves
+    const int G = C / kGroup;
+    int rpw = 32;
+    while (rpw > 1 && (int64_t)G * ((T + rpw - 1) / rpw) < 4096) rpw >>= 1;
+    const int waves_t = (T + rpw - 1) / rpw;
+    hipLaunchKernelGGL((quantize_act_mxfp4_kernel<K, WSIDE>), dim3(G, (waves_t + kActWaves - 1) / kActWaves),
+                       dim3(kActWaves * 64), 0, s, plan, (const _Float16 *)X, ldx, T, C, rpw, codes, scales);
     return hipGetLastError();
 }
 

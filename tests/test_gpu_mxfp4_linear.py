@@ -88,6 +88,8 @@ def test_repack_and_unpack_are_bit_exact(P, shape):
     dict(seed=9210, T=300, C=1024, N=272, bias=True),         # ragged in tokens and in outputs
     dict(seed=9211, T=257, C=2048, N=528, bias=False),        # a second token tile of one row
     dict(seed=9212, T=1024, C=4096, N=1536, bias=True),       # 4 x 6 tiles, 32 K-steps
+    dict(seed=9213, T=70, C=512, N=64, bias=True, pad=2),     # output rows that are not 16-byte aligned
+    dict(seed=9214, T=3, C=512, N=48, bias=False, pad=6),
 ])
 def test_mxfp4_linear_against_oracle(P, case):
     import torch
@@ -102,8 +104,12 @@ def test_mxfp4_linear_against_oracle(P, case):
     w.c.codes = w.c.scales = None
     x_codes = torch.as_tensor(_words(xc).view(np.int32)).cuda()
     x_scales = torch.as_tensor(xs).cuda()
-    got = P.paro_mxfp4_linear(w, x_codes, x_scales).cpu().numpy()
+    pad = case.get("pad", 0)
+    Y = torch.full((T, N + pad), 7.0, dtype=torch.float16, device="cuda")
+    got = P.paro_mxfp4_linear(w, x_codes, x_scales, Y[:, :N]).cpu().numpy()
     _check(got, xc, xs, wc, ws, bias, "every output")
+    if pad:
+        assert bool((Y[:, N:] == 7.0).all())                 # nothing written beyond a row's outputs
 
 
 def test_zero_blocks_and_extreme_scales(P):
