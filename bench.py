@@ -62,6 +62,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (config 3) side measurement")
     ap.add_argument("--no-extras", action="store_true", help="headline and per-linear figures only")
+    ap.add_argument("--mxfp4-probe", action="store_true",
+                    help="for rocprofv3: a few launches of the MXFP4 x MXFP4 linear on gate/up (1 token and 2048) and nothing else")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: 3 plain 256 MiB device copies, then on the dominant linear 3 fused "
                          "launches, 3 bare launches and 3 pure-read launches over the same bytes, each on distinct "
@@ -208,6 +210,26 @@ def main() -> int:
 
     cfg = pin.CONFIGS[args.config]
     T = cfg.tokens[0]
+
+    if args.mxfp4_probe:
+        shp = max(cfg.linears, key=lambda q: q.c_in * q.c_out)
+        N, C = shp.c_out, shp.c_in
+        w0 = paro.Mxfp4Weight(torch.randint(-2 ** 31, 2 ** 31 - 1, (N, C // 8), dtype=torch.int32, device=dev),
+                              torch.randint(112, 122, (N, C // 32), dtype=torch.uint8, device=dev))
+        paro.paro_mxfp4_repack(w0)
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        for Tq in (1, 2048):
+            xc = torch.randint(-2 ** 31, 2 ** 31 - 1, (Tq, C // 8), dtype=torch.int32, device=dev)
+            xs = torch.randint(118, 126, (Tq, C // 32), dtype=torch.uint8, device=dev)
+            yq = torch.empty((Tq, N), dtype=torch.float16, device=dev)
+            for _ in range(5):
+                paro.paro_mxfp4_linear(w0, xc, xs, yq)
+        torch.cuda.synchronize()
+        return 0
+
     lin = build_layer(args.config, T)
 
     if args.pmc_probe:
