@@ -94,15 +94,16 @@ struct WsLayout {
 WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T, bool always_fuse = false)
 {
     WsLayout L{0, 0, 0, 0, 0};
+    const bool fused = fused_decode(rot, w, T, always_fuse);
     if (fast_weight(w)) {
-        DecodeGeometry d = decode_geometry(w->c_in, w->c_out, T);
-        size_t wide = decode_wide_partial_bytes(w->c_in, w->c_out, T);
-        size_t part = d.partial_bytes > wide ? d.partial_bytes : wide;
+        // partial sums of the kernel this call launches: the K-major one (one part per K-slice) or the bare one
+        // (parts only beyond 6144 channels)
+        const size_t part = fused ? decode_geometry(w->c_in, w->c_out, T).partial_bytes
+                                  : decode_wide_partial_bytes(w->c_in, w->c_out, T);
         // the bare linear without partial sums to exchange needs no workspace at all
         L.exchange_bytes = (rot || part) ? kWsPartialOff + round_up(part, 256) : 0;
         if (T > kDecodeMaxTokens) L.gemm_bytes = round_up(gemm_scratch_bytes(*w, T), 256);
     }
-    const bool fused = fused_decode(rot, w, T, always_fuse);
     L.xr_bytes = (rot && !fused) ? round_up((size_t)T * w->c_in * 2, 256) : 0;
     L.scratch_bytes = L.xr_bytes + L.gemm_bytes;
     L.total = L.exchange_bytes + L.scratch_bytes;

@@ -88,12 +88,15 @@ def test_linear_argument_errors_and_workspace():
     assert lin(_w(), ldy=256) == E_SHAPE
     assert lin(_w(), ldx=516) == E_ALIGN
     assert lin(_w(qweight=FAKE + 4)) == E_ALIGN
-    # a repacked 1024-channel weight needs the split-K workspace
+    # a repacked weight needs no workspace for the bare linear up to 6144 channels (all K-slices in one block) ...
     w2 = _w(c_in=1024, packed=FAKE)
-    need = L.paro_workspace_bytes(None, ctypes.byref(w2), 1)
-    assert need >= 2 * 1 * 512 * 4
-    assert lin(w2, ldx=1024) == E_WS
-    assert lin(w2, ldx=1024, ws=FAKE, n=need - 1) == E_WS
+    assert L.paro_workspace_bytes(None, ctypes.byref(w2), 1) == 0
+    # ... and the partial sums of its blocks along K beyond that
+    w3 = _w(c_in=14336, packed=FAKE)
+    need = L.paro_workspace_bytes(None, ctypes.byref(w3), 1)
+    assert need >= 256 + 4 * 1 * 512 * 4
+    assert lin(w3, ldx=14336) == E_WS
+    assert lin(w3, ldx=14336, ws=FAKE, n=need - 1) == E_WS
     rl = lambda r, w, ws=FAKE, n=1 << 30: L.paro_rotated_linear(ctypes.byref(r), ctypes.byref(w), FAKE, 1024, FAKE, 512, 1, ws, n, None)
     assert rl(_rot(c_in=512), w2) == E_SHAPE                       # rot.c_in != w.c_in
     assert rl(_rot(c_in=1024), w2, ws=None, n=0) == E_WS
@@ -220,6 +223,30 @@ def test_workspace_parts():
     assert L.paro_workspace_bytes(ctypes.byref(r2), ctypes.byref(w), 1) - L.paro_workspace_exchange_bytes(
         ctypes.byref(r2), ctypes.byref(w), 1) == 4096
     assert L.paro_workspace_exchange_bytes(ctypes.byref(_rot(c_in=512)), ctypes.byref(w), 1) == 0     # mismatch: 0
+
+
+def test_exchange_part_covers_the_partial_sums_of_every_shape():
+    """Wherever a decode launch exchanges partial sums between blocks it stores K-parts x T x c_out fp32 words behind
+    the 256-byte header; the size the library reports must cover them for every shape, also for one K-slice with a
+    very wide output (no exchange at all: header only)."""
+    L = paro.lib()
+    for c_in in (512, 1024, 4096, 6144, 6656, 14336, 27648):
+        for c_out in (16, 4096, 28672, 98304):
+            for T in (1, 2, 4, 5, 16):
+                w = _w(c_in=c_in, c_out=c_out, packed=FAKE)
+                r = _rot(c_in=c_in, plan=FAKE)
+                ks = c_in // 512
+                fused = L.paro_workspace_bytes(ctypes.byref(r), ctypes.byref(w), T) == L.paro_workspace_exchange_bytes(
+                    ctypes.byref(r), ctypes.byref(w), T)
+                ex = L.paro_workspace_exchange_bytes(ctypes.byref(r), ctypes.byref(w), T)
+                if T <= 4 and fused and ks > 1:
+                    assert ex >= 256 + ks * T * c_out * 4, (c_in, c_out, T, ex)      # K-major kernel: one part per slice
+                if ks == 1:
+                    assert ex == 256, (c_in, c_out, T, ex)
+                bare = L.paro_workspace_exchange_bytes(None, ctypes.byref(w), T)
+                parts = 1 if ks <= 12 else (ks + 7) // 8                              # blocks along K of the bare kernel
+                assert bare == (0 if parts == 1 else 256 + (parts * T * c_out * 4 + 255) // 256 * 256), (c_in, c_out, T, bare)
+                assert ex >= bare
 
 
 def test_fused_or_two_launches_by_shape():

@@ -193,6 +193,7 @@ def test_bare_linear(P, packed, case):
     got = P.paro_w4a16_linear(w, dev(li.x), ws).cpu().numpy()
     _assert_linear(got, y, allowed, f"bare {case} packed={packed}")
     ex = P.paro_workspace_exchange_bytes(None, w, case["T"])
+    ws.exchange_bytes = ex                                              # 0: the buffer is scratch only, no header to read
     assert ws.partials_clean(ex) and ws.error_word() == 0               # partial sums left zero-filled
 
 
@@ -529,6 +530,27 @@ def test_selected_pairs_through_the_gpu_path(P):
     w = make_w(P, li)
     ws = P.Workspace(P.paro_workspace_bytes(rot, w, T))
     _assert_linear(P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy(), y, allowed, "selected pairs")
+
+
+def test_one_k_slice_with_a_very_wide_output(P):
+    """512 input channels (one K-slice: nothing to exchange between blocks) against 98304 outputs (24 MB of codes, the
+    size class that otherwise takes the 8-wave split-K blocks): the workspace holds the header only, and the guard
+    bytes placed behind it must stay untouched."""
+    import torch
+    li = pin.make_custom(7901, 1, 512, 98304, n_outlier=2)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    y, allowed = _linear_ref(li, u)
+    rot, w = make_rot(P, li), make_w(P, li)
+    need = P.paro_workspace_bytes(rot, w, 1)
+    assert need == P.paro_workspace_exchange_bytes(rot, w, 1) == 256
+    guard = 1 << 20
+    ws = P.Workspace(need + guard)
+    ws.buf[need:] = 0x5A
+    ws.nbytes = need
+    got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
+    _assert_linear(got, y, allowed, "one K-slice, 98304 outputs")
+    assert bool((ws.buf[need:need + guard] == 0x5A).all())
+    assert ws.error_word() == 0
 
 
 def test_seeded_sweep_of_shapes(P):
