@@ -132,7 +132,7 @@ constexpr int kActWaves = 4;
 template <int K>
 __global__ __launch_bounds__(kActWaves * 64) void quantize_act_kernel(const uint32_t *__restrict__ plan,
                                                                        const _Float16 *__restrict__ X, int64_t ldx, int T,
-                                                                       int C, uint32_t *__restrict__ codes,
+                                                                       int C, int rows_per_wave, uint32_t *__restrict__ codes,
                                                                        _Float16 *__restrict__ scales,
                                                                        uint8_t *__restrict__ zeros)
 {
@@ -140,49 +140,60 @@ __global__ __launch_bounds__(kActWaves * 64) void quantize_act_kernel(const uint
     __shared__ uint8_t s_codes[kActWaves][kGroup];
     const int g = blockIdx.x, G = C / kGroup;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = blockIdx.y * kActWaves + wave;
-    if (t >= T) return;
+    const int t0 = (blockIdx.y * kActWaves + wave) * rows_per_wave;
+    if (t0 >= T) return;
+    const int t1 = min(T, t0 + rows_per_wave);
 
+    // the group's plan once per wave, then a run of tokens
     LanePlan<K> P;
     load_lane_plan<K>(plan + (size_t)g * plan_group_dwords(K), lane, P);
-    *(uint32_t *)&s_stage[wave][2 * lane] = *((const uint32_t *)(X + (size_t)t * ldx + (size_t)g * kGroup) + lane);
-    __builtin_amdgcn_wave_barrier();
-    float a[1] = {(float)s_stage[wave][P.in_a] * P.sia};
-    float b[1] = {(float)s_stage[wave][P.in_b] * P.sib};
-    rotate_layers<K, 1>(P, a, b);
-    const float va = a[0] * P.soa, vb = b[0] * P.sob;
+    uint32_t raw = *((const uint32_t *)(X + (size_t)t0 * ldx + (size_t)g * kGroup) + lane);
+    for (int t = t0; t < t1; ++t) {
+        *(uint32_t *)&s_stage[wave][2 * lane] = raw;
+        if (t + 1 < t1) raw = *((const uint32_t *)(X + (size_t)(t + 1) * ldx + (size_t)g * kGroup) + lane);
+        __builtin_amdgcn_wave_barrier();
+        float a[1] = {(float)s_stage[wave][P.in_a] * P.sia};
+        float b[1] = {(float)s_stage[wave][P.in_b] * P.sib};
+        rotate_layers<K, 1>(P, a, b);
+        const float va = a[0] * P.soa, vb = b[0] * P.sob;
 
-    float mn = fminf(va, vb), mx = fmaxf(va, vb);
+        float mn = fminf(va, vb), mx = fmaxf(va, vb);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        mn = fminf(mn, __shfl_xor(mn, off, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    }
-    float s32 = (mx - mn) / 15.0f;
-    if (!(s32 >= 6.103515625e-05f)) s32 = 6.103515625e-05f;
-    const _Float16 s16 = (_Float16)s32;
-    const float s = (float)s16;
-    float zf = -rintf(mn / s);
-    zf = fminf(fmaxf(zf, 0.0f), 15.0f);
-    s_codes[wave][P.out_a] = (uint8_t)fminf(fmaxf(rintf(va / s) + zf, 0.0f), 15.0f);
-    s_codes[wave][P.out_b] = (uint8_t)fminf(fmaxf(rintf(vb / s) + zf, 0.0f), 15.0f);
-    __builtin_amdgcn_wave_barrier();
-    if (lane < kGroup / 8) {
-        uint32_t word = 0;
+        for (int off = 32; off > 0; off >>= 1) {
+            mn = fminf(mn, __shfl_xor(mn, off, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        }
+        float s32 = (mx - mn) / 15.0f;
+        if (!(s32 >= 6.103515625e-05f)) s32 = 6.103515625e-05f;
+        const _Float16 s16 = (_Float16)s32;
+        const float s = (float)s16;
+        float zf = -rintf(mn / s);
+        zf = fminf(fmaxf(zf, 0.0f), 15.0f);
+        s_codes[wave][P.out_a] = (uint8_t)fminf(fmaxf(rintf(va / s) + zf, 0.0f), 15.0f);
+        s_codes[wave][P.out_b] = (uint8_t)fminf(fmaxf(rintf(vb / s) + zf, 0.0f), 15.0f);
+        __builtin_amdgcn_wave_barrier();
+        if (lane < kGroup / 8) {
+            uint32_t word = 0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) word |= (uint32_t)s_codes[wave][lane * 8 + k] << (4 * k);
-        codes[(size_t)t * (C / 8) + (size_t)g * (kGroup / 8) + lane] = word;
+            for (int k = 0; k < 8; ++k) word |= (uint32_t)s_codes[wave][lane * 8 + k] << (4 * k);
+            codes[(size_t)t * (C / 8) + (size_t)g * (kGroup / 8) + lane] = word;
+        }
+        if (lane == 0) { scales[(size_t)t * G + g] = s16; zeros[(size_t)t * G + g] = (uint8_t)zf; }
+        __builtin_amdgcn_wave_barrier();
     }
-    if (lane == 0) { scales[(size_t)t * G + g] = s16; zeros[(size_t)t * G + g] = (uint8_t)zf; }
 }
 
 template <int K>
 static hipError_t launch_quantize_act_k(const paro_rotation &rot, const paro_half_t *X, int64_t ldx, int T,
                                         uint32_t *codes, paro_half_t *scales, uint8_t *zeros, hipStream_t s)
 {
-    hipLaunchKernelGGL(quantize_act_kernel<K>, dim3(rot.c_in / kGroup, (T + kActWaves - 1) / kActWaves),
-                       dim3(kActWaves * 64), 0, s, (const uint32_t *)rot.plan, (const _Float16 *)X, ldx, T, rot.c_in, codes,
-                       (_Float16 *)scales, zeros);
+    // runs of up to 32 tokens per wave, shorter while that leaves fewer than ~4096 waves
+    const int G = rot.c_in / kGroup;
+    int rpw = 32;
+    while (rpw > 1 && (int64_t)G * ((T + rpw - 1) / rpw) < 4096) rpw >>= 1;
+    const int waves_t = (T + rpw - 1) / rpw;
+    hipLaunchKernelGGL(quantize_act_kernel<K>, dim3(G, (waves_t + kActWaves - 1) / kActWaves), dim3(kActWaves * 64), 0, s,
+                       (const uint32_t *)rot.plan, (const _Float16 *)X, ldx, T, rot.c_in, rpw, codes, (_Float16 *)scales, zeros);
     return hipGetLastError();
 }
 
