@@ -75,25 +75,39 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const int ks, c
         load_stage(blob, a, tile_of(0), ks, lane, st0);
         load_stage(blob, a, tile_of(1), ks, lane, st1);
         const int in_a = io & 0xff, in_b = (io >> 8) & 0xff, out_a = (io >> 16) & 0xff, out_b = io >> 24;
-        for (int t = 0; t < (rw ? a.T : 0); ++t) {
-            float va = (float)s_x[t][gi * kGroup + in_a] * sia;
-            float vb = (float)s_x[t][gi * kGroup + in_b] * sib;
+        // up to 4 tokens side by side: the chains of a layer (4 multiply-adds, then a permute that takes far longer)
+        // are independent between tokens, so a batch costs little more than one token
+        constexpr int TB = T1 ? 1 : 4;
+        for (int t0 = 0; t0 < (rw ? a.T : 0); t0 += TB) {
+            float va[TB], vb[TB];
+#pragma unroll
+            for (int u = 0; u < TB; ++u) {
+                const int t = min(t0 + u, a.T - 1);                          // surplus slots repeat the last token
+                va[u] = (float)s_x[t][gi * kGroup + in_a] * sia;
+                vb[u] = (float)s_x[t][gi * kGroup + in_b] * sib;
+            }
 #pragma unroll
             for (int l = 0; l < K; ++l) {
-                float m00, m01, m10, m11;
-                bool ai = pm[l] & kMetaAIsI, ki = pm[l] & kMetaKeepI;
-                float c = pc[l], s = ps[l];
-                float ni_a = ai ? c : -s, ni_b = ai ? -s : c, nj_a = ai ? s : c, nj_b = ai ? c : s;
-                m00 = ki ? ni_a : nj_a; m01 = ki ? ni_b : nj_b; m10 = ki ? nj_a : ni_a; m11 = ki ? nj_b : ni_b;
-                float na = m00 * va + m01 * vb, nb2 = m10 * va + m11 * vb;
-                va = na;
-                vb = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute((int)(pm[l] & 0xff), __float_as_int(nb2)))
-                                 : nb2;
+                const bool ai = pm[l] & kMetaAIsI, ki = pm[l] & kMetaKeepI;
+                const float c = pc[l], s = ps[l];
+                const float ni_a = ai ? c : -s, ni_b = ai ? -s : c, nj_a = ai ? s : c, nj_b = ai ? c : s;
+                const float m00 = ki ? ni_a : nj_a, m01 = ki ? ni_b : nj_b, m10 = ki ? nj_a : ni_a, m11 = ki ? nj_b : ni_b;
+#pragma unroll
+                for (int u = 0; u < TB; ++u) {
+                    const float na = m00 * va[u] + m01 * vb[u], nb2 = m10 * va[u] + m11 * vb[u];
+                    va[u] = na;
+                    vb[u] = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute((int)(pm[l] & 0xff), __float_as_int(nb2)))
+                                        : nb2;
+                }
             }
-            // all lanes have read their inputs of token t (the bpermutes above are wave-wide),
-            // so the staging row can be overwritten with the result
-            s_x[t][gi * kGroup + out_a] = (_Float16)(va * soa);
-            s_x[t][gi * kGroup + out_b] = (_Float16)(vb * sob);
+            // all lanes have read their inputs of these tokens (the permutes above are wave-wide), so the staging
+            // rows can be overwritten with the results
+#pragma unroll
+            for (int u = 0; u < TB; ++u)
+                if (t0 + u < a.T) {
+                    s_x[t0 + u][gi * kGroup + out_a] = (_Float16)(va[u] * soa);
+                    s_x[t0 + u][gi * kGroup + out_b] = (_Float16)(vb[u] * sob);
+                }
         }
         __syncthreads();
 #pragma unroll

@@ -59,8 +59,8 @@ inline bool can_fuse_decode(const paro_rotation *rot, const paro_w4_weight *w, i
 // in one block, no exchange up to 6144 channels) costs one more launch, 2.6 us on the small
 // linears and well under 1 us in front of a long weight stream.  Measured break-even on MI355X
 // (4096 / 5120 / 14336 / 27648 input channels, 4096 .. 55296 outputs): 1 - 2 MB of partial sums
-// for one token, 0.5 MB for 2..4 tokens.  `always`: for callers without a scratch part.
-constexpr size_t kFusePartialOne = 3u << 19, kFusePartialFew = 1u << 19;
+// for one token, 0.75 MB for 2..4 tokens.  `always`: for callers without a scratch part.
+constexpr size_t kFusePartialOne = 3u << 19, kFusePartialFew = 3u << 18;
 inline bool fused_decode(const paro_rotation *rot, const paro_w4_weight *w, int T, bool always = false)
 {
     if (!can_fuse_decode(rot, w, T)) return false;

@@ -251,7 +251,7 @@ def test_exchange_part_covers_the_partial_sums_of_every_shape():
 
 def test_fused_or_two_launches_by_shape():
     """Up to 4 tokens the decode kernel hosts the rotation (no scratch part) unless the partial sums its blocks
-    would exchange (K-slices x T x c_out x 4 bytes) exceed 1.5 MB at one token or 0.5 MB at 2..4: then the
+    would exchange (K-slices x T x c_out x 4 bytes) exceed 1.5 MB at one token or 0.75 MB at 2..4: then the
     rotation runs as a pass of its own, which shows as a scratch part of T * c_in * 2 bytes."""
     L = paro.lib()
 
@@ -264,7 +264,8 @@ def test_fused_or_two_launches_by_shape():
     assert scratch(27648, 5120, 1) == 0                    # 54 slices x 5120 x 4 = 1.1 MB
     assert scratch(5120, 55296, 1) == 5120 * 2             # 10 x 55296 x 4 = 2.2 MB: two launches
     assert scratch(4096, 6144, 2) == 0 and scratch(4096, 4096, 3) == 0
-    assert scratch(4096, 6144, 4) == 4 * 4096 * 2          # 8 x 4 x 6144 x 4 = 786 KB
+    assert scratch(4096, 6144, 4) == 0                     # 8 x 4 x 6144 x 4 = 768 KiB: still hosted
+    assert scratch(5120, 5120, 4) == 4 * 5120 * 2          # 10 x 4 x 5120 x 4 = 800 KiB
     assert scratch(4096, 28672, 2) == 2 * 4096 * 2
 
 
