@@ -34,10 +34,10 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
 MFMA_FP4_PEAK_TFLOPS = 10100.0 # dense fp4
 # HBM bytes per launch of the dominant fused kernel (gate/up) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --pmc-probe [--config 4]`, scaled by the same counters on a 256 MiB copy
-# (profiles/decode_stream_pmc.md).  Config 2 runs the transform as a launch of its own: no single dominant launch.
-# Config 4's gate/up takes the two-launch route (rotation pass + bare kernel): the bare launch's counters (147.5 MB read,
-# 0.1 MB written) plus the pass's own 0.3 MB (plan, X, X').
-TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 4: 147_900_000}
+# (profiles/decode_stream_pmc.md).  Config 2 (16 tokens) and config 4's gate/up take the two-launch route (rotation pass +
+# bare kernel): the sum of both launches' counters (config 2: 62.3 MB + 0.9 MB written by the linear, 0.4 MB by the pass;
+# config 4: 147.5 MB + 0.1 MB, 0.3 MB).
+TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 2: 63_600_000, 4: 147_900_000}
 
 
 def algorithmic_bytes(c_in: int, c_out: int, T: int, rotated: bool = True, K: int = 8) -> int:
