@@ -1,4 +1,4 @@
-// Decode-side bare W4A16 linear, 1..16 tokens per pass: a block takes ALL K-slices of its tile
+// Decode-side bare W4A16 linear, 1..16 tokens per pass (17..32 in decode_wide2_kernel below): a block takes ALL K-slices of its tile
 // range, one 512-channel slice per wave (up to 12 waves = 6144 channels; beyond that the slices
 // are spread evenly over several blocks of at most 8 waves and only those few partial sums are
 // exchanged between blocks); the waves' partial tiles are summed through LDS, so layers up to
@@ -32,6 +32,7 @@ namespace paro {
 __host__ __device__ constexpr int wide_max_tiles(bool one_token) { return one_token ? 16 : 9; }
 constexpr int kWideStages = 3;
 constexpr int kWideWaves = 12;                  // most K-slices (waves) of one block
+constexpr int kWideMaxTokens = 32;              // tokens of one pass: 16 per token block, one or two blocks per wave
 
 // f(0), f(1), ... while f returns true, at most N times; nested, so that stopping is ONE forward jump
 // past all remaining steps (instruction fetch matters at these kernel durations)
@@ -144,30 +145,136 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs
     if constexpr (SPLIT) splitk_reduce(a, gridDim.x, kb, tile_lo, tile_hi, s_red);
 }
 
+// ------------------------------------------------------------------------------------------
+// 17..32 tokens in ONE pass over the weights: the same block / wave / stream structure with two blocks of 16
+// tokens per wave.  Two sets of activation fragments fill half the register file, so the zero-point trick of
+// tile_dot (two more sums per token block and group) does not fit; the codes are dequantised completely
+// instead ( (q - z) * s in fp16, the value paro_w4_dequant produces and the prefill GEMM uses: 13 vector
+// instructions per 8 weights instead of 5 ), once per tile for both token blocks.
+// ------------------------------------------------------------------------------------------
+constexpr int kWide2MaxTiles = 9;
+constexpr int kWide2Waves = 8;                   // 2 waves per SIMD: the two sets of activation fragments need 256 registers
+
+template <bool SPLIT>
+__global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeArgs a)
+{
+    constexpr int NS = kWideStages;
+    extern __shared__ __attribute__((aligned(16))) float s_wide[];       // [tiles per block][waves][2][256] | reduce scratch
+    const int kb = blockIdx.x, nb = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;
+    const int ks = kb * nw + wave;
+    const bool slice_ok = ks < a.KS;
+    const int tile_lo = nb * a.tiles_per_block;
+    const int tile_hi = min(a.NT, tile_lo + a.tiles_per_block);
+    const int n_iter = tile_hi - tile_lo;
+    auto tile_of = [&](int i) { return (i < n_iter && slice_ok) ? tile_lo + i : -1; };
+    const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
+    float *s_red = s_wide + (size_t)a.tiles_per_block * nw * 512;
+
+    Stage st[NS];
+    half8 xf[2][kSliceGroups][4];
+    const int ft = lane & 15, fkb = lane >> 4;
+    {
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int t = tb * 16 + ft;
+            const uint32_t xoff = (t < a.T && slice_ok) ? (uint32_t)(((size_t)t * a.ldx + (size_t)ks * kSliceCh + fkb * 32) * 2) : kOob;
+#pragma unroll
+            for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    union { u32x4 u; half8 h; } v;
+                    v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
+                    xf[tb][g2][j] = v.h;
+                }
+        }
+#pragma unroll
+        for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
+    }
+    auto emit = [&](const Stage &stg, int i) {
+        float4v tot[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        union { uint2 v; uint32_t d[2]; } sc; sc.v = stg.sc;
+#pragma unroll
+        for (int gi = 0; gi < kSliceGroups; ++gi) {
+            const uint32_t z = (stg.zq >> (4 * gi)) & 15u;
+            const half2v nlo = as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
+            const half2v nhi = as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
+            const half2v s2 = as_h2(((sc.d[gi >> 1] >> (16 * (gi & 1))) & 0xffffu) * 0x00010001u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t u = stg.w[gi][j], t = u >> 8;
+                union { uint32_t d[4]; half8 h; } b;
+                b.d[0] = as_u32((as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo) * s2);
+                b.d[1] = as_u32((as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi) * s2);
+                b.d[2] = as_u32((as_h2((t & 0x000F000Fu) | 0x64006400u) + nlo) * s2);
+                b.d[3] = as_u32((as_h2((t & 0x00F000F0u) | 0x54005400u) + nhi) * s2);
+                tot[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[0][gi][j], b.h, tot[0], 0, 0, 0);
+                tot[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[1][gi][j], b.h, tot[1], 0, 0, 0);
+            }
+        }
+        float *dst = s_wide + ((size_t)i * nw + wave) * 512;
+        *(float4v *)(dst + lane * 4) = tot[0];
+        *(float4v *)(dst + 256 + lane * 4) = tot[1];
+    };
+    static_while<kWide2MaxTiles>([&](auto I) {
+        constexpr int i = I;
+        if (i >= n_iter) return false;
+        load_stage(blob, a, tile_of(i + NS - 1), ks, lane, st[(i + NS - 1) % NS]);
+        emit(st[i % NS], i);
+        return true;
+    });
+    __syncthreads();
+    const int per_tile = a.T * kTileN;
+    for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += blockDim.x) {
+        const int i = idx / per_tile, rem = idx % per_tile;
+        const int t = rem / kTileN, nn = rem % kTileN;
+        const int e = (t >> 4) * 256 + (((t & 15) >> 2) * 16 + nn) * 4 + (t & 3);
+        float sum = 0.f;
+        for (int w = 0; w < nw; ++w) sum += s_wide[((size_t)i * nw + w) * 512 + e];
+        const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
+        if constexpr (!SPLIT) {
+            if (a.bias) sum += (float)a.bias[n];
+            a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
+        } else {
+            uint32_t bits = __float_as_uint(sum);
+            if ((bits << 1) == 0u) bits = 0x80000000u;
+            __hip_atomic_store((uint32_t *)(a.partial + ((size_t)kb * a.T + t) * a.N + n), bits, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if constexpr (SPLIT) splitk_reduce(a, gridDim.x, kb, tile_lo, tile_hi, s_red);
+}
+
 struct WideGeometry { int kb, nb, waves, tiles_per_block; size_t lds; };
 static WideGeometry wide_geometry(int c_in, int c_out, int T)
 {
+    const bool two = T > 16;                                 // two blocks of 16 tokens per wave (decode_wide2_kernel)
     WideGeometry g;
     const int KS = c_in / kGroup / kSliceGroups, NT = c_out / kTileN;
     // up to 12 slices fit one block (3 waves per SIMD): no exchange between blocks at all.  Beyond
     // that the slices are spread evenly over blocks of at most 8 waves.
-    g.kb = KS <= kWideWaves ? 1 : (KS + 7) / 8;
+    g.kb = KS <= (two ? kWide2Waves : kWideWaves) ? 1 : (KS + 7) / 8;
     g.waves = (KS + g.kb - 1) / g.kb;
     int nb = 256 / g.kb;                                     // one block per compute unit
     if (nb < 1) nb = 1;
     int tpb = (NT + nb - 1) / nb;
-    if (tpb > wide_max_tiles(T == 1)) tpb = wide_max_tiles(T == 1);
+    const int max_tiles = two ? kWide2MaxTiles : wide_max_tiles(T == 1);
+    if (tpb > max_tiles) tpb = max_tiles;
+    if (two && tpb * g.waves > 76) tpb = 76 / g.waves;         // 2 KB of LDS per (tile, wave)
     g.tiles_per_block = tpb;
     g.nb = (NT + tpb - 1) / tpb;
-    g.lds = ((size_t)tpb * g.waves * (T == 1 ? kTileN : 256) + kReduceWords) * sizeof(float);
+    g.lds = ((size_t)tpb * g.waves * (two ? 512 : T == 1 ? kTileN : 256) + kReduceWords) * sizeof(float);
     return g;
 }
 
 size_t decode_wide_partial_bytes(int c_in, int c_out, int T)
 {
     WideGeometry g = wide_geometry(c_in, c_out, T);
-    int t16 = T < 16 ? T : 16;
-    return g.kb > 1 ? (size_t)g.kb * t16 * c_out * sizeof(float) : 0;
+    int tp = T < kWideMaxTokens ? T : kWideMaxTokens;
+    return g.kb > 1 ? (size_t)g.kb * tp * c_out * sizeof(float) : 0;
 }
 
 // ws: the exchange part of the workspace (may be NULL where no partial sums are exchanged)
@@ -193,8 +300,9 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
     static std::atomic<uint64_t> attr_done{0};
     if (const int dev = once_pending(attr_done); dev >= 0) {
-        const void *fns[4] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
-                              (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>};
+        const void *fns[6] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
+                              (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>,
+                              (const void *)decode_wide2_kernel<false>, (const void *)decode_wide2_kernel<true>};
         for (const void *f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return e;
@@ -202,7 +310,10 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
         once_done(attr_done, dev);
     }
     const dim3 grid(g.kb, g.nb), block(g.waves * 64);
-    if (T == 1) {
+    if (T > 16) {
+        if (g.kb > 1) hipLaunchKernelGGL((decode_wide2_kernel<true>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((decode_wide2_kernel<false>), grid, block, g.lds, s, a);
+    } else if (T == 1) {
         if (g.kb > 1) hipLaunchKernelGGL((decode_wide_kernel<true, true>), grid, block, g.lds, s, a);
         else          hipLaunchKernelGGL((decode_wide_kernel<false, true>), grid, block, g.lds, s, a);
     } else {

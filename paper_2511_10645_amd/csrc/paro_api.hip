@@ -10,7 +10,8 @@ namespace {
 
 constexpr int kFuseMaxTokens = 4;            // the K-major decode kernel hosts the rotation up to this many tokens
 constexpr int64_t kMaxRowStride = 1 << 22;   // elements; the kernels address a run of up to 256 rows with 31-bit byte offsets
-constexpr int kDecodeMaxTokens = 16;         // above this the MFMA GEMM takes over from the streaming decode kernels
+constexpr int kDecodeMaxTokens = 16;         // above this the MFMA GEMM competes with passes of the streaming decode kernel
+constexpr int kStreamPassTokens = 32;        // tokens of one pass of the streaming kernel (two blocks of 16)
 
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -160,15 +161,17 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
     }
     if (T > kDecodeMaxTokens && gemm_supported(*w, ldx, ldy, T)) {
         // Moderate token counts leave most of the chip idle in the GEMM (few token tiles), while the
-        // streaming kernel re-reads the weights once per 16 tokens at HBM speed: take the cheaper.
-        // Measured per 16-token pass: ~5 us plus the tile bytes at ~6 TB/s.
-        const double passes = (double)((T + kDecodeMaxTokens - 1) / kDecodeMaxTokens);
-        const double stream_us = passes * (5.0 + (double)packed_tiles_bytes(w->c_in, w->c_out) / 6.0e6);
+        // streaming kernel re-reads the weights once per 32 tokens: take the cheaper.  Measured per pass:
+        // 17..32 tokens ~9 us plus the tile bytes at ~4.1 TB/s, up to 16 tokens ~5 us plus the bytes at ~6 TB/s.
+        const double mb = (double)packed_tiles_bytes(w->c_in, w->c_out) / 1.0e6;
+        const int rem = T % kStreamPassTokens;
+        const double stream_us = (double)(T / kStreamPassTokens) * (9.0 + mb / 4.1) +
+                                 (rem == 0 ? 0.0 : rem <= 16 ? 5.0 + mb / 6.0 : 9.0 + mb / 4.1);
         if (T >= 512 || gemm_estimate_us(*w, T) <= stream_us)
             return from_hip(launch_gemm(*w, X, ldx, Y, ldy, T, gemm_scratch, gemm_bytes, s));
     }
-    for (int t0 = 0; t0 < T; t0 += 16) {
-        int tc = T - t0 < 16 ? T - t0 : 16;
+    for (int t0 = 0; t0 < T; t0 += kStreamPassTokens) {
+        int tc = T - t0 < kStreamPassTokens ? T - t0 : kStreamPassTokens;
         hipError_t e = launch_decode_wide(*w, X + (size_t)t0 * ldx, ldx, Y + (size_t)t0 * ldy, ldy, tc, ws, s);
         if (e != hipSuccess) return PARO_ERR_HIP;
     }

@@ -177,15 +177,20 @@ def _assert_linear(got16, y, allowed, note):
     dict(T=23, c_in=2048, c_out=16 * 21),
     dict(T=300, c_in=1024, c_out=16 * 21),      # MFMA GEMM path, ragged token and output tiles
     dict(T=257, c_in=512, c_out=16 * 33),
-    dict(T=17, c_in=1024, c_out=16 * 21),       # two passes of the streaming kernel (16 + 1 tokens)
+    dict(T=17, c_in=1024, c_out=16 * 21),       # 17 tokens: one pass with a second, nearly empty block of 16 tokens
     dict(T=1, c_in=6144, c_out=16 * 37),        # 12 K-slices: the widest single-block reduction
     dict(T=5, c_in=6656, c_out=16 * 11),        # 13 K-slices: spread over two blocks of 7 waves, partials exchanged
     dict(T=16, c_in=5120, c_out=16 * 19),       # 10 K-slices, a full 16-token pass
     dict(T=300, c_in=512, c_out=16 * 1037),     # GEMM with 256 x 192 tiles (130 tiles of 256 x 256 would leave half the chip idle), ragged both ways
+    dict(T=32, c_in=4096, c_out=16 * 37),       # one pass with two blocks of 16 tokens per wave
+    dict(T=20, c_in=5120, c_out=16 * 19),       # 10 K-slices: two blocks of 5 waves in the two-block kernel, partials exchanged
+    dict(T=29, c_in=6656, c_out=16 * 11),       # 13 K-slices, 29 tokens
+    dict(T=31, c_in=512, c_out=16 * 700),       # more tiles than one round of blocks takes at 9 per block
+    dict(T=50, c_in=1024, c_out=16 * 21),       # a pass of 32 and a pass of 18 tokens
 ])
 def test_bare_linear(P, packed, case):
     li = pin.make_custom(700 + case["T"], case["T"], case["c_in"], case["c_out"], n_outlier=3)
-    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] in (3, 5, 300) else None
+    bias = pin.make_bias(9, 9, case["c_out"]) if case["T"] in (3, 5, 300, 29, 32) else None
     u = li.x.astype(np.float64)
     y, allowed = _linear_ref(li, u, bias)
     w = make_w(P, li, packed=packed, bias=bias)
@@ -366,7 +371,7 @@ def _check_block(got, u, qw, sc, qz, c_in, label):
 
 def _full_config_case(P, config, linear, T, n_samples=4096):
     """Full-size check in the launch configuration the benchmark times.  Rotation: every element against the
-    oracle, and the strict 2-ulp statistic.  Linear outputs: up to 16 tokens EVERY output; beyond that whole stripes
+    oracle, and the strict 2-ulp statistic.  Linear outputs: up to 32 tokens EVERY output; beyond that whole stripes
     (all outputs of the first and the last 32 tokens; all tokens of 256 output columns: the first 64, the last 128 -
     the last output tile and the separately launched tail - and 64 spread over the middle) plus random samples."""
     li = pin.make_linear(config, linear, tokens=T, keep_codes=False)
@@ -387,7 +392,7 @@ def _full_config_case(P, config, linear, T, n_samples=4096):
     yb = P.paro_w4a16_linear(w, dev(xr), ws).cpu().numpy()
     ub = xr.astype(np.float64)
     assert ws.error_word() == 0
-    if T <= 16:
+    if T <= 32:
         _check_block(got, u, li.qweight, li.scales, li.qzeros, li.c_in, "fused, every output")
         _check_block(yb, ub, li.qweight, li.scales, li.qzeros, li.c_in, "bare, every output")
         two_launches = P.paro_workspace_bytes(rot, w, T) > P.paro_workspace_exchange_bytes(rot, w, T)
@@ -445,7 +450,7 @@ def test_config4_32b(P, linear, T):
     _full_config_case(P, 4, linear, T)
 
 
-@pytest.mark.parametrize("linear,T", [(0, 40), (1, 128), (2, 96), (3, 256), (3, 512)])
+@pytest.mark.parametrize("linear,T", [(0, 40), (1, 128), (2, 96), (3, 256), (3, 512), (2, 32), (3, 24)])
 def test_config1_shapes_between_decode_and_prefill(P, linear, T):
     """Tens to hundreds of tokens on the 8B-class shapes: repeated streaming passes, or the GEMM with K split
     over blockIdx.y and the separate reduction, whichever the call picks."""
