@@ -136,12 +136,15 @@ constexpr int kMxMaxWaves = 12;                      // 3 waves per SIMD: 170 re
 
 struct MxStage { u32x4 w[4]; uint32_t sc; };
 
-// SPW: 512-channel slices per wave (wave w takes slices w, w + waves, ...)
-template <int SPW>
-__global__ __launch_bounds__(kMxMaxWaves * 64) void mxfp4_decode_kernel(MxArgs a)
+// SPW: 512-channel slices per wave (wave w takes slices w, w + waves, ...).  TB: blocks of 16 tokens per wave
+// (the weight tile of a unit is multiplied with each; the 4 MFMAs per token block are a small part of a unit's
+// time, so up to 64 tokens cost little more than 16).  SPW * TB sets of activation fragments live in registers:
+// up to 5 with 12 waves per block, up to 8 with 8.
+template <int SPW, int TB>
+__global__ __launch_bounds__((SPW * TB <= 5 ? kMxMaxWaves : 8) * 64) void mxfp4_decode_kernel(MxArgs a)
 {
     constexpr int NS = kMxStages;
-    extern __shared__ __attribute__((aligned(16))) float s_part[];       // [tiles per block][waves][256]
+    extern __shared__ __attribute__((aligned(16))) float s_part[];       // [tiles per block][waves][TB][256]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = blockDim.x >> 6;
@@ -151,26 +154,28 @@ __global__ __launch_bounds__(kMxMaxWaves * 64) void mxfp4_decode_kernel(MxArgs a
     const int K128 = a.C / 128;
     const __amdgpu_buffer_rsrc_t blob = mx_rsrc(a.blob, a.blob_bytes);
 
-    // ---- activations of the wave's slices as A operands: lane = (token l % 16, 32-channel block l / 16) ----
+    // ---- activations of the wave's slices as A operands: lane = (token l % 16 of its block, 32-channel block l / 16) ----
     const int ft = lane & 15, fkb = lane >> 4;
-    u32x4 xf[SPW][4];
-    uint32_t xsc[SPW];
+    u32x4 xf[SPW][TB][4];
+    uint32_t xsc[SPW][TB];
     {
         const __amdgpu_buffer_rsrc_t xr = mx_rsrc(a.xc, (uint32_t)((size_t)a.T * a.C / 2));
         const __amdgpu_buffer_rsrc_t sr = mx_rsrc(a.xs, (uint32_t)((size_t)a.T * a.C / 32));
 #pragma unroll
-        for (int q = 0; q < SPW; ++q) {
-            const int ks = wave + q * nw;
-            const bool ok = ks < a.KS && ft < a.T;
-            const uint32_t xo = ok ? (uint32_t)((size_t)ft * (a.C / 2) + (size_t)ks * 256 + fkb * 16) : kOobM;
+        for (int q = 0; q < SPW; ++q)
 #pragma unroll
-            for (int m = 0; m < 4; ++m) xf[q][m] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xo + m * 64), 0, 0);
-            // the slice's 16 scale bytes: dword m = K-step m, byte kb = the lane's block
-            const u32x4 sc = __builtin_amdgcn_raw_buffer_load_b128(sr, ok ? (int)((size_t)ft * (a.C / 32) + (size_t)ks * 16) : (int)kOobM, 0, 0);
-            const int sh = 8 * fkb;
-            xsc[q] = ((sc[0] >> sh) & 0xffu) | (((sc[1] >> sh) & 0xffu) << 8) | (((sc[2] >> sh) & 0xffu) << 16) |
-                     (((sc[3] >> sh) & 0xffu) << 24);
-        }
+            for (int tb = 0; tb < TB; ++tb) {
+                const int ks = wave + q * nw, t = tb * 16 + ft;
+                const bool ok = ks < a.KS && t < a.T;
+                const uint32_t xo = ok ? (uint32_t)((size_t)t * (a.C / 2) + (size_t)ks * 256 + fkb * 16) : kOobM;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) xf[q][tb][m] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xo + m * 64), 0, 0);
+                // the slice's 16 scale bytes: dword m = K-step m, byte kb = the lane's block
+                const u32x4 sc = __builtin_amdgcn_raw_buffer_load_b128(sr, ok ? (int)((size_t)t * (a.C / 32) + (size_t)ks * 16) : (int)kOobM, 0, 0);
+                const int sh = 8 * fkb;
+                xsc[q][tb] = ((sc[0] >> sh) & 0xffu) | (((sc[1] >> sh) & 0xffu) << 8) | (((sc[2] >> sh) & 0xffu) << 16) |
+                             (((sc[3] >> sh) & 0xffu) << 24);
+            }
     }
     // unit i = (tile tile_lo + i / SPW, slice wave + (i % SPW) waves); nothing to load beyond the range: zeros
     MxStage st[NS];
@@ -186,65 +191,97 @@ __global__ __launch_bounds__(kMxMaxWaves * 64) void mxfp4_decode_kernel(MxArgs a
 #pragma unroll
     for (int i = 0; i + 1 < NS; ++i) load_unit(i, st[i]);
 
-    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    float4v acc[TB];
     mx_static_while<kMxMaxUnits>([&](auto I) {
         constexpr int i = I;
         constexpr int q = i % SPW;
         if (i / SPW >= n_iter) return false;
         load_unit(i + NS - 1, st[(i + NS - 1) % NS]);
         const MxStage &s = st[i % NS];
-        if constexpr (q == 0) acc = float4v{0.f, 0.f, 0.f, 0.f};
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][0]), as_operand(s.w[0]), acc, 4, 4, 0, (int)xsc[q], 0, (int)s.sc);
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][1]), as_operand(s.w[1]), acc, 4, 4, 1, (int)xsc[q], 1, (int)s.sc);
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][2]), as_operand(s.w[2]), acc, 4, 4, 2, (int)xsc[q], 2, (int)s.sc);
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][3]), as_operand(s.w[3]), acc, 4, 4, 3, (int)xsc[q], 3, (int)s.sc);
-        if constexpr (q == SPW - 1) *(float4v *)(s_part + ((size_t)(i / SPW) * nw + wave) * 256 + lane * 4) = acc;
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            if constexpr (q == 0) acc[tb] = float4v{0.f, 0.f, 0.f, 0.f};
+            acc[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][tb][0]), as_operand(s.w[0]), acc[tb], 4, 4, 0, (int)xsc[q][tb], 0, (int)s.sc);
+            acc[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][tb][1]), as_operand(s.w[1]), acc[tb], 4, 4, 1, (int)xsc[q][tb], 1, (int)s.sc);
+            acc[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][tb][2]), as_operand(s.w[2]), acc[tb], 4, 4, 2, (int)xsc[q][tb], 2, (int)s.sc);
+            acc[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(xf[q][tb][3]), as_operand(s.w[3]), acc[tb], 4, 4, 3, (int)xsc[q][tb], 3, (int)s.sc);
+            if constexpr (q == SPW - 1) *(float4v *)(s_part + (((size_t)(i / SPW) * nw + wave) * TB + tb) * 256 + lane * 4) = acc[tb];
+        }
         return true;
     });
     __syncthreads();
-    // ---- sum the waves' partial tiles: element lane * 4 + r <-> token 4 (lane / 16) + r, row lane % 16 ----
+    // ---- sum the waves' partial tiles: element lane * 4 + r <-> token 4 (lane / 16) + r of its block, row lane % 16 ----
     const int per_tile = a.T * kTileN;
     for (int idx = threadIdx.x; idx < n_iter * per_tile; idx += blockDim.x) {
         const int i = idx / per_tile, rem = idx % per_tile;
         const int t = rem / kTileN, nn = rem % kTileN;
-        const int e = ((t >> 2) * 16 + nn) * 4 + (t & 3);
+        const int e = (t >> 4) * 256 + (((t & 15) >> 2) * 16 + nn) * 4 + (t & 3);
         float sum = 0.f;
-        for (int w = 0; w < nw; ++w) sum += s_part[((size_t)i * nw + w) * 256 + e];
+        for (int w = 0; w < nw; ++w) sum += s_part[((size_t)i * nw + w) * (TB * 256) + e];
         const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
         if (a.bias) sum += (float)a.bias[n];
         a.Y[(size_t)t * a.ldy + n] = (_Float16)sum;
     }
 }
 
-struct MxGeometry { int spw, waves, tiles_per_block, blocks; size_t lds; };
-static bool mx_geometry(int c_in, int c_out, MxGeometry &g)
+// Geometry of a pass of T tokens: TB token blocks per wave, as many as the registers allow for this K.
+struct MxGeometry { int spw, tb, waves, tiles_per_block, blocks; size_t lds; };
+static bool mx_geometry(int c_in, int c_out, int T, MxGeometry &g)
 {
     const int KS = c_in / 512, NT = c_out / kTileN;
-    g.spw = (KS + kMxMaxWaves - 1) / kMxMaxWaves;
-    if (g.spw > 5) return false;
+    const int want = T > 32 ? 4 : T > 16 ? 2 : 1;
+    g.tb = 0;
+    for (int tb = want; tb >= 1 && !g.tb; tb >>= 1) {
+        // sets of fragments = SPW * TB: up to 5 with 12 waves per block, up to 8 with 8 waves
+        const int spw12 = (KS + kMxMaxWaves - 1) / kMxMaxWaves, spw8 = (KS + 7) / 8;
+        if (spw12 * tb <= 5) { g.tb = tb; g.spw = spw12; }
+        else if (spw8 * tb <= 8) { g.tb = tb; g.spw = spw8; }
+    }
+    if (!g.tb || g.spw > 5) return false;
     g.waves = (KS + g.spw - 1) / g.spw;
     int tpb = (NT + 255) / 256;                               // one block per compute unit
     if (tpb > kMxMaxUnits / g.spw) tpb = kMxMaxUnits / g.spw;
-    if (tpb * g.waves > 144) tpb = 144 / g.waves;             // 1 KB of LDS per (tile, wave)
+    if (tpb * g.waves * g.tb > 144) tpb = 144 / (g.waves * g.tb);   // TB KB of LDS per (tile, wave)
+    if (tpb < 1) return false;
     g.tiles_per_block = tpb;
     g.blocks = (NT + tpb - 1) / tpb;
-    g.lds = (size_t)tpb * g.waves * 1024;
+    g.lds = (size_t)tpb * g.waves * g.tb * 1024;
     return true;
 }
 
 bool mxfp4_linear_supported(const paro_mxfp4_weight &w)
 {
     MxGeometry g;
-    return w.packed && w.c_in % 512 == 0 && w.c_out % 16 == 0 && mx_geometry(w.c_in, w.c_out, g) &&
+    return w.packed && w.c_in % 512 == 0 && w.c_out % 16 == 0 && mx_geometry(w.c_in, w.c_out, 1, g) &&
            (size_t)w.c_out * w.c_in / 2 + (size_t)w.c_out * w.c_in / 32 < (1ull << 31);
 }
 
-// one pass of up to 16 tokens
+// tokens one pass of the streaming kernel takes for this K (64, 32 or 16)
+static int mxfp4_pass_tokens(const paro_mxfp4_weight &w, int T)
+{
+    MxGeometry g;
+    return mx_geometry(w.c_in, w.c_out, T, g) ? 16 * g.tb : 16;
+}
+
+template <int SPW, int TB>
+static hipError_t launch_mxfp4_decode_cfg(const MxArgs &a, const MxGeometry &g, hipStream_t s)
+{
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
+        hipError_t e = hipFuncSetAttribute((const void *)mxfp4_decode_kernel<SPW, TB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        once_done(attr_done, dev);
+    }
+    hipLaunchKernelGGL((mxfp4_decode_kernel<SPW, TB>), dim3(g.blocks), dim3(g.waves * 64), g.lds, s, a);
+    return hipGetLastError();
+}
+
+// one pass of up to mxfp4_pass_tokens() tokens
 static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t *xc, const uint8_t *xs, int T,
                                       paro_half_t *Y, int64_t ldy, hipStream_t s)
 {
     MxGeometry g;
-    if (!mx_geometry(w.c_in, w.c_out, g)) return hipErrorInvalidValue;
+    if (!mx_geometry(w.c_in, w.c_out, T, g) || T > 16 * g.tb) return hipErrorInvalidValue;
     MxArgs a;
     a.blob = w.packed;
     a.scales_off = (uint32_t)((size_t)w.c_out * w.c_in / 2);
@@ -252,28 +289,21 @@ static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t
     a.xc = xc; a.xs = xs; a.Y = (_Float16 *)Y; a.ldy = ldy; a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.NT = w.c_out / kTileN; a.KS = w.c_in / 512;
     a.tiles_per_block = g.tiles_per_block;
-    static std::atomic<uint64_t> attr_done{0};
-    if (const int dev = once_pending(attr_done); dev >= 0) {
-        const void *fns[5] = {(const void *)mxfp4_decode_kernel<1>, (const void *)mxfp4_decode_kernel<2>,
-                              (const void *)mxfp4_decode_kernel<3>, (const void *)mxfp4_decode_kernel<4>,
-                              (const void *)mxfp4_decode_kernel<5>};
-        for (const void *f : fns) {
-            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-        }
-        once_done(attr_done, dev);
+    switch (g.tb * 8 + g.spw) {
+    case 1 * 8 + 1: return launch_mxfp4_decode_cfg<1, 1>(a, g, s);
+    case 1 * 8 + 2: return launch_mxfp4_decode_cfg<2, 1>(a, g, s);
+    case 1 * 8 + 3: return launch_mxfp4_decode_cfg<3, 1>(a, g, s);
+    case 1 * 8 + 4: return launch_mxfp4_decode_cfg<4, 1>(a, g, s);
+    case 1 * 8 + 5: return launch_mxfp4_decode_cfg<5, 1>(a, g, s);
+    case 2 * 8 + 1: return launch_mxfp4_decode_cfg<1, 2>(a, g, s);
+    case 2 * 8 + 2: return launch_mxfp4_decode_cfg<2, 2>(a, g, s);
+    case 2 * 8 + 3: return launch_mxfp4_decode_cfg<3, 2>(a, g, s);
+    case 2 * 8 + 4: return launch_mxfp4_decode_cfg<4, 2>(a, g, s);
+    case 4 * 8 + 1: return launch_mxfp4_decode_cfg<1, 4>(a, g, s);
+    case 4 * 8 + 2: return launch_mxfp4_decode_cfg<2, 4>(a, g, s);
+    default: return hipErrorInvalidValue;
     }
-    const dim3 grid(g.blocks), block(g.waves * 64);
-    switch (g.spw) {
-    case 1: hipLaunchKernelGGL(mxfp4_decode_kernel<1>, grid, block, g.lds, s, a); break;
-    case 2: hipLaunchKernelGGL(mxfp4_decode_kernel<2>, grid, block, g.lds, s, a); break;
-    case 3: hipLaunchKernelGGL(mxfp4_decode_kernel<3>, grid, block, g.lds, s, a); break;
-    case 4: hipLaunchKernelGGL(mxfp4_decode_kernel<4>, grid, block, g.lds, s, a); break;
-    default: hipLaunchKernelGGL(mxfp4_decode_kernel<5>, grid, block, g.lds, s, a); break;
-    }
-    return hipGetLastError();
 }
-
 
 // ------------------------------------------------------------------------------------------
 // More than 16 tokens: tiled GEMM.  Block tile 256 tokens x 256 outputs x 128 channels (one K-step of
@@ -514,9 +544,9 @@ static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *
     return hipGetLastError();
 }
 
-// Which kernel: the streaming kernel reads the whole weight once per 16 tokens, the GEMM once per 256 but
-// works on 256 x 256 tiles whatever T is.
-constexpr int kMxGemmMinTokens = 64;
+// Which kernel: the streaming kernel reads the whole weight once per 64 tokens (32 or 16 where K is deep), the
+// GEMM once per 256 but works on 256 x 256 tiles whatever T is.
+constexpr int kMxGemmMinTokens = 65;
 
 hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_codes, const uint8_t *x_scales, int T,
                                paro_half_t *Y, int64_t ldy, hipStream_t s)
@@ -524,11 +554,13 @@ hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_cod
     // the GEMM addresses the activations with 32-bit offsets
     if (T >= kMxGemmMinTokens && (size_t)T * w.c_in / 2 < (1ull << 31) && ((size_t)(T - 1) * ldy + w.c_out) * 2 < (1ull << 31))
         return launch_mxfp4_gemm(w, x_codes, x_scales, T, Y, ldy, s);
-    for (int t0 = 0; t0 < T; t0 += 16) {
-        const int tp = T - t0 < 16 ? T - t0 : 16;
+    for (int t0 = 0; t0 < T;) {
+        const int pass = mxfp4_pass_tokens(w, T - t0);
+        const int tp = T - t0 < pass ? T - t0 : pass;
         hipError_t e = launch_mxfp4_decode(w, x_codes + (size_t)t0 * (w.c_in / 8), x_scales + (size_t)t0 * (w.c_in / 32), tp,
                                            Y + (size_t)t0 * ldy, ldy, s);
         if (e != hipSuccess) return e;
+        t0 += tp;
     }
     return hipSuccess;
 }

@@ -84,10 +84,16 @@ def test_repack_and_unpack_are_bit_exact(P, shape):
     dict(seed=9206, T=37, C=1024, N=80, bias=True),           # three passes of up to 16 tokens
     dict(seed=9207, T=1, C=4096, N=6144, bias=False),         # more tiles than blocks
     dict(seed=9208, T=16, C=6144, N=4112, bias=False),        # 12 slices, 257 tiles
-    dict(seed=9209, T=64, C=512, N=256, bias=True),           # tiled kernel from 64 tokens: one tile, 4 K-steps
+    dict(seed=9209, T=65, C=512, N=256, bias=True),           # tiled kernel from 65 tokens: one tile, 4 K-steps
     dict(seed=9210, T=300, C=1024, N=272, bias=True),         # ragged in tokens and in outputs
     dict(seed=9211, T=257, C=2048, N=528, bias=False),        # a second token tile of one row
     dict(seed=9212, T=1024, C=4096, N=1536, bias=True),       # 4 x 6 tiles, 32 K-steps
+    dict(seed=9215, T=64, C=4096, N=528, bias=True),          # 64 tokens in one pass: four token blocks per wave
+    dict(seed=9216, T=40, C=5120, N=272, bias=False),         # 10 slices, three of four token blocks used
+    dict(seed=9217, T=32, C=14336, N=96, bias=True),          # 28 slices: 4 per wave, two token blocks
+    dict(seed=9218, T=50, C=14336, N=48, bias=False),         # the same K: a pass of 32 and a pass of 18
+    dict(seed=9219, T=20, C=27648, N=32, bias=False),         # 54 slices: 16 tokens per pass only (16 + 4)
+    dict(seed=9220, T=48, C=8192, N=64, bias=True),           # 16 slices: 2 per wave, four token blocks
     dict(seed=9213, T=70, C=512, N=64, bias=True, pad=2),     # output rows that are not 16-byte aligned
     dict(seed=9214, T=3, C=512, N=48, bias=False, pad=6),
 ])
