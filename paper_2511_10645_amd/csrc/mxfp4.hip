@@ -545,15 +545,22 @@ static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *
 }
 
 // Which kernel: the streaming kernel reads the whole weight once per 64 tokens (32 or 16 where K is deep), the
-// GEMM once per 256 but works on 256 x 256 tiles whatever T is.
-constexpr int kMxGemmMinTokens = 65;
-
+// GEMM once per 256 but works on 256 x 256 tiles whatever T is, one round of them per 256 compute units.
+// Measured: a pass of TB blocks of 16 tokens takes ~3 us + the blob at 5.5 TB/s + TB x (0.8 us + the blob at
+// 30 TB/s); a round of GEMM tiles ~0.9 us per K-step + 3 us.
 hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_codes, const uint8_t *x_scales, int T,
                                paro_half_t *Y, int64_t ldy, hipStream_t s)
 {
+    const int pass = mxfp4_pass_tokens(w, T);
     // the GEMM addresses the activations with 32-bit offsets
-    if (T >= kMxGemmMinTokens && (size_t)T * w.c_in / 2 < (1ull << 31) && ((size_t)(T - 1) * ldy + w.c_out) * 2 < (1ull << 31))
-        return launch_mxfp4_gemm(w, x_codes, x_scales, T, Y, ldy, s);
+    if (T > pass && (size_t)T * w.c_in / 2 < (1ull << 31) && ((size_t)(T - 1) * ldy + w.c_out) * 2 < (1ull << 31)) {
+        const double mb = ((double)w.c_out * w.c_in / 2 + (double)w.c_out * w.c_in / 32) / 1.0e6;
+        const double pass_us = 3.0 + mb / 5.5 + (pass / 16) * (0.8 + mb / 30.0);
+        const double stream_us = (double)((T + pass - 1) / pass) * pass_us;
+        const long tiles = (long)((T + kMxBM - 1) / kMxBM) * ((w.c_out + kMxBN - 1) / kMxBN);
+        const double gemm_us = (double)((tiles + 255) / 256) * ((w.c_in / 128) * 0.9 + 3.0);
+        if (gemm_us < stream_us) return launch_mxfp4_gemm(w, x_codes, x_scales, T, Y, ldy, s);
+    }
     for (int t0 = 0; t0 < T;) {
         const int pass = mxfp4_pass_tokens(w, T - t0);
         const int tp = T - t0 < pass ? T - t0 : pass;
