@@ -195,3 +195,46 @@ def test_whole_equation_from_dense_weight_and_fp16_activations(P, case):
     rel = np.linalg.norm(got.astype(np.float64) - exact) / np.linalg.norm(exact)
     say(f"  relative error against the unquantised W x + b: {rel:.3f}")
     assert rel < 0.35
+
+
+def test_graph_replays_match_eager(P):
+    """The MXFP4 calls only enqueue kernels: a captured sequence (whole equation at 3 tokens, contraction at 40 and at
+    150 tokens) replays to the eager bits, with eager work between the replays."""
+    import torch
+    li = pin.make_custom(9601, 150, 1024, 176, n_outlier=3)
+    rot = P.Rotation(li.pairs, li.theta, li.ch_scale)
+    P.paro_rotation_plan_build(rot)
+    rng = np.random.default_rng(9601)
+    w = P.paro_mxfp4_quantize_weight(rot, torch.as_tensor((rng.standard_normal((176, 1024)) * 0.05).astype(np.float16)).cuda())
+    P.paro_mxfp4_repack(w)
+    x = torch.as_tensor(li.x).cuda()
+    xc, xs = P.paro_rotate_scale_quantize_mxfp4(rot, x)
+    buf = torch.empty(P.paro_workspace_bytes_mxfp4(1024, 3), dtype=torch.uint8, device="cuda")
+    outs = [torch.zeros((t, 176), dtype=torch.float16, device="cuda") for t in (3, 40, 150)]
+
+    def sequence():
+        P.paro_rotated_linear_mxfp4(rot, w, x[:3], buf, Y=outs[0])
+        P.paro_mxfp4_linear(w, xc[:40], xs[:40], outs[1])
+        P.paro_mxfp4_linear(w, xc, xs, outs[2])
+
+    sequence()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            sequence()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), rep
+        sequence()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), rep

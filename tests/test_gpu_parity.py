@@ -233,7 +233,7 @@ def test_rotated_linear(P, case):
         assert ws.partials_clean() and ws.error_word() == 0              # no partial sums left behind, no wait ran out
 
 
-@pytest.mark.parametrize("T", [1, 3, 16, 40, 300])
+@pytest.mark.parametrize("T", [1, 3, 16, 27, 40, 300])
 @pytest.mark.parametrize("fused", [False, True])
 def test_linear_with_padded_rows(P, T, fused):
     """X and Y as column slices of wider buffers (ld > width): every kernel of the dispatch (narrow, wide,
