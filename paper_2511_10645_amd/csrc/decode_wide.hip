@@ -23,6 +23,7 @@
 // stream by the same time.  Hence: up to 4 tokens the K-major kernel (decode.hip), whose blocks
 // rotate only their own slice; 5..16 tokens a rotation pass, then this kernel.
 #include "decode_common.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace paro {
@@ -44,11 +45,53 @@ __device__ __forceinline__ void static_while(F &&f)
     }
 }
 
+// Activation fragments of several tokens.  An MFMA A fragment wants, per lane, 16 bytes of token lane % 16 at
+// channel offset 32 (lane / 16) + 8 j: loaded straight from X, one instruction touches 32 cache lines (16 rows x 2)
+// and uses 32 bytes of each, and the compute unit's vector-memory path, which takes a cache line per cycle, spends
+// 2 us per launch on a 16-token input of 4096 channels (128 KB per block) before the first weight tile can be
+// multiplied.  Instead every instruction reads 4 token rows x 256 contiguous bytes (8 full lines), the wave parks
+// the 16 x 128 sub-block in a private LDS area (rows padded to 272 bytes: the 16-byte accesses of both directions
+// are conflict-free) and reads its fragments from there.  Measured, bare linear at 16 tokens: 4096 -> 6144
+// 8.0 -> 6.3 us, 4096 -> 4096 7.4 -> 5.3 us.  No block barrier: the area is private to the wave and LDS operations
+// of one wave execute in issue order.
+constexpr int kXsRowBytes = kGroup * 2 + 16;
+constexpr int kXsWords = 16 * kXsRowBytes / 4;      // 1088 floats per wave
+template <int TB>
+__device__ __forceinline__ void load_x_fragments(const DecodeArgs &a, int ks, bool slice_ok, int lane, char *xs,
+                                                 half8 (&xf)[TB][kSliceGroups][4])
+{
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
+    const int lr = lane >> 4, lc = lane & 15;
+    u32x4 raw[TB][kSliceGroups][4];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int t = tb * 16 + q * 4 + lr;
+            const uint32_t off = (t < a.T && slice_ok) ? (uint32_t)(((size_t)t * a.ldx + (size_t)ks * kSliceCh) * 2 + lc * 16) : kOob;
+#pragma unroll
+            for (int g2 = 0; g2 < kSliceGroups; ++g2)
+                raw[tb][g2][q] = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(off + g2 * kGroup * 2), 0, 0);
+        }
+    const int ft = lane & 15, fkb = lane >> 4;
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) *(u32x4 *)(xs + (q * 4 + lr) * kXsRowBytes + lc * 16) = raw[tb][g2][q];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xf[tb][g2][j] = *(const half8 *)(xs + ft * kXsRowBytes + fkb * 64 + j * 16);
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
 template <bool SPLIT, bool T1>
 __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs a)
 {
     constexpr int NS = kWideStages;
-    // [tiles per block][waves] partial tiles | kReduceWords reduce scratch
+    // [waves][tiles per block] partial tiles | kReduceWords reduce scratch
     extern __shared__ __attribute__((aligned(16))) float s_wide[];
     const int kb = blockIdx.x, nb = blockIdx.y;
     const int lane = threadIdx.x & 63;
@@ -62,12 +105,24 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs
     auto tile_of = [&](int i) { return (i < n_iter && slice_ok) ? tile_lo + i : -1; };
     const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
     constexpr int kTileWords = T1 ? kTileN : 256;
-    float *s_red = s_wide + (size_t)a.tiles_per_block * nw * kTileWords;
+    // a wave's partial tiles are contiguous; several tokens: the same area first parks its activations
+    const int wstride = T1 ? a.tiles_per_block * kTileWords : max(a.tiles_per_block * kTileWords, kXsWords);
+    float *s_mine = s_wide + (size_t)wave * wstride;
+    float *s_red = s_wide + (size_t)nw * wstride;
 
     Stage st[NS];
     half8 xf[kSliceGroups][4];
     const int ft = lane & 15, fkb = lane >> 4;
-    {
+    if constexpr (!T1) {
+        half8 xt[1][kSliceGroups][4];
+        load_x_fragments<1>(a, ks, slice_ok, lane, (char *)s_mine, xt);
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xf[g2][j] = xt[0][g2][j];
+#pragma unroll
+        for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
+    } else {
         const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
         const uint32_t xoff = (ft < a.T && slice_ok) ? (uint32_t)(((size_t)ft * a.ldx + (size_t)ks * kSliceCh + fkb * 32) * 2) : kOob;
 #pragma unroll
@@ -104,7 +159,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs
     // 4*(lane/16)+r, row lane%16 (1 KB per tile and wave); one token: the 16 rows only (64 B)
     auto emit = [&](const Stage &stg, int i) {
         float4v tot = tile_dot<T1>(stg, xf, nb1, nb2, dq);
-        float *dst = s_wide + ((size_t)i * nw + wave) * kTileWords;
+        float *dst = s_mine + i * kTileWords;
         if constexpr (T1) { if (lane < 16) dst[lane] = tot[0]; }
         else *(float4v *)(dst + lane * 4) = tot;
     };
@@ -130,7 +185,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs
         const int t = rem / kTileN, nn = rem % kTileN;
         const int e = T1 ? nn : ((t >> 2) * 16 + nn) * 4 + (t & 3);
         float sum = 0.f;
-        for (int w = 0; w < nw; ++w) sum += s_wide[((size_t)i * nw + w) * kTileWords + e];
+        for (int w = 0; w < nw; ++w) sum += s_wide[(size_t)w * wstride + i * kTileWords + e];
         const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
         if constexpr (!SPLIT) {
             if (a.bias) sum += (float)a.bias[n];
@@ -159,7 +214,7 @@ template <bool SPLIT>
 __global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeArgs a)
 {
     constexpr int NS = kWideStages;
-    extern __shared__ __attribute__((aligned(16))) float s_wide[];       // [tiles per block][waves][2][256] | reduce scratch
+    extern __shared__ __attribute__((aligned(16))) float s_wide[];       // [waves][tiles per block][2][256] | reduce scratch
     const int kb = blockIdx.x, nb = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -171,29 +226,15 @@ __global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeAr
     const int n_iter = tile_hi - tile_lo;
     auto tile_of = [&](int i) { return (i < n_iter && slice_ok) ? tile_lo + i : -1; };
     const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
-    float *s_red = s_wide + (size_t)a.tiles_per_block * nw * 512;
+    const int wstride = max(a.tiles_per_block * 512, kXsWords);
+    float *s_mine = s_wide + (size_t)wave * wstride;
+    float *s_red = s_wide + (size_t)nw * wstride;
 
     Stage st[NS];
     half8 xf[2][kSliceGroups][4];
-    const int ft = lane & 15, fkb = lane >> 4;
-    {
-        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)(((size_t)(a.T - 1) * a.ldx + a.C) * 2));
+    load_x_fragments<2>(a, ks, slice_ok, lane, (char *)s_mine, xf);
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            const int t = tb * 16 + ft;
-            const uint32_t xoff = (t < a.T && slice_ok) ? (uint32_t)(((size_t)t * a.ldx + (size_t)ks * kSliceCh + fkb * 32) * 2) : kOob;
-#pragma unroll
-            for (int g2 = 0; g2 < kSliceGroups; ++g2)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    union { u32x4 u; half8 h; } v;
-                    v.u = __builtin_amdgcn_raw_buffer_load_b128(xr, (int)(xoff + (g2 * kGroup + j * 8) * 2), 0, 0);
-                    xf[tb][g2][j] = v.h;
-                }
-        }
-#pragma unroll
-        for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
-    }
+    for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
     auto emit = [&](const Stage &stg, int i) {
         float4v tot[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
         union { uint2 v; uint32_t d[2]; } sc; sc.v = stg.sc;
@@ -215,7 +256,7 @@ __global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeAr
                 tot[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[1][gi][j], b.h, tot[1], 0, 0, 0);
             }
         }
-        float *dst = s_wide + ((size_t)i * nw + wave) * 512;
+        float *dst = s_mine + i * 512;
         *(float4v *)(dst + lane * 4) = tot[0];
         *(float4v *)(dst + 256 + lane * 4) = tot[1];
     };
@@ -233,7 +274,7 @@ __global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeAr
         const int t = rem / kTileN, nn = rem % kTileN;
         const int e = (t >> 4) * 256 + (((t & 15) >> 2) * 16 + nn) * 4 + (t & 3);
         float sum = 0.f;
-        for (int w = 0; w < nw; ++w) sum += s_wide[((size_t)i * nw + w) * 512 + e];
+        for (int w = 0; w < nw; ++w) sum += s_wide[(size_t)w * wstride + i * 512 + e];
         const size_t n = (size_t)(tile_lo + i) * kTileN + nn;
         if constexpr (!SPLIT) {
             if (a.bias) sum += (float)a.bias[n];
@@ -266,7 +307,9 @@ static WideGeometry wide_geometry(int c_in, int c_out, int T)
     if (two && tpb * g.waves > 76) tpb = 76 / g.waves;         // 2 KB of LDS per (tile, wave)
     g.tiles_per_block = tpb;
     g.nb = (NT + tpb - 1) / tpb;
-    g.lds = ((size_t)tpb * g.waves * (two ? 512 : T == 1 ? kTileN : 256) + kReduceWords) * sizeof(float);
+    const int tile_words = two ? 512 : T == 1 ? kTileN : 256;
+    const int wstride = T == 1 ? tpb * tile_words : std::max(tpb * tile_words, kXsWords);   // as in the kernels
+    g.lds = ((size_t)g.waves * wstride + kReduceWords) * sizeof(float);
     return g;
 }
 
