@@ -29,8 +29,9 @@
 namespace paro {
 
 // most tiles per wave (the stream loop is unrolled): one token keeps 64 B of partial sums per tile
-// and wave in LDS, several tokens 1 KB
-__host__ __device__ constexpr int wide_max_tiles(bool one_token) { return one_token ? 16 : 9; }
+// and wave in LDS, several tokens 1 KB (the launcher also keeps the block's total within the LDS)
+__host__ __device__ constexpr int wide_max_tiles(bool one_token) { return one_token ? 16 : 14; }
+constexpr size_t kWideLdsBytes = 160 * 1024;
 constexpr int kWideStages = 3;
 constexpr int kWideWaves = 12;                  // most K-slices (waves) of one block
 constexpr int kWideMaxTokens = 32;              // tokens of one pass: 16 per token block, one or two blocks per wave
@@ -305,6 +306,10 @@ static WideGeometry wide_geometry(int c_in, int c_out, int T)
     const int max_tiles = two ? kWide2MaxTiles : wide_max_tiles(T == 1);
     if (tpb > max_tiles) tpb = max_tiles;
     if (two && tpb * g.waves > 76) tpb = 76 / g.waves;         // 2 KB of LDS per (tile, wave)
+    if (!two && T > 1) {                                     // 1 KB of LDS per (tile, wave), next to the reduce scratch
+        const int fit = (int)((kWideLdsBytes - kReduceWords * sizeof(float)) / ((size_t)g.waves * 1024));
+        if (tpb > fit) tpb = fit;
+    }
     g.tiles_per_block = tpb;
     g.nb = (NT + tpb - 1) / tpb;
     const int tile_words = two ? 512 : T == 1 ? kTileN : 256;
@@ -326,7 +331,7 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
 {
     if (packed_blob_bytes(w.c_in, w.c_out) >= (1ull << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets (checked by the caller)
     const WideGeometry g = wide_geometry(w.c_in, w.c_out, T);
-    if (g.kb > 64 || g.lds > 160 * 1024 || (g.kb > 1 && !ws)) return hipErrorInvalidValue;
+    if (g.kb > 64 || g.lds > kWideLdsBytes || (g.kb > 1 && !ws)) return hipErrorInvalidValue;
     DecodeArgs a;
     a.blob = w.packed;
     a.scales_off = (uint32_t)packed_tiles_bytes(w.c_in, w.c_out);

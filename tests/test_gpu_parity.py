@@ -558,6 +558,25 @@ def test_one_k_slice_with_a_very_wide_output(P):
     assert ws.error_word() == 0
 
 
+@pytest.mark.parametrize("case", [(5, 1024, 53248), (16, 1536, 57344), (2, 6144, 45056), (9, 5120, 55296)],
+                         ids=lambda c: f"T{c[0]}_{c[1]}to{c[2]}")
+def test_long_streams_at_several_tokens(P, case):
+    """Outputs wide enough that a block of the streaming kernel runs 11..14 tiles per wave at 2..16 tokens (1 KB of
+    partial sums per tile and wave: the longest streams the LDS holds for 2, 3, 10 and 12 waves per block), bare and
+    behind the rotation pass; every output is compared."""
+    T, c_in, c_out = case
+    li = pin.make_custom(7950 + T, T, c_in, c_out, n_outlier=2)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale)
+    y, allowed = _linear_ref(li, u)
+    yb, allowed_b = _linear_ref(li, li.x.astype(np.float64))
+    rot, w = make_rot(P, li), make_w(P, li)
+    ws = P.Workspace.shared([(rot, w, T), (None, w, T)])
+    x = dev(li.x)
+    _assert_linear(P.paro_w4a16_linear(w, x, ws).cpu().numpy(), yb, allowed_b, f"long stream bare {case}")
+    _assert_linear(P.paro_rotated_linear(rot, w, x, ws).cpu().numpy(), y, allowed, f"long stream fused {case}")
+    assert ws.partials_clean(ws.exchange_bytes) and ws.error_word() == 0
+
+
 def test_seeded_sweep_of_shapes(P):
     """48 seeded draws of (T, c_in, c_out, layers, pairs per layer, scale order, bias, plan, repack): whatever
     kernel the dispatch picks (narrow, wide with 1..n blocks per column, rotation pass, GEMM with ragged tiles,
