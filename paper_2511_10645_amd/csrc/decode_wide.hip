@@ -204,9 +204,9 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs
 // ------------------------------------------------------------------------------------------
 // 17..32 tokens in ONE pass over the weights: the same block / wave / stream structure with two blocks of 16
 // tokens per wave.  Two sets of activation fragments fill half the register file, so the zero-point trick of
-// tile_dot (two more sums per token block and group) does not fit; the codes are dequantised completely
-// instead ( (q - z) * s in fp16, the value paro_w4_dequant produces and the prefill GEMM uses: 13 vector
-// instructions per 8 weights instead of 5 ), once per tile for both token blocks.
+// tile_dot (two more sums per token block and group) does not fit; the zero point is subtracted from the codes
+// instead ( q - z, exact in fp16: 9 vector instructions per 8 weights instead of 5 ), once per tile for both token
+// blocks, and the scale of a group multiplies its fp32 sums as in tile_dot.
 // ------------------------------------------------------------------------------------------
 constexpr int kWide2MaxTiles = 9;
 constexpr int kWide2Waves = 8;                   // 2 waves per SIMD: the two sets of activation fragments need 256 registers
@@ -236,26 +236,33 @@ __global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeAr
     load_x_fragments<2>(a, ks, slice_ok, lane, (char *)s_mine, xf);
 #pragma unroll
     for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
+    auto to_vgpr = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_ds_bpermute(lane << 2, (int)v); };
+    const DequantConsts dq = {to_vgpr(a.m_lo), to_vgpr(a.m_hi), to_vgpr(a.k_lo), to_vgpr(a.k_hi)};
+    // B holds q - z exactly (the code or-ed into the mantissa of 1024 or 64, minus 1024 + z or 64 + z: 9 vector
+    // instructions per 8 weights); the group's scale multiplies the fp32 sums of the group, once per tile.
     auto emit = [&](const Stage &stg, int i) {
         float4v tot[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-        union { uint2 v; uint32_t d[2]; } sc; sc.v = stg.sc;
+        union { uint2 v; _Float16 h[4]; } sc; sc.v = stg.sc;
 #pragma unroll
         for (int gi = 0; gi < kSliceGroups; ++gi) {
             const uint32_t z = (stg.zq >> (4 * gi)) & 15u;
             const half2v nlo = as_h2((0xE400u + z) * 0x00010001u);          // -(1024 + z), twice
             const half2v nhi = as_h2((0xD400u + (z << 4)) * 0x00010001u);   // -(64 + z), twice
-            const half2v s2 = as_h2(((sc.d[gi >> 1] >> (16 * (gi & 1))) & 0xffffu) * 0x00010001u);
+            float4v acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t u = stg.w[gi][j], t = u >> 8;
                 union { uint32_t d[4]; half8 h; } b;
-                b.d[0] = as_u32((as_h2((u & 0x000F000Fu) | 0x64006400u) + nlo) * s2);
-                b.d[1] = as_u32((as_h2((u & 0x00F000F0u) | 0x54005400u) + nhi) * s2);
-                b.d[2] = as_u32((as_h2((t & 0x000F000Fu) | 0x64006400u) + nlo) * s2);
-                b.d[3] = as_u32((as_h2((t & 0x00F000F0u) | 0x54005400u) + nhi) * s2);
-                tot[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[0][gi][j], b.h, tot[0], 0, 0, 0);
-                tot[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[1][gi][j], b.h, tot[1], 0, 0, 0);
+                b.d[0] = as_u32(as_h2(and_or(u, dq.m_lo, dq.k_lo)) + nlo);
+                b.d[1] = as_u32(as_h2(and_or(u, dq.m_hi, dq.k_hi)) + nhi);
+                b.d[2] = as_u32(as_h2(and_or(t, dq.m_lo, dq.k_lo)) + nlo);
+                b.d[3] = as_u32(as_h2(and_or(t, dq.m_hi, dq.k_hi)) + nhi);
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[0][gi][j], b.h, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[1][gi][j], b.h, acc[1], 0, 0, 0);
             }
+            const float sg = (float)sc.h[gi];
+            tot[0] += sg * acc[0];
+            tot[1] += sg * acc[1];
         }
         float *dst = s_mine + i * 512;
         *(float4v *)(dst + lane * 4) = tot[0];

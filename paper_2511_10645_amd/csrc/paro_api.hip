@@ -162,13 +162,13 @@ paro_status run_linear(const paro_w4_weight *w, const paro_half_t *X, int64_t ld
     if (T > kDecodeMaxTokens && gemm_supported(*w, ldx, ldy, T)) {
         // Moderate token counts leave most of the chip idle in the GEMM (few token tiles), while the
         // streaming kernel re-reads the weights once per 32 tokens: take the cheaper.  Measured per pass:
-        // 17..32 tokens ~5 us plus the tile bytes at ~3.25 TB/s, up to 16 tokens ~3.5 us plus the bytes at
-        // ~5.2 TB/s, and ~2.5 us more where the K-slices of a row are spread over several blocks.
+        // 17..32 tokens ~5 us plus the tile bytes at ~3.75 TB/s, up to 16 tokens ~3.5 us plus the bytes at
+        // ~5.2 TB/s, and ~2.5 us (4 us at 17..32 tokens) more where the K-slices of a row are spread over several blocks.
         const double mb = (double)packed_tiles_bytes(w->c_in, w->c_out) / 1.0e6;
         const int rem = T % kStreamPassTokens;
-        const double ex32 = decode_wide_partial_bytes(w->c_in, w->c_out, kStreamPassTokens) ? 2.5 : 0.0;
+        const double ex32 = decode_wide_partial_bytes(w->c_in, w->c_out, kStreamPassTokens) ? 4.0 : 0.0;
         const double ex16 = decode_wide_partial_bytes(w->c_in, w->c_out, 16) ? 2.5 : 0.0;
-        const double pass32 = 5.0 + mb / 3.25 + ex32;
+        const double pass32 = 5.0 + mb / 3.75 + ex32;
         const double stream_us = (double)(T / kStreamPassTokens) * pass32 +
                                  (rem == 0 ? 0.0 : rem <= 16 ? 3.5 + mb / 5.2 + ex16 : pass32);
         if (T >= 512 || gemm_estimate_us(*w, T) <= stream_us)
