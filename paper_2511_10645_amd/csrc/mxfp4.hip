@@ -306,7 +306,7 @@ static hipError_t launch_mxfp4_decode(const paro_mxfp4_weight &w, const uint32_t
 }
 
 // ------------------------------------------------------------------------------------------
-// More than 16 tokens: tiled GEMM.  Block tile 256 tokens x 256 outputs x 128 channels (one K-step of
+// More than 16 tokens: tiled GEMM.  Block tile 256 (or 128, see the launcher) tokens x 256 outputs x 128 channels (one K-step of
 // the matrix instruction: 64 bytes per row of either operand), 8 waves side by side along the outputs:
 // wave tile 256 tokens x 32 outputs = 16 x 2 MFMA tiles of 16 x 16 (128 accumulator registers).
 //   - Weights never touch LDS: the repacked blob IS the operand order, every 16-row tile of a K-step
@@ -331,14 +331,18 @@ struct MxGemmArgs {
 
 constexpr int kMxBM = 256, kMxBN = 256;
 constexpr int kMxRowBytes = 64;                          // one K-step of one row
-constexpr int kMxStageBytes = kMxBM * kMxRowBytes + kMxBM * 4;   // codes | scale dwords (4 blocks per row)
+constexpr int mx_stage_bytes(int bm) { return bm * kMxRowBytes + bm * 4; }   // codes | scale dwords (4 blocks per row)
 constexpr int kMxChunk = 12;                             // K-steps written out in the loop body (24: no faster)
 
 __device__ __forceinline__ int mx_lds_off(int row, int chunk) { return row * kMxRowBytes + ((chunk ^ ((row >> 1) & 3)) << 4); }
 
+// BM: tokens per block tile, 256, or 128 where 256-token tiles would leave half of the compute units idle
+template <int BM>
 __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [3][kMxStageBytes]
+    extern __shared__ __attribute__((aligned(16))) char smem_mx[];          // [3][kStage]
+    constexpr int kStage = mx_stage_bytes(BM);
+    constexpr int MI = BM / 16;                                             // 16-row MFMA tiles of a wave
     const int bid = blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
     const int pb = a.patch_m * a.patch_n;
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     const int pm = gp % m_patches, pn = gp / m_patches;
     const int mt = pm * a.patch_m + q % a.patch_m, ntile = pn * a.patch_n + q / a.patch_m;
     if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
-    const int m0 = mt * kMxBM, n0 = ntile * kMxBN;
+    const int m0 = mt * BM, n0 = ntile * kMxBN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -362,19 +366,19 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     const uint32_t ga = (uint32_t)((size_t)(m0 + (tid >> 2)) * (a.C / 2) + (tid & 3) * 16);
     const uint32_t ga_step = (uint32_t)(128 * (a.C / 2));
     const int la0 = mx_lds_off(tid >> 2, tid & 3), la1 = mx_lds_off((tid >> 2) + 128, tid & 3);
-    const uint32_t gs = tid < kMxBM ? (uint32_t)((size_t)(m0 + tid) * (a.C / 32)) : kOobM;
-    const int ls = kMxBM * kMxRowBytes + (tid & (kMxBM - 1)) * 4;
+    const uint32_t gs = tid < BM ? (uint32_t)((size_t)(m0 + tid) * (a.C / 32)) : kOobM;
+    const int ls = BM * kMxRowBytes + (tid & (BM - 1)) * 4;
     struct AStage { u32x4 c0, c1; uint32_t sc; };
     auto load_a = [&](int ks, AStage &st) {
         const bool ok = ks < n_ks;
         st.c0 = __builtin_amdgcn_raw_buffer_load_b128(xr, ok ? (int)ga : (int)kOobM, ks * kMxRowBytes, 0);
-        st.c1 = __builtin_amdgcn_raw_buffer_load_b128(xr, ok ? (int)(ga + ga_step) : (int)kOobM, ks * kMxRowBytes, 0);
+        if constexpr (BM == 256) st.c1 = __builtin_amdgcn_raw_buffer_load_b128(xr, ok ? (int)(ga + ga_step) : (int)kOobM, ks * kMxRowBytes, 0);
         st.sc = __builtin_amdgcn_raw_buffer_load_b32(sr, ok ? (int)gs : (int)kOobM, ks * 4, 0);
     };
     auto store_a = [&](char *buf, const AStage &st) {
         *(u32x4 *)(buf + la0) = st.c0;
-        *(u32x4 *)(buf + la1) = st.c1;
-        if (tid < kMxBM) *(uint32_t *)(buf + ls) = st.sc;
+        if constexpr (BM == 256) *(u32x4 *)(buf + la1) = st.c1;
+        if (tid < BM) *(uint32_t *)(buf + ls) = st.sc;
     };
     // ---- weights: the wave's two 16-row tiles, as they lie in the blob ----
     const int nt16 = n0 / 16 + wave * 2;
@@ -396,9 +400,9 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
         d1 = __builtin_amdgcn_raw_buffer_load_b32(br, ok && n_ok1 ? (int)(gw0 + gw_step) : (int)kOobM, slice * 256, 0);
     };
 
-    float4v acc[16][2];
+    float4v acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { acc[i][0] = float4v{0.f, 0.f, 0.f, 0.f}; acc[i][1] = float4v{0.f, 0.f, 0.f, 0.f}; }
+    for (int i = 0; i < MI; ++i) { acc[i][0] = float4v{0.f, 0.f, 0.f, 0.f}; acc[i][1] = float4v{0.f, 0.f, 0.f, 0.f}; }
 
     // ---- prologue ----
     // LDS holds three K-steps of activations: step k is multiplied from buffer k % 3 while step k + 2 is written
@@ -417,7 +421,7 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     load_wscales(0, wq0, wq1);
     load_wscales(1, wq0_n, wq1_n);
     store_a(smem_mx, ar[0]);
-    store_a(smem_mx + kMxStageBytes, ar[1]);
+    store_a(smem_mx + kStage, ar[1]);
     load_a(2, ar[2]);
     load_a(3, ar[0]);
     load_a(4, ar[1]);
@@ -427,7 +431,7 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 
     const int fr = lane & 15, fkb = lane >> 4;
     const int fa_off = mx_lds_off(fr, fkb);                                          // + 1024 per MFMA tile (16 rows)
-    const int fs_off = kMxBM * kMxRowBytes + fr * 4 + fkb;                           // + 64 per MFMA tile
+    const int fs_off = BM * kMxRowBytes + fr * 4 + fkb;                           // + 64 per MFMA tile
     // fragments are requested kFragAhead tiles before their MFMAs (an LDS read takes several times as long as the
     // two MFMAs of a tile), across the end of a K-step as well
     constexpr int kFragAhead = 3;
@@ -444,24 +448,24 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
             constexpr int u = I;
             const int ks = ks0 + u;
             if (ks >= n_ks) return false;
-            const char *cur = smem_mx + (u % 3) * kMxStageBytes;
-            const char *nxt = smem_mx + ((u + 1) % 3) * kMxStageBytes;
-            char *fill = smem_mx + ((u + 2) % 3) * kMxStageBytes;
+            const char *cur = smem_mx + (u % 3) * kStage;
+            const char *nxt = smem_mx + ((u + 1) % 3) * kStage;
+            char *fill = smem_mx + ((u + 2) % 3) * kStage;
             AStage &an = ar[(u + 2) % 3];                                           // holds K-step ks + 2
             BStage &bc = bq[u % 3];
             const uint32_t ws0 = wq0 >> (8 * (u & 3)), ws1 = wq1 >> (8 * (u & 3));
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
+            for (int i = 0; i < MI; ++i) {
                 constexpr int kRing = kFragAhead + 1;
                 const int ip = i + kFragAhead;
-                if (ip < 16) {
+                if (ip < MI) {
                     fa[ip % kRing] = *(const u32x4 *)(cur + fa_off + ip * 1024);
                     xsb[ip % kRing] = *(const uint8_t *)(cur + fs_off + ip * 64);
                 } else {
-                    fa[ip % kRing] = *(const u32x4 *)(nxt + fa_off + (ip - 16) * 1024);
-                    xsb[ip % kRing] = *(const uint8_t *)(nxt + fs_off + (ip - 16) * 64);
+                    fa[ip % kRing] = *(const u32x4 *)(nxt + fa_off + (ip - MI) * 1024);
+                    xsb[ip % kRing] = *(const uint8_t *)(nxt + fs_off + (ip - MI) * 64);
                 }
-                if (i == 4) {                                                       // requested three K-steps ago
+                if (i == MI / 4) {                                                  // requested three K-steps ago
                     store_a(fill, an);
                     load_a(ks + 5, an);
                 }
@@ -497,7 +501,7 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     const int orow = lane >> 2, ocol = (lane & 3) * 8;                               // this lane's 8 outputs of the strip
     const bool row_wide = a.ldy % 8 == 0 && ((uintptr_t)a.Y % 16) == 0 && nw0 + 32 <= a.N;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < MI; ++i) {
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
@@ -521,6 +525,29 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     }
 }
 
+template <int BM>
+static hipError_t launch_mxfp4_gemm_bm(MxGemmArgs &a, hipStream_t s)
+{
+    a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = (a.N + kMxBN - 1) / kMxBN;
+    int blocks;
+    gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
+    constexpr int lds = 3 * mx_stage_bytes(BM);
+    static std::atomic<uint64_t> attr_done{0};
+    if (const int dev = once_pending(attr_done); dev >= 0) {
+        hipError_t e = hipFuncSetAttribute((const void *)mxfp4_gemm_kernel<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        once_done(attr_done, dev);
+    }
+    hipLaunchKernelGGL(mxfp4_gemm_kernel<BM>, dim3(blocks), dim3(512), lds, s, a);
+    return hipGetLastError();
+}
+
+// 256-token tiles fill at most half a round of blocks: 128-token tiles, twice as many
+static bool mxfp4_gemm_small_tiles(const paro_mxfp4_weight &w, int T)
+{
+    return (long)((T + kMxBM - 1) / kMxBM) * ((w.c_out + kMxBN - 1) / kMxBN) <= 128;
+}
+
 static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *xc, const uint8_t *xs, int T, paro_half_t *Y,
                                     int64_t ldy, hipStream_t s)
 {
@@ -530,24 +557,13 @@ static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *
     a.blob_bytes = a.scales_off + (uint32_t)((size_t)w.c_out * w.c_in / 32);
     a.xc = xc; a.xs = xs; a.Y = (_Float16 *)Y; a.ldy = ldy; a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.K128 = w.c_in / 128; a.KS = w.c_in / 512;
-    a.m_tiles = (T + kMxBM - 1) / kMxBM; a.n_tiles = (w.c_out + kMxBN - 1) / kMxBN;
-    int blocks;
-    gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
-    constexpr int lds = 3 * kMxStageBytes;
-    static std::atomic<uint64_t> attr_done{0};
-    if (const int dev = once_pending(attr_done); dev >= 0) {
-        hipError_t e = hipFuncSetAttribute((const void *)mxfp4_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        once_done(attr_done, dev);
-    }
-    hipLaunchKernelGGL(mxfp4_gemm_kernel, dim3(blocks), dim3(512), lds, s, a);
-    return hipGetLastError();
+    return mxfp4_gemm_small_tiles(w, T) ? launch_mxfp4_gemm_bm<128>(a, s) : launch_mxfp4_gemm_bm<256>(a, s);
 }
 
 // Which kernel: the streaming kernel reads the whole weight once per 64 tokens (32 or 16 where K is deep), the
-// GEMM once per 256 but works on 256 x 256 tiles whatever T is, one round of them per 256 compute units.
+// GEMM once per 256 (or 128) but works on whole tiles whatever T is, one round of them per 256 compute units.
 // Measured: a pass of TB blocks of 16 tokens takes ~3 us + the blob at 5.5 TB/s + TB x (0.8 us + the blob at
-// 30 TB/s); a round of GEMM tiles ~0.9 us per K-step + 3 us.
+// 30 TB/s); a round of GEMM tiles ~0.9 us per K-step (0.8 us with 128-token tiles) + 3 us.
 hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_codes, const uint8_t *x_scales, int T,
                                paro_half_t *Y, int64_t ldy, hipStream_t s)
 {
@@ -557,8 +573,10 @@ hipError_t launch_mxfp4_linear(const paro_mxfp4_weight &w, const uint32_t *x_cod
         const double mb = ((double)w.c_out * w.c_in / 2 + (double)w.c_out * w.c_in / 32) / 1.0e6;
         const double pass_us = 3.0 + mb / 5.5 + (pass / 16) * (0.8 + mb / 30.0);
         const double stream_us = (double)((T + pass - 1) / pass) * pass_us;
-        const long tiles = (long)((T + kMxBM - 1) / kMxBM) * ((w.c_out + kMxBN - 1) / kMxBN);
-        const double gemm_us = (double)((tiles + 255) / 256) * ((w.c_in / 128) * 0.9 + 3.0);
+        const bool small = mxfp4_gemm_small_tiles(w, T);
+        const int bm = small ? 128 : kMxBM;
+        const long tiles = (long)((T + bm - 1) / bm) * ((w.c_out + kMxBN - 1) / kMxBN);
+        const double gemm_us = (double)((tiles + 255) / 256) * ((w.c_in / 128) * (small ? 0.8 : 0.9) + 3.0);
         if (gemm_us < stream_us) return launch_mxfp4_gemm(w, x_codes, x_scales, T, Y, ldy, s);
     }
     for (int t0 = 0; t0 < T;) {
