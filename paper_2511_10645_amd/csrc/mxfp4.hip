@@ -326,7 +326,7 @@ struct MxGemmArgs {
     _Float16 *Y; int64_t ldy;
     const _Float16 *bias;
     int T, C, N, K128, KS;
-    int m_tiles, n_tiles, patch_m, patch_n;
+    int m_tiles, n_tiles, n_tile0, patch_m, patch_n;     // the launch covers output tiles [n_tile0, n_tile0 + n_tiles)
 };
 
 constexpr int kMxBM = 256, kMxBN = 256;
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
     const int pm = gp % m_patches, pn = gp / m_patches;
     const int mt = pm * a.patch_m + q % a.patch_m, ntile = pn * a.patch_n + q / a.patch_m;
     if (mt >= a.m_tiles || ntile >= a.n_tiles) return;
-    const int m0 = mt * BM, n0 = ntile * kMxBN;
+    const int m0 = mt * BM, n0 = (a.n_tile0 + ntile) * kMxBN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -526,9 +526,9 @@ __global__ __launch_bounds__(512) void mxfp4_gemm_kernel(MxGemmArgs a)
 }
 
 template <int BM>
-static hipError_t launch_mxfp4_gemm_bm(MxGemmArgs &a, hipStream_t s)
+static hipError_t launch_mxfp4_gemm_bm(MxGemmArgs &a, int n_tile0, int n_count, hipStream_t s)
 {
-    a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = (a.N + kMxBN - 1) / kMxBN;
+    a.m_tiles = (a.T + BM - 1) / BM; a.n_tiles = n_count; a.n_tile0 = n_tile0;
     int blocks;
     gemm_patches(a.m_tiles, a.n_tiles, a.patch_m, a.patch_n, blocks);
     constexpr int lds = 3 * mx_stage_bytes(BM);
@@ -557,7 +557,17 @@ static hipError_t launch_mxfp4_gemm(const paro_mxfp4_weight &w, const uint32_t *
     a.blob_bytes = a.scales_off + (uint32_t)((size_t)w.c_out * w.c_in / 32);
     a.xc = xc; a.xs = xs; a.Y = (_Float16 *)Y; a.ldy = ldy; a.bias = (const _Float16 *)w.bias;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.K128 = w.c_in / 128; a.KS = w.c_in / 512;
-    return mxfp4_gemm_small_tiles(w, T) ? launch_mxfp4_gemm_bm<128>(a, s) : launch_mxfp4_gemm_bm<256>(a, s);
+    const int m_big = (T + kMxBM - 1) / kMxBM, n_all = (w.c_out + kMxBN - 1) / kMxBN;
+    if (mxfp4_gemm_small_tiles(w, T)) return launch_mxfp4_gemm_bm<128>(a, 0, n_all, s);
+    // A last round of 256-token tiles that would be at most half full runs as a launch of its own with 128-token
+    // tiles (896 tiles = 3 rounds + one round of 256 half-size tiles instead of 4 rounds).
+    const long tiles = (long)m_big * n_all, full = tiles / 256, rem = tiles - full * 256;
+    const int n_main = (int)(full * 256 / m_big);
+    if (rem > 0 && rem <= 128 && n_main > 0 && n_main < n_all) {
+        hipError_t e = launch_mxfp4_gemm_bm<256>(a, 0, n_main, s);
+        return e != hipSuccess ? e : launch_mxfp4_gemm_bm<128>(a, n_main, n_all - n_main, s);
+    }
+    return launch_mxfp4_gemm_bm<256>(a, 0, n_all, s);
 }
 
 // Which kernel: the streaming kernel reads the whole weight once per 64 tokens (32 or 16 where K is deep), the

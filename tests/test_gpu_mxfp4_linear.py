@@ -89,6 +89,7 @@ def test_repack_and_unpack_are_bit_exact(P, shape):
     dict(seed=9211, T=257, C=2048, N=528, bias=False),        # a second token tile of one row
     dict(seed=9212, T=1024, C=4096, N=1536, bias=True),       # 8 x 6 tiles of 128 tokens, 32 K-steps
     dict(seed=9221, T=2100, C=512, N=3856, bias=True),        # 9 x 16 tiles of 256 tokens (more than half a round), ragged both ways
+    dict(seed=9222, T=2048, C=512, N=9216, bias=False),       # 8 x 36 = 288 tiles: one round of 256-token tiles, the last 4 output tiles as 128-token tiles
     dict(seed=9215, T=64, C=4096, N=528, bias=True),          # 64 tokens in one pass: four token blocks per wave
     dict(seed=9216, T=40, C=5120, N=272, bias=False),         # 10 slices, three of four token blocks used
     dict(seed=9217, T=32, C=14336, N=96, bias=True),          # 28 slices: 4 per wave, two token blocks
