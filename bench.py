@@ -34,10 +34,10 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
 MFMA_FP4_PEAK_TFLOPS = 10100.0 # dense fp4
 # HBM bytes per launch of the dominant fused kernel (gate/up) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --pmc-probe [--config 4]`, scaled by the same counters on a 256 MiB copy
-# (profiles/decode_stream_pmc.md).  Config 2 (16 tokens) and config 4's gate/up take the two-launch route (rotation pass +
-# bare kernel): the sum of both launches' counters (config 2: 62.3 MB + 0.9 MB written by the linear, 0.4 MB by the pass;
-# config 4: 147.5 MB + 0.1 MB, 0.3 MB).
-TRAFFIC_BYTES_PER_LAUNCH = {1: 64_800_000, 2: 63_600_000, 4: 147_900_000}
+# (profiles/decode_stream_pmc.md).  Configs 1 and 4 (one token): the streaming kernel whose waves transform their own
+# K-slice (62.07 MB + 0.06 MB written; 148.45 + 0.11).  Config 2 (16 tokens) takes the two-launch route (rotation pass +
+# bare kernel): the sum of both launches' counters (62.3 MB + 0.9 MB written by the linear, 0.4 MB by the pass).
+TRAFFIC_BYTES_PER_LAUNCH = {1: 62_100_000, 2: 63_600_000, 4: 148_600_000}
 
 
 def algorithmic_bytes(c_in: int, c_out: int, T: int, rotated: bool = True, K: int = 8) -> int:
@@ -193,6 +193,16 @@ def main() -> int:
         w = L["copies"][0]
         return paro.paro_workspace_bytes(L["rot"], w, T) > paro.paro_workspace_exchange_bytes(L["rot"], w, T)
 
+    def fused_kernels(L, T: int) -> str:
+        # which kernels the fused call launches on this shape, read off the workspace it asks for
+        w = L["copies"][0]
+        if two_launches(L, T):
+            return f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})"
+        ex = paro.paro_workspace_exchange_bytes(L["rot"], w, T)
+        if T == 1 and L["shape"].c_in > 512 and ex == max(256, paro.paro_workspace_exchange_bytes(None, w, T)):
+            return "decode_wide_kernel (every wave transforms its own K-slice, T=1)"
+        return f"decode_kernel (fused, split-K, T={T})"
+
     def roofline_of(config: int, lin, per, T: int):
         dom = max(lin, key=lambda L: L["bytes"])
         dom_us = per[dom["shape"].name]["us_fused"]
@@ -201,9 +211,7 @@ def main() -> int:
         read_bytes = dom["copies"][0].packed.numel()
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(config),
-                "kernel": (f"rotate_planned_kernel + decode_wide_kernel (two launches, T={T})" if two_launches(dom, T) else
-                           f"decode_kernel (fused, split-K, T={T})")
-                          + f" on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
+                "kernel": fused_kernels(dom, T) + f" on {dom['shape'].name} {dom['shape'].c_in}->{dom['shape'].c_out}",
                 "algorithmic_bytes_per_launch": dom["bytes"], "avg_launch_us": dom_us,
                 "pure_read_us_same_bytes": round(read_us, 3),
                 "frac_of_measured": round((dom["bytes"] / dom_us) / (read_bytes / read_us), 4)}

@@ -88,9 +88,24 @@ __device__ __forceinline__ void load_x_fragments(const DecodeArgs &a, int ks, bo
         }
 }
 
-template <bool SPLIT, bool T1>
-__global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs a)
+// ROTK > 0 (one token only): the transform of Eq. 8 with ROTK rotation layers is hosted.  A wave owns one K-slice,
+// so it needs the transformed activations of that slice only - its 4 groups - and produces them itself: no
+// hand-over between waves, no block barrier, and nothing is exchanged between blocks that the bare kernel would
+// not exchange.  The 4 groups are rotated side by side (their chains of 4 multiply-adds and a permute are
+// independent) from the compact copy of the plan (4 bytes per lane and layer: 44 registers hold all of it, so
+// every plan row is requested before the first weight stage and none waits behind a weight tile - vector memory
+// returns in order; sine and cosine come from the hardware functions, which fill the permutes' latency), and the
+// first weight stages are in flight the whole time: what the launch pays for the transform is one 4-wide rotation
+// (~0.7 us) where the stream is too short to hide it, and next to nothing in front of a long stream.  Every block
+// repeats the work of its column of K-slices (the compact plan, 22 bytes per channel, comes out of L2 for all but
+// the first), which is what makes this form unsuitable for more than one token.
+// MAXW: most waves per block (8: two waves per SIMD and 256 registers; otherwise kWideWaves).
+constexpr int kRotStageWords = kSliceCh / 2;     // the slice's 512 fp16 activations of one token, in floats
+
+template <bool SPLIT, bool T1, int ROTK = 0, int MAXW = kWideWaves>
+__global__ __launch_bounds__(MAXW * 64) void decode_wide_kernel(DecodeArgs a)
 {
+    static_assert(ROTK == 0 || T1, "the hosted transform is for one token");
     constexpr int NS = kWideStages;
     // [waves][tiles per block] partial tiles | kReduceWords reduce scratch
     extern __shared__ __attribute__((aligned(16))) float s_wide[];
@@ -107,14 +122,81 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(DecodeArgs
     const __amdgpu_buffer_rsrc_t blob = make_rsrc(a.blob, a.blob_bytes);
     constexpr int kTileWords = T1 ? kTileN : 256;
     // a wave's partial tiles are contiguous; several tokens: the same area first parks its activations
-    const int wstride = T1 ? a.tiles_per_block * kTileWords : max(a.tiles_per_block * kTileWords, kXsWords);
+    const int wstride = ROTK > 0 ? max(a.tiles_per_block * kTileWords, kRotStageWords)
+                        : T1     ? a.tiles_per_block * kTileWords
+                                 : max(a.tiles_per_block * kTileWords, kXsWords);
     float *s_mine = s_wide + (size_t)wave * wstride;
     float *s_red = s_wide + (size_t)nw * wstride;
 
     Stage st[NS];
     half8 xf[kSliceGroups][4];
     const int ft = lane & 15, fkb = lane >> 4;
-    if constexpr (!T1) {
+    if constexpr (ROTK > 0) {
+        constexpr int K = ROTK;
+        const int ksp = slice_ok ? ks : 0;                                   // a surplus wave repeats slice 0 (its tiles are empty)
+        _Float16 *sx = (_Float16 *)s_mine;                                   // the slice of the token, 512 fp16
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.X, (uint32_t)a.C * 2u);
+        uint32_t xin[kSliceGroups];
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+            xin[g2] = __builtin_amdgcn_raw_buffer_load_b32(xr, (int)(((size_t)ksp * kSliceCh + g2 * kGroup + 2 * lane) * 2), 0, 0);
+        // the compact plan of the slice's 4 groups: 3 + K dwords per lane and group, all requested at once
+        const uint32_t *cplan = a.plan + (size_t)ksp * kSliceGroups * plan_compact_group_dwords(K) + lane;
+        uint32_t io[kSliceGroups], sci[kSliceGroups], sco[kSliceGroups], pm[kSliceGroups][K];
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+            const uint32_t *gp = cplan + (size_t)g2 * plan_compact_group_dwords(K);
+            io[g2] = gp[0]; sci[g2] = gp[64]; sco[g2] = gp[128];
+#pragma unroll
+            for (int l = 0; l < K; ++l) pm[g2][l] = gp[(kPlanCompactHeadRows + l) * 64];
+        }
+        // the weight stream starts here, behind the plan and the activations (vector memory returns in order)
+#pragma unroll
+        for (int s = 0; s + 1 < NS; ++s) load_stage(blob, a, tile_of(s), ks, lane, st[s]);
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) *(uint32_t *)&sx[g2 * kGroup + 2 * lane] = xin[g2];
+        __builtin_amdgcn_wave_barrier();
+        // the 4 groups side by side: their chains (4 multiply-adds, then a permute that takes far longer) are independent
+        float va[kSliceGroups], vb[kSliceGroups];
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+            va[g2] = (float)sx[g2 * kGroup + (io[g2] & 0xff)] * (float)as_h2(sci[g2])[0];
+            vb[g2] = (float)sx[g2 * kGroup + ((io[g2] >> 8) & 0xff)] * (float)as_h2(sci[g2])[1];
+        }
+#pragma unroll
+        for (int l = 0; l < K; ++l) {
+#pragma unroll
+            for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+                const uint32_t m = pm[g2][l];
+                const float rev = (float)(m >> 8) * (1.0f / 16777216.0f);      // exact: 24 bits
+                const float c = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
+                const bool ai = m & kCompactAIsI, ki = m & kCompactKeepI;
+                const float ni_a = ai ? c : -sn, ni_b = ai ? -sn : c, nj_a = ai ? sn : c, nj_b = ai ? c : sn;
+                const float m00 = ki ? ni_a : nj_a, m01 = ki ? ni_b : nj_b, m10 = ki ? nj_a : ni_a, m11 = ki ? nj_b : ni_b;
+                const float na = m00 * va[g2] + m01 * vb[g2], nb2 = m10 * va[g2] + m11 * vb[g2];
+                va[g2] = na;
+                vb[g2] = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute((int)((m & 63u) << 2), __float_as_int(nb2)))
+                                     : nb2;
+            }
+        }
+        // every lane has read its inputs: the staging rows take the results
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2) {
+            sx[g2 * kGroup + ((io[g2] >> 16) & 0xff)] = (_Float16)(va[g2] * (float)as_h2(sco[g2])[0]);
+            sx[g2 * kGroup + (io[g2] >> 24)] = (_Float16)(vb[g2] * (float)as_h2(sco[g2])[1]);
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int g2 = 0; g2 < kSliceGroups; ++g2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (ft == 0) v = *(const half8 *)&sx[g2 * kGroup + fkb * 32 + j * 8];
+                xf[g2][j] = v;
+            }
+        __builtin_amdgcn_wave_barrier();                                      // the area holds partial sums from here on
+    } else if constexpr (!T1) {
         half8 xt[1][kSliceGroups][4];
         load_x_fragments<1>(a, ks, slice_ok, lane, (char *)s_mine, xt);
 #pragma unroll
@@ -298,7 +380,7 @@ __global__ __launch_bounds__(kWide2Waves * 64) void decode_wide2_kernel(DecodeAr
 }
 
 struct WideGeometry { int kb, nb, waves, tiles_per_block; size_t lds; };
-static WideGeometry wide_geometry(int c_in, int c_out, int T)
+static WideGeometry wide_geometry(int c_in, int c_out, int T, bool hosted = false)
 {
     const bool two = T > 16;                                 // two blocks of 16 tokens per wave (decode_wide2_kernel)
     WideGeometry g;
@@ -320,7 +402,8 @@ static WideGeometry wide_geometry(int c_in, int c_out, int T)
     g.tiles_per_block = tpb;
     g.nb = (NT + tpb - 1) / tpb;
     const int tile_words = two ? 512 : T == 1 ? kTileN : 256;
-    const int wstride = T == 1 ? tpb * tile_words : std::max(tpb * tile_words, kXsWords);   // as in the kernels
+    const int wstride = hosted ? std::max(tpb * tile_words, kRotStageWords)                // as in the kernels
+                        : T == 1 ? tpb * tile_words : std::max(tpb * tile_words, kXsWords);
     g.lds = ((size_t)g.waves * wstride + kReduceWords) * sizeof(float);
     return g;
 }
@@ -332,12 +415,17 @@ size_t decode_wide_partial_bytes(int c_in, int c_out, int T)
     return g.kb > 1 ? (size_t)g.kb * tp * c_out * sizeof(float) : 0;
 }
 
-// ws: the exchange part of the workspace (may be NULL where no partial sums are exchanged)
+// Whether the one-token kernel can host this transform (instantiated for the paper's 8 layers)
+bool decode_wide_hosts(const paro_rotation &rot, int T) { return T == 1 && rot.plan && rot.n_layers == 8; }
+
+// ws: the exchange part of the workspace (may be NULL where no partial sums are exchanged).
+// rot: NULL for the bare linear; otherwise a transform decode_wide_hosts() accepts, applied to X by the kernel itself.
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
-                              int T, void *ws, hipStream_t s)
+                              int T, void *ws, hipStream_t s, const paro_rotation *rot)
 {
     if (packed_blob_bytes(w.c_in, w.c_out) >= (1ull << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets (checked by the caller)
-    const WideGeometry g = wide_geometry(w.c_in, w.c_out, T);
+    if (rot && (!decode_wide_hosts(*rot, T) || rot->c_in != w.c_in)) return hipErrorInvalidValue;
+    const WideGeometry g = wide_geometry(w.c_in, w.c_out, T, rot != nullptr);
     if (g.kb > 64 || g.lds > kWideLdsBytes || (g.kb > 1 && !ws)) return hipErrorInvalidValue;
     DecodeArgs a;
     a.blob = w.packed;
@@ -346,7 +434,7 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
     a.blob_bytes = a.zeros_off + (uint32_t)packed_zeros_bytes(w.c_in, w.c_out);
     a.X = (const _Float16 *)X; a.ldx = ldx; a.Y = (_Float16 *)Y; a.ldy = ldy;
     a.bias = (const _Float16 *)w.bias;
-    a.plan = nullptr;
+    a.plan = rot ? (const uint32_t *)rot->plan + plan_compact_offset_dwords(rot->c_in / kGroup, rot->n_layers) : nullptr;
     a.err = ws ? (uint32_t *)ws + kWsErrorWord : nullptr;
     a.partial = ws ? (float *)((char *)ws + kWsPartialOff) : nullptr;
     a.T = T; a.C = w.c_in; a.N = w.c_out; a.G = w.c_in / kGroup; a.NT = w.c_out / kTileN;
@@ -355,9 +443,11 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
     a.m_lo = 0x000F000Fu; a.m_hi = 0x00F000F0u; a.k_lo = 0x64006400u; a.k_hi = 0x54005400u;
     static std::atomic<uint64_t> attr_done{0};
     if (const int dev = once_pending(attr_done); dev >= 0) {
-        const void *fns[6] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
-                              (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>,
-                              (const void *)decode_wide2_kernel<false>, (const void *)decode_wide2_kernel<true>};
+        const void *fns[] = {(const void *)decode_wide_kernel<false, false>, (const void *)decode_wide_kernel<false, true>,
+                             (const void *)decode_wide_kernel<true, false>, (const void *)decode_wide_kernel<true, true>,
+                             (const void *)decode_wide2_kernel<false>, (const void *)decode_wide2_kernel<true>,
+                             (const void *)decode_wide_kernel<false, true, 8, 8>, (const void *)decode_wide_kernel<true, true, 8, 8>,
+                             (const void *)decode_wide_kernel<false, true, 8>};
         for (const void *f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return e;
@@ -365,7 +455,13 @@ hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int
         once_done(attr_done, dev);
     }
     const dim3 grid(g.kb, g.nb), block(g.waves * 64);
-    if (T > 16) {
+    if (rot) {
+        // blocks of more than 8 waves hold all K-slices of their rows (wide_geometry): only the 8-wave form is split
+        if (g.kb > 1 && g.waves > 8) return hipErrorInvalidValue;
+        if (g.kb > 1)          hipLaunchKernelGGL((decode_wide_kernel<true, true, 8, 8>), grid, block, g.lds, s, a);
+        else if (g.waves <= 8) hipLaunchKernelGGL((decode_wide_kernel<false, true, 8, 8>), grid, block, g.lds, s, a);
+        else                   hipLaunchKernelGGL((decode_wide_kernel<false, true, 8>), grid, block, g.lds, s, a);
+    } else if (T > 16) {
         if (g.kb > 1) hipLaunchKernelGGL((decode_wide2_kernel<true>), grid, block, g.lds, s, a);
         else          hipLaunchKernelGGL((decode_wide2_kernel<false>), grid, block, g.lds, s, a);
     } else if (T == 1) {

@@ -62,10 +62,22 @@ inline bool can_fuse_decode(const paro_rotation *rot, const paro_w4_weight *w, i
 // (4096 / 5120 / 14336 / 27648 input channels, 4096 .. 55296 outputs): 1 - 2 MB of partial sums
 // for one token, 0.75 MB for 2..4 tokens.  `always`: for callers without a scratch part.
 constexpr size_t kFusePartialOne = 3u << 19, kFusePartialFew = 3u << 18;
+// One token, the paper's 8 layers, a long weight stream: the kernel in which every wave transforms its own K-slice
+// (decode_wide.hip) - nothing is exchanged between blocks that the bare linear would not exchange, and the stream
+// hides the transform.  Every block repeats the rotation of its column of K-slices (~3 us of vector work and plan
+// traffic per block), which a short stream does not hide: measured against the K-major kernel on MI355X,
+// 4096 -> 28672 (59 MB of tiles) 13.3 against 14.8 us, 5120 -> 55296 26.9 against 28.8, 27648 -> 5120 (71 MB) 15.9
+// against 18.9, but 14336 -> 4096 (29 MB) 11.3 against 10.6 and 4096 -> 6144 8.6 against 6.9.
+constexpr size_t kWideHostMinBytes = 40u << 20;
+inline bool fused_wide(const paro_rotation *rot, const paro_w4_weight *w, int T)
+{
+    return can_fuse_decode(rot, w, T) && decode_wide_hosts(*rot, T) &&
+           packed_tiles_bytes(w->c_in, w->c_out) >= kWideHostMinBytes;
+}
 inline bool fused_decode(const paro_rotation *rot, const paro_w4_weight *w, int T, bool always = false)
 {
     if (!can_fuse_decode(rot, w, T)) return false;
-    if (always) return true;
+    if (always || fused_wide(rot, w, T)) return true;
     return decode_geometry(w->c_in, w->c_out, T).partial_bytes <= (T == 1 ? kFusePartialOne : kFusePartialFew);
 }
 
@@ -99,8 +111,8 @@ WsLayout ws_layout(const paro_rotation *rot, const paro_w4_weight *w, int T, boo
     if (fast_weight(w)) {
         // partial sums of the kernel this call launches: the K-major one (one part per K-slice) or the bare one
         // (parts only beyond 6144 channels)
-        const size_t part = fused ? decode_geometry(w->c_in, w->c_out, T).partial_bytes
-                                  : decode_wide_partial_bytes(w->c_in, w->c_out, T);
+        const size_t part = fused && !fused_wide(rot, w, T) ? decode_geometry(w->c_in, w->c_out, T).partial_bytes
+                                                            : decode_wide_partial_bytes(w->c_in, w->c_out, T);
         // the bare linear without partial sums to exchange needs no workspace at all
         L.exchange_bytes = (rot || part) ? kWsPartialOff + round_up(part, 256) : 0;
         if (T > kDecodeMaxTokens) L.gemm_bytes = round_up(gemm_scratch_bytes(*w, T), 256);
@@ -268,7 +280,7 @@ size_t paro_workspace_partials_offset(void) { return kWsPartialOff; }
 size_t paro_rotation_plan_bytes(const paro_rotation *rot)
 {
     if (check_rotation(rot) != PARO_OK) return 0;
-    return round_up((size_t)(rot->c_in / kGroup) * plan_group_dwords(rot->n_layers) * 4, 256);
+    return round_up(plan_total_dwords(rot->c_in / kGroup, rot->n_layers) * 4, 256);
 }
 
 paro_status paro_rotation_plan_build(const paro_rotation *rot, void *plan_out, void *stream)
@@ -356,6 +368,7 @@ static paro_status rotated_linear(const paro_rotation *rot, const paro_w4_weight
     if (L.total && !aligned(ws, 256)) return PARO_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
 
+    if (fused_wide(rot, w, T)) return from_hip(launch_decode_wide(*w, X, ldx, Y, ldy, T, ws, s, rot));
     if (fused_decode(rot, w, T, always_fuse)) return from_hip(launch_decode(rot, *w, X, ldx, Y, ldy, T, ws, s));
 
     // two passes: transform into the workspace, then the bare linear

@@ -37,6 +37,20 @@ constexpr uint32_t kMetaKeepI = 1u << 9;
 
 __host__ __device__ inline int plan_rows(int n_layers) { return kPlanHeadRows + kPlanRowsPerLayer * n_layers; }
 __host__ __device__ inline size_t plan_group_dwords(int n_layers) { return (size_t)plan_rows(n_layers) * kLanes; }
+// Second part of the plan blob, behind the rows of all groups: the same plan in 4 bytes per lane and layer, for the
+// one-token linear whose waves each transform their own K-slice (every block reads the whole plan, so its size
+// counts).  Per group 3 + n_layers rows of 64 dwords: [in_a | in_b << 8 | out_a << 16 | out_b << 24],
+// [fp16 scale of in_a | fp16 scale of in_b << 16], [the same for out_a, out_b], then per layer
+// [lane to pull from | a-is-i << 6 | keep-i << 7 | angle << 8] with the angle in units of 2^-24 of a revolution
+// (the hardware sine and cosine take revolutions and are accurate to 1.3e-7 on these arguments, measured).
+constexpr int kPlanCompactHeadRows = 3;
+constexpr uint32_t kCompactAIsI = 1u << 6, kCompactKeepI = 1u << 7;
+__host__ __device__ inline size_t plan_compact_group_dwords(int n_layers) { return (size_t)(kPlanCompactHeadRows + n_layers) * kLanes; }
+__host__ __device__ inline size_t plan_compact_offset_dwords(int n_groups, int n_layers) { return (size_t)n_groups * plan_group_dwords(n_layers); }
+__host__ __device__ inline size_t plan_total_dwords(int n_groups, int n_layers)
+{
+    return (size_t)n_groups * (plan_group_dwords(n_layers) + plan_compact_group_dwords(n_layers));
+}
 
 // ---------------------------------------------------------------------------------------
 // Repacked weight blob (paro_w4_repack).  NT = c_out/16 row tiles, G = c_in/128 groups,
@@ -139,8 +153,9 @@ hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, con
 // reduced through LDS; wider layers spread the slices over several blocks and exchange partials.
 // ws: the exchange part of the workspace.
 size_t decode_wide_partial_bytes(int c_in, int c_out, int T);
+bool decode_wide_hosts(const paro_rotation &rot, int T);
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
-                              int T, void *ws, hipStream_t s);
+                              int T, void *ws, hipStream_t s, const paro_rotation *rot = nullptr);
 hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,
                                  paro_half_t *Y, int64_t ldy, int T, hipStream_t s);
 

@@ -27,6 +27,7 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
     __shared__ uint8_t s_pi[kMaxLayers][64], s_pj[kMaxLayers][64];   // completed matching per layer
     __shared__ int16_t s_slot[kMaxLayers][64];                        // source slot of pair, -1 = filler
     __shared__ float s_c[kMaxLayers][64], s_s[kMaxLayers][64];
+    __shared__ uint32_t s_rev[kMaxLayers][64];                        // angle of the pair in units of 2^-24 of a revolution
     __shared__ uint8_t s_cha[kMaxLayers][64], s_chb[kMaxLayers][64];  // channels in slots a, b before layer l
     __shared__ uint8_t s_pair[kMaxLayers][64];                        // which completed pair lane p processes
     __shared__ uint8_t s_src[kMaxLayers][64];                         // lane to pull from after layer l
@@ -68,12 +69,17 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
     for (int l = 0; l < n_layers; ++l) {
         int slot = s_slot[l][lane];
         float c = 1.0f, s = 0.0f;
+        uint32_t rev = 0;
         if (slot >= 0) {
             double sd, cd;
-            sincos((double)gt[(size_t)l * ppl + slot], &sd, &cd);
+            const double th = (double)gt[(size_t)l * ppl + slot];
+            sincos(th, &sd, &cd);
             c = (float)cd; s = (float)sd;
+            double turns = th * 0.15915494309189535;                  // 1 / (2 pi)
+            turns -= floor(turns);
+            rev = (uint32_t)llrint(turns * 16777216.0) & 0xFFFFFFu;
         }
-        s_c[l][lane] = c; s_s[l][lane] = s;
+        s_c[l][lane] = c; s_s[l][lane] = s; s_rev[l][lane] = rev;
     }
     __syncthreads();
 
@@ -148,6 +154,19 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
         row[0 * 64 + lane] = __float_as_uint(s_c[l][pr]);
         row[1 * 64 + lane] = __float_as_uint(s_s[l][pr]);
         row[2 * 64 + lane] = meta;
+    }
+    // the compact copy (see plan_compact_group_dwords)
+    uint32_t *cout = plan + plan_compact_offset_dwords(gridDim.x, n_layers) + (size_t)g * plan_compact_group_dwords(n_layers);
+    auto h16 = [](float f) { union { _Float16 h; uint16_t u; } v; v.h = (_Float16)f; return (uint32_t)v.u; };
+    cout[0 * 64 + lane] = out[0 * 64 + lane];
+    cout[1 * 64 + lane] = h16(sia) | (h16(sib) << 16);
+    cout[2 * 64 + lane] = h16(soa) | (h16(sob) << 16);
+    for (int l = 0; l < n_layers; ++l) {
+        int pr = s_pair[l][lane];
+        uint32_t m = (uint32_t)s_src[l][lane] | (s_rev[l][pr] << 8);
+        if (s_cha[l][lane] == s_pi[l][pr]) m |= kCompactAIsI;
+        if (s_keep[l][lane] == s_pi[l][pr]) m |= kCompactKeepI;
+        cout[(size_t)(kPlanCompactHeadRows + l) * 64 + lane] = m;
     }
 }
 

@@ -577,6 +577,37 @@ def test_long_streams_at_several_tokens(P, case):
     assert ws.partials_clean(ws.exchange_bytes) and ws.error_word() == 0
 
 
+@pytest.mark.parametrize("case", [
+    dict(c_in=512, c_out=163856, ppl=64, order=0, bias=False),      # one K-slice: blocks of one wave, a ragged last block
+    dict(c_in=6144, c_out=13712, ppl=23, order=1, bias=True),       # 12 slices in one block; partial matchings, scale after
+    dict(c_in=7168, c_out=11728, ppl=64, order=0, bias=True),       # 14 slices: two blocks of 7 waves per row, partial sums exchanged
+    dict(c_in=1024, c_out=81936, ppl=64, order=0, bias=False, scale=False),   # two slices, no channel scale
+], ids=lambda c: f"{c['c_in']}to{c['c_out']}")
+def test_one_token_transform_inside_the_streaming_kernel(P, case):
+    """One token and at least 40 MiB of weight tiles: the fused call runs the streaming kernel whose waves each
+    transform their own K-slice from the compact plan (angles in 2^-24 revolutions, fp16 scales).  Every output
+    against the oracle, on block shapes the benchmark configurations do not have; nothing but the header and the
+    partial sums of a split row may be needed in the workspace."""
+    c_in, c_out = case["c_in"], case["c_out"]
+    li = pin.make_custom(7960 + c_in // 512, 1, c_in, c_out, pairs_per_layer=case["ppl"], n_outlier=2)
+    bias = pin.make_bias(7960, 3, c_out) if case["bias"] else None
+    scale = case.get("scale", True)
+    u = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale if scale else None, scale_order=case["order"])
+    y, allowed = _linear_ref(li, u, bias)
+    rot = make_rot(P, li, scale=scale, scale_order=case["order"])
+    w = make_w(P, li, bias=bias)
+    need = P.paro_workspace_bytes(rot, w, 1)
+    assert need == P.paro_workspace_exchange_bytes(rot, w, 1) == max(256, P.paro_workspace_exchange_bytes(None, w, 1))
+    ws = P.Workspace(need)
+    got = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
+    _assert_linear(got, y, allowed, f"transform inside the streaming kernel {case}")
+    assert ws.partials_clean() and ws.error_word() == 0
+    # the same call twice more on the same workspace (the exchange part must come back empty)
+    for _ in range(2):
+        again = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
+        assert np.array_equal(again.view(np.uint16), got.view(np.uint16)) or case["c_in"] > 6144
+
+
 def test_seeded_sweep_of_shapes(P):
     """48 seeded draws of (T, c_in, c_out, layers, pairs per layer, scale order, bias, plan, repack): whatever
     kernel the dispatch picks (narrow, wide with 1..n blocks per column, rotation pass, GEMM with ragged tiles,
