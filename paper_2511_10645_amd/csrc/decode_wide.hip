@@ -170,13 +170,9 @@ __global__ __launch_bounds__(MAXW * 64) void decode_wide_kernel(DecodeArgs a)
                 const uint32_t m = pm[g2][l];
                 const float rev = (float)(m >> 8) * (1.0f / 16777216.0f);      // exact: 24 bits
                 const float c = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
-                const bool ai = m & kCompactAIsI, ki = m & kCompactKeepI;
-                const float ni_a = ai ? c : -sn, ni_b = ai ? -sn : c, nj_a = ai ? sn : c, nj_b = ai ? c : sn;
-                const float m00 = ki ? ni_a : nj_a, m01 = ki ? ni_b : nj_b, m10 = ki ? nj_a : ni_a, m11 = ki ? nj_b : ni_b;
-                const float na = m00 * va[g2] + m01 * vb[g2], nb2 = m10 * va[g2] + m11 * vb[g2];
+                const float na = c * va[g2] - sn * vb[g2], nb2 = c * vb[g2] + sn * va[g2];
                 va[g2] = na;
-                vb[g2] = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute((int)((m & 63u) << 2), __float_as_int(nb2)))
-                                     : nb2;
+                vb[g2] = (l + 1 < K) ? __int_as_float(__builtin_amdgcn_ds_bpermute((int)(m & 0xffu), __float_as_int(nb2))) : nb2;
             }
         }
         // every lane has read its inputs: the staging rows take the results

@@ -39,12 +39,13 @@ __host__ __device__ inline int plan_rows(int n_layers) { return kPlanHeadRows + 
 __host__ __device__ inline size_t plan_group_dwords(int n_layers) { return (size_t)plan_rows(n_layers) * kLanes; }
 // Second part of the plan blob, behind the rows of all groups: the same plan in 4 bytes per lane and layer, for the
 // one-token linear whose waves each transform their own K-slice (every block reads the whole plan, so its size
-// counts).  Per group 3 + n_layers rows of 64 dwords: [in_a | in_b << 8 | out_a << 16 | out_b << 24],
-// [fp16 scale of in_a | fp16 scale of in_b << 16], [the same for out_a, out_b], then per layer
-// [lane to pull from | a-is-i << 6 | keep-i << 7 | angle << 8] with the angle in units of 2^-24 of a revolution
-// (the hardware sine and cosine take revolutions and are accurate to 1.3e-7 on these arguments, measured).
+// counts, and every (group, layer) is used once per wave, so nothing can be expanded ahead).  Per group 3 + n_layers
+// rows of 64 dwords: [in_a | in_b << 8 | out_a << 16 | out_b << 24], [fp16 scale of in_a | fp16 scale of in_b << 16],
+// [the same for out_a, out_b], then per layer [4 x lane to pull from | phi << 8]: keep = cos(phi) A - sin(phi) B,
+// send = cos(phi) B + sin(phi) A, phi in units of 2^-24 of a revolution (the hardware sine and cosine take
+// revolutions and are accurate to 1.3e-7 on these arguments, measured); see plan_build_kernel for how one angle
+// per lane covers the four ways a pair can sit in a lane.
 constexpr int kPlanCompactHeadRows = 3;
-constexpr uint32_t kCompactAIsI = 1u << 6, kCompactKeepI = 1u << 7;
 __host__ __device__ inline size_t plan_compact_group_dwords(int n_layers) { return (size_t)(kPlanCompactHeadRows + n_layers) * kLanes; }
 __host__ __device__ inline size_t plan_compact_offset_dwords(int n_groups, int n_layers) { return (size_t)n_groups * plan_group_dwords(n_layers); }
 __host__ __device__ inline size_t plan_total_dwords(int n_groups, int n_layers)

@@ -155,19 +155,38 @@ __global__ __launch_bounds__(64) void plan_build_kernel(const int16_t *__restric
         row[1 * 64 + lane] = __float_as_uint(s_s[l][pr]);
         row[2 * 64 + lane] = meta;
     }
-    // the compact copy (see plan_compact_group_dwords)
+    // The compact copy (see plan_compact_group_dwords).  Per lane and layer ONE angle phi and the lane to pull from:
+    //     keep = cos(phi) A - sin(phi) B,   send = cos(phi) B + sin(phi) A
+    // with no case distinction at run time.  The 2 x 2 block that maps the lane's (A, B) to (keep, send) is
+    // [k0 k1; s (-k1) s k0] with (k0, k1) one of (c, -s), (s, c), (-s, c), (c, s) and s = +1 where "A holds i" and
+    // "i is kept" agree, -1 otherwise; the formula above yields s * send, so the sent value may carry a sign that
+    // is known here: eps of the value a lane receives multiplies its k1 (which turns phi into another multiple of
+    // the pair's angle and a quarter turn), the kept value is always true, and the sign of the last layer's
+    // second output goes into its output scale.
+    __shared__ int8_t s_eps[64];
     uint32_t *cout = plan + plan_compact_offset_dwords(gridDim.x, n_layers) + (size_t)g * plan_compact_group_dwords(n_layers);
     auto h16 = [](float f) { union { _Float16 h; uint16_t u; } v; v.h = (_Float16)f; return (uint32_t)v.u; };
+    int eps_b = 1, eps_out = 1;
+    for (int l = 0; l < n_layers; ++l) {
+        const int pr = s_pair[l][lane];
+        const bool ai = s_cha[l][lane] == s_pi[l][pr], ki = s_keep[l][lane] == s_pi[l][pr];
+        const uint32_t th = s_rev[l][pr], q4 = 1u << 22;
+        uint32_t phi;
+        if (ai && ki)        phi = eps_b > 0 ? th : 0u - th;
+        else if (ai && !ki)  phi = eps_b > 0 ? th - q4 : q4 - th;
+        else if (!ai && ki)  phi = eps_b > 0 ? 0u - th - q4 : th + q4;
+        else                 phi = eps_b > 0 ? 0u - th : th;
+        cout[(size_t)(kPlanCompactHeadRows + l) * 64 + lane] = ((uint32_t)s_src[l][lane] << 2) | ((phi & 0xFFFFFFu) << 8);
+        const int eps_send = (ai == ki) ? eps_b : -eps_b;
+        __syncthreads();
+        s_eps[lane] = (int8_t)eps_send;
+        __syncthreads();
+        if (l + 1 < n_layers) eps_b = s_eps[s_src[l][lane]];
+        else eps_out = eps_send;
+    }
     cout[0 * 64 + lane] = out[0 * 64 + lane];
     cout[1 * 64 + lane] = h16(sia) | (h16(sib) << 16);
-    cout[2 * 64 + lane] = h16(soa) | (h16(sob) << 16);
-    for (int l = 0; l < n_layers; ++l) {
-        int pr = s_pair[l][lane];
-        uint32_t m = (uint32_t)s_src[l][lane] | (s_rev[l][pr] << 8);
-        if (s_cha[l][lane] == s_pi[l][pr]) m |= kCompactAIsI;
-        if (s_keep[l][lane] == s_pi[l][pr]) m |= kCompactKeepI;
-        cout[(size_t)(kPlanCompactHeadRows + l) * 64 + lane] = m;
-    }
+    cout[2 * 64 + lane] = h16(soa) | (h16(eps_out > 0 ? sob : -sob) << 16);
 }
 
 hipError_t launch_plan_build(const paro_rotation &rot, void *plan_out, hipStream_t s)
