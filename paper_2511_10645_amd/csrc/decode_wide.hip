@@ -14,14 +14,15 @@
 // tile take 64 bytes of LDS per wave, so a block can run up to 16 tiles per wave and every shape
 // of the benchmark fits one round of blocks.
 //
-// The transform cannot be hosted here at a profit.  Measured: the rotation units dealt out to the
-// first waves of the grid, results published through agent-scope stores and fetched by every
-// wave with agent-scope loads (self-flagging words, no fences) costs +5 us per launch at one
-// token and +6..8 us at 16, more than a separate rotation launch (+3.2 us): vector memory
-// returns in order for the whole compute unit, so a poll waits behind every weight tile the
-// unit has requested, and throttling the requests until the activations have arrived delays the
-// stream by the same time.  Hence: up to 4 tokens the K-major kernel (decode.hip), whose blocks
-// rotate only their own slice; 5..16 tokens a rotation pass, then this kernel.
+// The transform.  Several tokens: it cannot be hosted here at a profit.  Measured: the rotation units dealt out to
+// the first waves of the grid, results published through agent-scope stores and fetched by every wave with
+// agent-scope loads (self-flagging words, no fences) costs +5 us per launch at one token and +6..8 us at 16, more
+// than a separate rotation launch (+3 us): vector memory returns in order for the whole compute unit, so a poll
+// waits behind every weight tile the unit has requested, and throttling the requests until the activations have
+// arrived delays the stream by the same time.  Hence 2..4 tokens the K-major kernel (decode.hip), whose blocks rotate
+// only their own slice; 5..16 tokens a rotation pass, then this kernel.  One token: a wave needs the transformed
+// activations of its own K-slice only, and produces them itself (ROTK below) - used where the weight stream is long
+// enough to hide that prologue, the K-major kernel elsewhere.
 #include "decode_common.h"
 #include <algorithm>
 #include <type_traits>
