@@ -606,6 +606,13 @@ def test_one_token_transform_inside_the_streaming_kernel(P, case):
     for _ in range(2):
         again = P.paro_rotated_linear(rot, w, dev(li.x), ws).cpu().numpy()
         assert np.array_equal(again.view(np.uint16), got.view(np.uint16)) or case["c_in"] > 6144
+    # a pair table that breaks Def. 1 in one group has no defined result: every output becomes NaN on this path too
+    bad = li.pairs.copy()
+    bad[0, 3, 5, 1] = bad[0, 3, 6, 0]
+    rot_bad = P.Rotation(bad, li.theta, li.ch_scale if scale else None, scale_order=case["order"])
+    P.paro_rotation_plan_build(rot_bad)
+    nan = P.paro_rotated_linear(rot_bad, w, dev(li.x), ws).cpu().numpy()
+    assert np.isnan(nan.astype(np.float32)).all()
 
 
 def test_seeded_sweep_of_shapes(P):
