@@ -115,8 +115,11 @@ paro_status paro_select_pairs_host(const int32_t *order_host, int32_t group, int
 size_t paro_rotation_plan_bytes(const paro_rotation *rot);
 /* Builds the plan on the device: per group and layer, the lane routing, fp32 cos/sin
  * (rounded from an fp64 evaluation) and the folded channel scales used by the fast
- * rotation kernels.  plan_out: device buffer of paro_rotation_plan_bytes(), 256-byte
- * aligned.  rot->plan is ignored. */
+ * rotation kernels, followed by a compact copy (one angle in 2^-24 revolutions per lane
+ * and layer, fp16 scales) for the one-token linear whose waves each transform their own
+ * slice of the input channels (Eq. 4, 5 with the sine and cosine taken at run time).
+ * plan_out: device buffer of paro_rotation_plan_bytes(), 256-byte aligned.  rot->plan is
+ * ignored. */
 paro_status paro_rotation_plan_build(const paro_rotation *rot, void *plan_out, void *stream);
 
 /* Size in bytes of the kernel-private weight blob for `w` (0 on invalid arguments). */
