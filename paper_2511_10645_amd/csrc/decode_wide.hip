@@ -415,6 +415,19 @@ size_t decode_wide_partial_bytes(int c_in, int c_out, int T)
 // Whether the one-token kernel can host this transform (instantiated for the paper's 8 layers)
 bool decode_wide_hosts(const paro_rotation &rot, int T) { return T == 1 && rot.plan && rot.n_layers == 8; }
 
+// Whether it pays: every wave spends ~1.5 us on its 4 groups before it consumes its first tile, which its weight
+// stream hides from about 4 tiles per wave on (6 where a block has more than 8 waves, three per SIMD).  Measured on
+// MI355X, this kernel against the K-major kernel (or rotation pass + bare kernel where that is faster), us:
+// 4096 -> 12288 (3 tiles per wave) 8.7 / 8.9, 4096 -> 16384 (4) 9.7 / 10.3, 4096 -> 28672 (7) 12.8 / 14.8,
+// 2048 -> 28672 (7) 8.3 / 10.2, 14336 -> 4096 (4) 10.3 / 10.5, 14336 -> 8192 (8) 14.1 / 17.4, 8192 -> 8192 (4)
+// 11.0 / 10.9, 27648 -> 5120 (9) 15.5 / 18.9, 5120 -> 55296 (14, 10 waves) 26.1 / 28.8; but 4096 -> 6144 (2)
+// 7.5 / 6.8, 5120 -> 7168 (2) 9.1 / 7.9, 6144 -> 12288 (3, 12 waves) 11.9 / 11.5.
+bool decode_wide_hosting_pays(int c_in, int c_out)
+{
+    const WideGeometry g = wide_geometry(c_in, c_out, 1, true);
+    return g.tiles_per_block >= (g.waves <= 8 ? 4 : 6);
+}
+
 // ws: the exchange part of the workspace (may be NULL where no partial sums are exchanged).
 // rot: NULL for the bare linear; otherwise a transform decode_wide_hosts() accepts, applied to X by the kernel itself.
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,

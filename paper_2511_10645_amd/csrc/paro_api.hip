@@ -62,17 +62,12 @@ inline bool can_fuse_decode(const paro_rotation *rot, const paro_w4_weight *w, i
 // (4096 / 5120 / 14336 / 27648 input channels, 4096 .. 55296 outputs): 1 - 2 MB of partial sums
 // for one token, 0.75 MB for 2..4 tokens.  `always`: for callers without a scratch part.
 constexpr size_t kFusePartialOne = 3u << 19, kFusePartialFew = 3u << 18;
-// One token, the paper's 8 layers, a long weight stream: the kernel in which every wave transforms its own K-slice
-// (decode_wide.hip) - nothing is exchanged between blocks that the bare linear would not exchange, and the stream
-// hides the transform.  Every block repeats the rotation of its column of K-slices (~3 us of vector work and plan
-// traffic per block), which a short stream does not hide: measured against the K-major kernel on MI355X,
-// 4096 -> 28672 (59 MB of tiles) 13.3 against 14.8 us, 5120 -> 55296 26.9 against 28.8, 27648 -> 5120 (71 MB) 15.9
-// against 18.9, but 14336 -> 4096 (29 MB) 11.3 against 10.6 and 4096 -> 6144 8.6 against 6.9.
-constexpr size_t kWideHostMinBytes = 40u << 20;
+// One token, the paper's 8 layers, a weight stream of some length per wave: the kernel in which every wave transforms
+// its own K-slice (decode_wide.hip) - nothing is exchanged between blocks that the bare linear would not exchange, and
+// the stream hides the transform (decode_wide_hosting_pays has the measurements behind the rule).
 inline bool fused_wide(const paro_rotation *rot, const paro_w4_weight *w, int T)
 {
-    return can_fuse_decode(rot, w, T) && decode_wide_hosts(*rot, T) &&
-           packed_tiles_bytes(w->c_in, w->c_out) >= kWideHostMinBytes;
+    return can_fuse_decode(rot, w, T) && decode_wide_hosts(*rot, T) && decode_wide_hosting_pays(w->c_in, w->c_out);
 }
 inline bool fused_decode(const paro_rotation *rot, const paro_w4_weight *w, int T, bool always = false)
 {

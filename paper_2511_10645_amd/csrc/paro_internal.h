@@ -155,6 +155,7 @@ hipError_t launch_decode_multi(int n_parts, const paro_rotation *const *rot, con
 // ws: the exchange part of the workspace.
 size_t decode_wide_partial_bytes(int c_in, int c_out, int T);
 bool decode_wide_hosts(const paro_rotation &rot, int T);
+bool decode_wide_hosting_pays(int c_in, int c_out);
 hipError_t launch_decode_wide(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx, paro_half_t *Y, int64_t ldy,
                               int T, void *ws, hipStream_t s, const paro_rotation *rot = nullptr);
 hipError_t launch_linear_generic(const paro_w4_weight &w, const paro_half_t *X, int64_t ldx,

@@ -243,9 +243,12 @@ def test_exchange_part_covers_the_partial_sums_of_every_shape():
                 bare = L.paro_workspace_exchange_bytes(None, ctypes.byref(w), T)
                 parts = 1 if ks <= 12 else (ks + 7) // 8                              # blocks along K of the bare kernel
                 assert bare == (0 if parts == 1 else 256 + (parts * T * c_out * 4 + 255) // 256 * 256), (c_in, c_out, T, bare)
-                # one token and at least 40 MiB of weight tiles: every wave transforms its own slice inside the
-                # bare kernel's block structure, which exchanges what the bare kernel exchanges (plus the header)
-                hosted_wide = T == 1 and c_in * c_out // 2 >= 40 << 20
+                # one token and at least 4 tiles per wave of the bare kernel's blocks (6 where a block has more than 8
+                # waves): every wave transforms its own slice inside that block structure, which exchanges what the
+                # bare kernel exchanges (plus the header)
+                waves = -(-ks // parts)
+                tiles = min(16, -(-(c_out // 16) // max(1, 256 // parts)))
+                hosted_wide = T == 1 and tiles >= (4 if waves <= 8 else 6)
                 if hosted_wide:
                     assert fused and ex == max(bare, 256), (c_in, c_out, T, ex, bare)
                 elif T <= 4 and fused and ks > 1:
@@ -256,8 +259,8 @@ def test_exchange_part_covers_the_partial_sums_of_every_shape():
 
 
 def test_fused_or_two_launches_by_shape():
-    """Up to 4 tokens a decode kernel hosts the rotation (no scratch part): at one token and from 40 MiB of weight
-    tiles the kernel whose waves each transform their own K-slice, otherwise the K-major kernel unless the partial
+    """Up to 4 tokens a decode kernel hosts the rotation (no scratch part): at one token and from 4 tiles per wave
+    the kernel whose waves each transform their own K-slice, otherwise the K-major kernel unless the partial
     sums its blocks would exchange (K-slices x T x c_out x 4 bytes) exceed 1.5 MB at one token or 0.75 MB at 2..4 -
     then the rotation runs as a pass of its own, which shows as a scratch part of T * c_in * 2 bytes."""
     L = paro.lib()
@@ -269,13 +272,15 @@ def test_fused_or_two_launches_by_shape():
 
     assert scratch(4096, 6144, 1) == 0 and scratch(4096, 28672, 1) == 0 and scratch(14336, 4096, 1) == 0
     assert scratch(27648, 5120, 1) == 0                    # 54 slices x 5120 x 4 = 1.1 MB
-    assert scratch(5120, 55296, 1) == 0                    # 135 MiB of tiles: hosted by the waves of the bare kernel's blocks
+    assert scratch(5120, 55296, 1) == 0                    # 14 tiles per wave: hosted by the waves of the bare kernel's blocks
     assert scratch(5120, 16384, 1) == 0                    # 10 x 16384 x 4 = 640 KB: K-major kernel
     assert scratch(5120, 14336, 2) == 2 * 5120 * 2         # 2 tokens, 10 x 2 x 14336 x 4 = 1.1 MB: two launches
     ex = lambda c_in, c_out, T: L.paro_workspace_exchange_bytes(
         ctypes.byref(_rot(c_in=c_in, plan=FAKE)), ctypes.byref(_w(c_in=c_in, c_out=c_out, packed=FAKE)), T)
     assert ex(4096, 28672, 1) == 256 and ex(5120, 55296, 1) == 256        # nothing exchanged between blocks
     assert ex(27648, 5120, 1) == 256 + 7 * 5120 * 4                       # 54 slices in 7 blocks of 8 waves
+    assert ex(14336, 4096, 1) == 256 + 4 * 4096 * 4                       # 4 tiles per wave: hosted too (4 blocks of 7 waves per row)
+    assert ex(6144, 12288, 1) == 256 + 12 * 12288 * 4                     # 12 waves, 3 tiles per wave: K-major kernel
     assert ex(4096, 6144, 1) == 256 + 8 * 6144 * 4                        # K-major kernel: one part per slice
     assert scratch(4096, 6144, 2) == 0 and scratch(4096, 4096, 3) == 0
     assert scratch(4096, 6144, 4) == 0                     # 8 x 4 x 6144 x 4 = 768 KiB: still hosted

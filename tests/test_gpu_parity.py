@@ -579,12 +579,12 @@ def test_long_streams_at_several_tokens(P, case):
 
 @pytest.mark.parametrize("case", [
     dict(c_in=512, c_out=163856, ppl=64, order=0, bias=False),      # one K-slice: blocks of one wave, a ragged last block
-    dict(c_in=6144, c_out=13712, ppl=23, order=1, bias=True),       # 12 slices in one block; partial matchings, scale after
+    dict(c_in=6144, c_out=24592, ppl=23, order=1, bias=True),       # 12 slices in one block, 7 tiles per wave; partial matchings, scale after
     dict(c_in=7168, c_out=11728, ppl=64, order=0, bias=True),       # 14 slices: two blocks of 7 waves per row, partial sums exchanged
     dict(c_in=1024, c_out=81936, ppl=64, order=0, bias=False, scale=False),   # two slices, no channel scale
 ], ids=lambda c: f"{c['c_in']}to{c['c_out']}")
 def test_one_token_transform_inside_the_streaming_kernel(P, case):
-    """One token and at least 40 MiB of weight tiles: the fused call runs the streaming kernel whose waves each
+    """One token and at least 4 tiles per wave (6 in blocks of more than 8 waves): the fused call runs the streaming kernel whose waves each
     transform their own K-slice from the compact plan (angles in 2^-24 revolutions, fp16 scales).  Every output
     against the oracle, on block shapes the benchmark configurations do not have; nothing but the header and the
     partial sums of a split row may be needed in the workspace."""
