@@ -615,6 +615,43 @@ def test_one_token_transform_inside_the_streaming_kernel(P, case):
     assert np.isnan(nan.astype(np.float32)).all()
 
 
+@pytest.mark.parametrize("ppl,order", [(64, 0), (23, 1), (1, 0)])
+def test_compact_plan_rows_rotate_like_the_oracle(P, ppl, order):
+    """The plan's compact copy read back and run in numpy, lane by lane: per group the channel ids and fp16 scales,
+    per layer one angle (2^-24 revolutions) and the lane to pull from, `keep = cos A - sin B`, `send = cos B + sin A`
+    with no case distinction.  It must reproduce the oracle's rotation (Eq. 4, 5, 8) to the accuracy of the angle
+    grid: this pins the layout and the sign tracking of the plan builder apart from any kernel that reads it."""
+    K, G = 8, 3
+    li = pin.make_custom(7990 + ppl, 2, 128 * G, 16, pairs_per_layer=ppl)
+    rot = make_rot(P, li, scale_order=order)
+    words = rot.plan.cpu().numpy().view(np.uint32)
+    compact = words[G * (5 + 3 * K) * 64:][:G * (3 + K) * 64].reshape(G, 3 + K, 64)
+    x = li.x.astype(np.float64)
+    ref = oracle.rotate_scale(li.x, li.pairs, li.theta, li.ch_scale, scale_order=order)
+    got = np.zeros_like(ref)
+    h16 = lambda u: (u & 0xffff).astype(np.uint16).view(np.float16).astype(np.float64)
+    for g in range(G):
+        io, sci, sco = compact[g, 0], compact[g, 1], compact[g, 2]
+        in_a, in_b, out_a, out_b = io & 0xff, (io >> 8) & 0xff, (io >> 16) & 0xff, io >> 24
+        assert sorted(np.r_[in_a, in_b]) == list(range(128)) and sorted(np.r_[out_a, out_b]) == list(range(128))
+        for t in range(x.shape[0]):
+            row = x[t, g * 128:(g + 1) * 128]
+            A, B = row[in_a] * h16(sci), row[in_b] * h16(sci >> 16)
+            for l in range(K):
+                m = compact[g, 3 + l]
+                phi = 2.0 * np.pi * (m >> 8).astype(np.float64) / 2.0 ** 24
+                src = (m & 0xff) >> 2
+                keep, send = np.cos(phi) * A - np.sin(phi) * B, np.cos(phi) * B + np.sin(phi) * A
+                A, B = keep, (send[src] if l + 1 < K else send)
+            out = np.empty(128)
+            out[out_a], out[out_b] = A * h16(sco), B * h16(sco >> 16)
+            got[t, g * 128:(g + 1) * 128] = out
+    scale = np.abs(ref).max()
+    err = np.abs(got - ref).max() / scale
+    say(f"compact plan, {ppl} pairs per layer, scale order {order}: max error / max |x'| = {err:.2e}")
+    assert err < 4e-6            # 8 layers x half a step of the angle grid (1.9e-7 rad), with margin
+
+
 def test_seeded_sweep_of_shapes(P):
     """48 seeded draws of (T, c_in, c_out, layers, pairs per layer, scale order, bias, plan, repack): whatever
     kernel the dispatch picks (narrow, wide with 1..n blocks per column, rotation pass, GEMM with ragged tiles,
